@@ -1,0 +1,323 @@
+"""Pins for the CPU oracle (no GPU): every oracle function is checked against
+something other than itself -- closed forms of the carry-save array
+multiplier, dense linear algebra on tiny graphs, library routines on special
+cases, hand-evaluated sets, and invariants of the definitions."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from conftest import golden_path
+
+
+def _csr(n, batch=1, flags=oracle.DEFAULT_FLAGS):
+    aig = wl.csa_multiplier_aig(n)
+    return aig, oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch, flags)
+
+
+def _dense_from_aig(aig, self_loops=True):
+    """Binary symmetric adjacency written straight from the fanin records."""
+    n1 = aig.num_nodes
+    A = np.zeros((n1, n1))
+    for v in range(n1):
+        if self_loops:
+            A[v, v] = 1.0
+        for lit in (aig.fanin0[v], aig.fanin1[v]):
+            if lit >= 0:
+                A[v, lit >> 1] = 1.0
+                A[lit >> 1, v] = 1.0
+    return A
+
+
+# ---------------------------------------------------------------- adjacency
+@pytest.mark.parametrize("n", [6, 8, 17, 32, 64])
+def test_degree_histogram_closed_form(n):
+    """Without the self-loop: 2n POs of degree 1, 2n^2-n nodes of degree 3,
+    6n^2-11n of degree 4, n of degree 5, 2n PIs of degree n."""
+    aig, (rowptr, col, val, pol) = _csr(n)
+    deg = np.diff(rowptr) - 1
+    hist = np.bincount(deg)
+    want = {1: 2 * n, 3: 2 * n * n - n, 4: 6 * n * n - 11 * n, 5: n}
+    want[n] = want.get(n, 0) + 2 * n
+    for d in range(len(hist)):
+        assert hist[d] == want.get(d, 0), (n, d)
+    assert (deg[:2 * n] == n).all() and (deg[-2 * n:] == 1).all()
+    # unique undirected edges 2*AND + PO, stored entries 2U + N
+    U = 16 * n * n - 20 * n
+    assert rowptr[-1] == 2 * U + aig.num_nodes == 40 * n * n - 47 * n
+
+
+@pytest.mark.parametrize("n", [2, 3, 5, 16])
+def test_csr_structure(n):
+    aig, (rowptr, col, val, pol) = _csr(n)
+    n1 = aig.num_nodes
+    A = _dense_from_aig(aig)
+    rows = np.repeat(np.arange(n1), np.diff(rowptr))
+    B = np.zeros_like(A)
+    B[rows, col] = 1.0
+    assert np.array_equal(A, B)                       # same pattern, hence symmetric with self-loops
+    assert len(col) == int(A.sum())                   # no duplicate entries
+    for i in range(n1):                               # strictly ascending columns
+        c = col[rowptr[i]:rowptr[i + 1]]
+        assert (np.diff(c) > 0).all()
+    deg = np.diff(rowptr).astype(np.float32)
+    assert np.array_equal(val, (np.float32(1.0) / deg)[rows])    # correctly rounded fp32 1/deg
+    # polarity byte: bit2 self-loop; bit1 the column drives the row; bit0 inverted record
+    assert np.array_equal((pol & 4) != 0, rows == col)
+    assert np.array_equal((pol & 2) != 0, col < rows)            # drivers precede their node
+    for v in range(n1):
+        for lit in {int(aig.fanin0[v]), int(aig.fanin1[v])} - {-1}:
+            u = lit >> 1
+            p = rowptr[v] + np.searchsorted(col[rowptr[v]:rowptr[v + 1]], u)
+            q = rowptr[u] + np.searchsorted(col[rowptr[u]:rowptr[u + 1]], v)
+            assert pol[p] & 1 == lit & 1 and pol[q] & 1 == lit & 1
+    inverted_entries = int(((pol & 1) != 0).sum())
+    pairs = {(int(l) >> 1, v, int(l) & 1) for v in range(n1) for l in (aig.fanin0[v], aig.fanin1[v]) if l >= 0}
+    assert inverted_entries == 2 * sum(1 for _, _, inv in pairs if inv)
+
+
+def test_csr_flags_and_batch():
+    aig, full = _csr(4)
+    n1 = aig.num_nodes
+    # directed, no self-loops, unit weights: row v holds exactly its distinct drivers
+    rowptr, col, val, pol = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1, 0)
+    for v in range(n1):
+        want = sorted({int(l) >> 1 for l in (aig.fanin0[v], aig.fanin1[v]) if l >= 0})
+        assert list(col[rowptr[v]:rowptr[v + 1]]) == want
+    assert (val == 1.0).all()
+    # batch = block diagonal copies
+    rp3, c3, v3, p3 = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 3, oracle.DEFAULT_FLAGS)
+    rp1, c1, v1, p1 = full
+    nnz1 = rp1[-1]
+    for c in range(3):
+        assert np.array_equal(rp3[c * n1:(c + 1) * n1 + 1] - c * nnz1, rp1)
+        assert np.array_equal(c3[c * nnz1:(c + 1) * nnz1], c1 + c * n1)
+        assert np.array_equal(v3[c * nnz1:(c + 1) * nnz1], v1)
+        assert np.array_equal(p3[c * nnz1:(c + 1) * nnz1], p1)
+
+
+# --------------------------------------------------------------------- SpMM
+@pytest.mark.parametrize("n", [2, 3])
+def test_spmm_equals_dense_product(n):
+    """The only multipliers with <= 64 nodes (18 and 51): dense D^-1 (A+I) X."""
+    aig, (rowptr, col, val, pol) = _csr(n)
+    A = _dense_from_aig(aig)
+    w = (np.float32(1.0) / A.sum(axis=1).astype(np.float32)).astype(np.float64)
+    X = wl.uniform_features_numpy(11, 0, aig.num_nodes, 12)
+    want = (w[:, None] * A) @ X.astype(np.float64)
+    want_abs = (w[:, None] * A) @ np.abs(X.astype(np.float64))
+    Y, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert np.allclose(Y, want, rtol=0, atol=1e-15)
+    assert np.allclose(S, want_abs, rtol=0, atol=1e-15)
+    # unit vectors pick out columns of A_hat
+    E = np.eye(aig.num_nodes, dtype=np.float32)
+    Ycols, _ = oracle.spmm_f64(rowptr, col, val, E)
+    assert np.array_equal(Ycols, w[:, None] * A)
+    assert np.array_equal(oracle.dense_adjacency(rowptr, col, val), w[:, None] * A)
+
+
+@pytest.mark.parametrize("n,batch", [(8, 1), (32, 2)])
+def test_spmm_ones_gives_row_sums(n, batch):
+    aig, (rowptr, col, val, pol) = _csr(n, batch)
+    N = aig.num_nodes * batch
+    ones = np.ones((N, 4), dtype=np.float32)
+    Y, S = oracle.spmm_f64(rowptr, col, val, ones)
+    deg = np.diff(rowptr)
+    want = deg * (np.float32(1.0) / deg.astype(np.float32)).astype(np.float64)
+    assert np.allclose(Y, want[:, None], rtol=0, atol=1e-15) and np.array_equal(Y, S)
+    assert np.abs(Y - 1.0).max() < 2.0 ** -23
+    # without normalisation the row sum is the degree, exactly
+    rowptr, col, val, pol = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch,
+                                             oracle.SYMMETRIC | oracle.SELF_LOOPS)
+    Y, _ = oracle.spmm_f64(rowptr, col, val, ones)
+    assert np.array_equal(Y, np.repeat(deg.astype(np.float64)[:, None], 4, axis=1))
+
+
+def test_spmm_matches_scipy_on_stress_graph():
+    import scipy.sparse as sp
+
+    g = wl.stress_graph(5, 1 << 14, window=256, dmin=64, dmax=2048)
+    X = wl.uniform_features_numpy(5, 0, g.n, 8)
+    Y, S = oracle.spmm_f64(g.rowptr, g.col, g.val, X)
+    M = sp.csr_matrix((g.val.astype(np.float64), g.col, g.rowptr), shape=(g.n, g.n))
+    assert np.allclose(Y, M @ X.astype(np.float64), rtol=0, atol=1e-12)
+    assert np.allclose(S, M @ np.abs(X.astype(np.float64)), rtol=0, atol=1e-12)
+
+
+# --------------------------------------------------------------------- plan
+@pytest.mark.parametrize("n,batch,T", [(8, 1, 7), (8, 2, 9), (32, 1, 32), (32, 1, 33), (64, 1, 12)])
+def test_plan_on_multipliers(n, batch, T):
+    aig, (rowptr, col, val, pol) = _csr(n, batch)
+    N = aig.num_nodes * batch
+    pl = oracle.plan(rowptr, T)
+    deg = np.diff(rowptr)
+    # only the 2n primary inputs of each copy (row length n+1) are high-degree for 7 <= T <= n+1
+    assert len(pl["hd_rows"]) == 2 * n * batch
+    want_hd = np.concatenate([np.arange(2 * n) + c * aig.num_nodes for c in range(batch)])
+    assert np.array_equal(pl["hd_rows"], want_hd)
+    assert np.array_equal(pl["row_class"], (deg >= T).astype(np.uint8))
+    assert np.array_equal(np.sort(np.concatenate([pl["hd_rows"], pl["ld_rows"]])), np.arange(N))
+    assert (np.diff(pl["ld_rows"]) > 0).all()
+    # stable ascending-degree order == numpy's stable argsort of the LD degrees
+    ld = pl["ld_rows"]
+    assert np.array_equal(pl["ld_rows_by_degree"], ld[np.argsort(deg[ld], kind="stable")])
+    hist = np.bincount(deg[ld], minlength=T)[:T]
+    assert np.array_equal(pl["ld_deg_offsets"], np.concatenate([[0], np.cumsum(hist)]))
+
+
+def test_plan_thresholds_on_stress_graph():
+    g = wl.stress_graph(6, 1 << 15, window=256, dmin=64, dmax=1024)
+    deg = np.diff(g.rowptr)
+    prev = None
+    for T in (16, 32, 64, 128):
+        pl = oracle.plan(g.rowptr, T)
+        assert np.array_equal(pl["hd_rows"], np.nonzero(deg >= T)[0])
+        assert np.array_equal(pl["ld_rows"], np.nonzero(deg < T)[0])
+        if prev is not None:
+            assert len(pl["hd_rows"]) <= prev
+        prev = len(pl["hd_rows"])
+    with pytest.raises(ValueError):
+        oracle.plan(g.rowptr, 0)
+
+
+# ---------------------------------------------------------------- partition
+def _parse_hand_cases():
+    cases, cur = [], None
+    for line in open(golden_path("regrow_hand_cases.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "case":
+            cur = dict(name=t[1], n=int(t[2]), parts=[])
+            cases.append(cur)
+        elif t[0] == "edges":
+            cur["edges"] = [tuple(int(x) for x in e.split("-")) for e in t[1:]]
+        elif t[0] == "partof":
+            cur["partof"] = np.array([int(x) for x in t[1:]], dtype=np.int32)
+        elif t[0] == "part":
+            kv = dict(x.split("=") for x in t[2:])
+            cur["parts"].append(dict(p=int(t[1]), S=[int(x) for x in kv["S"].split(",")],
+                                     B=[int(x) for x in kv["B"].split(",")],
+                                     crossing=int(kv["crossing"]), kept=int(kv["kept"])))
+    return cases
+
+
+def _csr_from_edges(n, edges, self_loops):
+    rows = [set() for _ in range(n)]
+    for u, v in edges:
+        rows[u].add(v)
+        rows[v].add(u)
+    if self_loops:
+        for v in range(n):
+            rows[v].add(v)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    col = []
+    for v in range(n):
+        col += sorted(rows[v])
+        rowptr[v + 1] = len(col)
+    col = np.array(col, dtype=np.int32)
+    val = (np.float32(1) / np.diff(rowptr).astype(np.float32))[np.repeat(np.arange(n), np.diff(rowptr))]
+    return rowptr, col, val.astype(np.float32)
+
+
+@pytest.mark.parametrize("self_loops", [False, True])
+def test_regrow_hand_cases(self_loops):
+    for case in _parse_hand_cases():
+        rowptr, col, val = _csr_from_edges(case["n"], case["edges"], self_loops)
+        for want in case["parts"]:
+            got = oracle.regrow_part(rowptr, col, val, case["partof"], want["p"])
+            no, nh = got["n_owned"], got["n_halo"]
+            assert list(got["global_id"][:no]) == want["S"], case["name"]
+            assert list(got["global_id"][no:]) == want["B"], case["name"]
+            assert got["n_crossing"] == want["crossing"]
+            loops = (no + nh) if self_loops else 0
+            assert got["rowptr"][-1] == 2 * want["kept"] + loops
+            # without re-growth only E[S_p] survives
+            bare = oracle.regrow_part(rowptr, col, val, case["partof"], want["p"], flags=0)
+            assert bare["n_halo"] == 0 and list(bare["global_id"]) == want["S"]
+            assert bare["rowptr"][-1] == 2 * (want["kept"] - want["crossing"]) + (no if self_loops else 0)
+
+
+def _sets_bruteforce(rowptr, col, part_of, p):
+    """Eq. (1)-(2) with Python sets."""
+    n = len(rowptr) - 1
+    nbr = lambda u: {int(c) for c in col[rowptr[u]:rowptr[u + 1]] if c != u}
+    S = {v for v in range(n) if part_of[v] == p}
+    N = set().union(*[nbr(u) for u in S]) if S else set()
+    B = N - S
+    E = {(i, int(j)) for i in range(n) for j in col[rowptr[i]:rowptr[i + 1]]}
+    C = {(i, j) for (i, j) in E if (i in S and j in B) or (i in B and j in S)}
+    ES = {(i, j) for (i, j) in E if i in S and j in S}
+    halo_loops = {(u, u) for u in B if (u, u) in E}
+    return S, B, C, ES | C | halo_loops
+
+
+@pytest.mark.parametrize("n,P", [(2, 2), (3, 2), (3, 3), (4, 3), (8, 5)])
+def test_regrow_on_multipliers(n, P):
+    aig, (rowptr, col, val, pol) = _csr(n, batch=2)
+    N = 2 * aig.num_nodes
+    part_of = oracle.part_of_default(N, aig.num_nodes, P)
+    # contiguous slices of each copy, every part non-empty, non-decreasing inside a copy
+    assert set(part_of) == set(range(P))
+    assert (np.diff(part_of[:aig.num_nodes]) >= 0).all()
+    assert np.array_equal(part_of[:aig.num_nodes], part_of[aig.num_nodes:])
+    X = wl.uniform_features_numpy(2, 0, N, 8)
+    Yfull, _ = oracle.spmm_f64(rowptr, col, val, X)
+    Yback = np.full_like(Yfull, np.nan)
+    total_cross, seen = 0, np.zeros(N, dtype=int)
+    for p in range(P):
+        got = oracle.regrow_part(rowptr, col, val, part_of, p)
+        S, B, C, Eplus = _sets_bruteforce(rowptr, col, part_of, p)
+        no, gid = got["n_owned"], got["global_id"]
+        assert list(gid[:no]) == sorted(S) and list(gid[no:]) == sorted(B)
+        assert got["n_crossing"] == len(C) // 2
+        sub_rows = np.repeat(np.arange(len(gid)), np.diff(got["rowptr"]))
+        assert {(int(gid[i]), int(gid[j])) for i, j in zip(sub_rows, got["col"])} == Eplus
+        assert len(got["col"]) == len(Eplus)
+        for li in range(len(gid)):
+            c = got["col"][got["rowptr"][li]:got["rowptr"][li + 1]]
+            assert (np.diff(c) > 0).all()
+        # owned rows keep their whole neighbourhood and hence their global weight
+        for li in range(no):
+            g = gid[li]
+            assert sorted(gid[got["col"][got["rowptr"][li]:got["rowptr"][li + 1]]]) == \
+                list(col[rowptr[g]:rowptr[g + 1]])
+        deg_local = np.diff(got["rowptr"]).astype(np.float32)
+        assert np.array_equal(got["val"], (np.float32(1) / deg_local)[sub_rows])
+        seen[gid[:no]] += 1
+        total_cross += got["n_crossing"]
+        Yp, _ = oracle.spmm_f64(got["rowptr"], got["col"], got["val"], X[gid])
+        Yback[gid[:no]] = Yp[:no]
+    assert (seen == 1).all()
+    cut = sum(1 for i in range(N) for j in col[rowptr[i]:rowptr[i + 1]] if i < j and part_of[i] != part_of[j])
+    assert total_cross == 2 * cut
+    assert np.allclose(Yback, Yfull, rtol=0, atol=1e-15)
+
+
+def test_regrow_one_way_edges_and_weight_modes():
+    """Directed pattern: 0->1, 1->2, 2->0, 3->0 (+ self-loops), parts {0,1} | {2,3}."""
+    rowptr = np.array([0, 2, 4, 6, 8], dtype=np.int64)
+    col = np.array([0, 1, 1, 2, 0, 2, 0, 3], dtype=np.int32)
+    val = np.array([.5, .25, 1., 2., 3., 4., 5., 6.], dtype=np.float32)
+    part_of = np.array([0, 0, 1, 1], dtype=np.int32)
+    g0 = oracle.regrow_part(rowptr, col, val, part_of, 0, weight_mode=2)
+    # N(S_0) = {1, 2}; B_0 = {2}; node 3 points into S_0 but is not a neighbour of S_0
+    assert list(g0["global_id"]) == [0, 1, 2] and g0["n_crossing"] == 2     # {1,2} and {2,0}
+    assert list(g0["rowptr"]) == [0, 2, 4, 6]
+    assert list(g0["col"]) == [0, 1, 1, 2, 0, 2] and list(g0["val"]) == [.5, .25, 1., 2., 3., 4.]
+    g1 = oracle.regrow_part(rowptr, col, val, part_of, 1, weight_mode=0)
+    assert list(g1["global_id"]) == [2, 3, 0] and g1["n_crossing"] == 2     # {2,0} and {3,0}
+    assert list(g1["col"]) == [0, 2, 1, 2, 2] and (g1["val"] == 1).all()
+
+
+def test_sage_forward_reduces_to_spmm():
+    aig, (rowptr, col, val, pol) = _csr(4)
+    N, F = aig.num_nodes, 8
+    X = np.abs(wl.uniform_features_numpy(9, 0, N, F))
+    I, Z, z = np.eye(F, dtype=np.float32), np.zeros((F, F), dtype=np.float32), np.zeros(F, dtype=np.float32)
+    H1, H2 = oracle.sage_forward_f64(rowptr, col, val, X, I, Z, z, I, Z, z)
+    Y1, _ = oracle.spmm_f64(rowptr, col, val, X)
+    Y2, _ = oracle.spmm_f64(rowptr, col, val, Y1.astype(np.float32))
+    assert np.array_equal(H1, Y1.astype(np.float32)) and np.allclose(H2, Y2, atol=1e-15)
+    H1s, H2s = oracle.sage_forward_f64(rowptr, col, val, X, Z, I, z, Z, I, z + 1)
+    assert np.array_equal(H1s, X) and np.allclose(H2s, X.astype(np.float64) + 1)
