@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the degree-split SpMM hot path on one MI355X.
+
+One "step" = one full aggregation Y = A_hat X (LD kernel + HD kernel + split-row
+reduction) over the whole workload graph, inputs resident in HBM.  Prints ONE
+JSON line: throughput in GFLOP/s (2*nnz*F per step), the effective HBM rate,
+the roofline of the dominant (LD) kernel measured with HIP events, and the CPU
+oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# name -> (multiplier bits, batch copies, F, feature seed, degree threshold)
+WORKLOADS = {
+    "csa1024_b16_F64": (1024, 16, 64, 3, 32),    # the headline graph: 134,103,040 nodes
+    "csa1024_b1_F64": (1024, 1, 64, 2, 32),
+    "csa256_b1_F64": (256, 1, 64, 1, 32),
+    "csa32_b1_F32": (32, 1, 32, 0, 32),
+}
+
+
+def algorithmic_bytes(n, nnz, F):
+    """row pointers + column indices + weights + X read once + Y written once"""
+    return 8 * (n + 1) + 4 * nnz + 4 * nnz + 4 * n * F + 4 * n * F
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--xcd-remap", type=int, default=None)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path is single-GPU by design); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2511_18297_amd import build as groot_build
+
+    if not os.path.exists(groot_build.LIB_PATH):
+        groot_build.build()
+    import paper_2511_18297_amd as G
+    import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+    if args.xcd_remap is not None:
+        G.groot_set_tuning("xcd_remap", args.xcd_remap)
+
+    name = args.workload
+    if name is None:
+        # the headline graph needs ~76 GB of HBM; fall back to one copy on smaller parts
+        name = "csa1024_b16_F64" if props.total_memory > 100e9 else "csa1024_b1_F64"
+    bits, batch, F, seed, T = WORKLOADS[name]
+
+    t0 = time.time()
+    aig = wl.csa_multiplier_aig(bits)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    view = G.groot_graph_view(g)
+    n, nnz = view["n"], view["nnz"]
+    plan = G.groot_spmm_plan(g, T)
+    pv = G.groot_plan_view(plan)
+    n_hd, n_ld = pv["n_hd"], pv["n_ld"]
+    nnz_hd = int(np.diff(view["rowptr"])[pv["hd_rows"]].sum()) if n_hd else 0
+    G.groot_plan_upload(plan, F)
+    t_setup = time.time() - t0
+    X = wl.uniform_features(seed, 0, n, F, device="cuda")
+    Y = torch.empty_like(X)
+    torch.cuda.synchronize()
+
+    def run(phases, count):
+        for _ in range(count):
+            G.groot_spmm_execute_phases(plan, X, Y, F, phases)
+
+    # ---- whole path: W warm-up steps, then exactly K timed steps
+    run(G.GROOT_PHASE_ALL, args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(G.GROOT_PHASE_ALL, args.steps)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    flops = 2.0 * nnz * F
+    bytes_all = algorithmic_bytes(n, nnz, F)
+    gflops = flops / (ms_per_step * 1e-3) / 1e9
+    gbps = bytes_all / (ms_per_step * 1e-3) / 1e9
+
+    # ---- dominant kernel (LD) alone, HIP events on the launch stream
+    def timed_phase(phases):
+        run(phases, 2)
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        run(phases, args.steps)
+        stop.record()
+        stop.synchronize()
+        return start.elapsed_time(stop) / args.steps
+
+    ms_ld = timed_phase(G.GROOT_PHASE_LD)
+    ms_hd = timed_phase(G.GROOT_PHASE_HD | G.GROOT_PHASE_FINISH) if n_hd else 0.0
+    # LD launch: whole rowptr, the LD rows' indices and weights, X once, the LD rows of Y
+    bytes_ld = 8 * (n + 1) + 8 * (nnz - nnz_hd) + 4 * n * F + 4 * n_ld * F
+    ld_gbps = bytes_ld / (ms_ld * 1e-3) / 1e9
+
+    # ---- device copy of the same N x F matrix: the practical streaming ceiling of this machine
+    Z = torch.empty_like(X)
+    for _ in range(2):
+        Z.copy_(X)
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(5):
+        Z.copy_(X)
+    stop.record()
+    stop.synchronize()
+    copy_gbps = 2 * 4 * n * F / (start.elapsed_time(stop) / 5 * 1e-3) / 1e9
+    del Z
+
+    # ---- CPU oracle on a bounded sample: copy 0 of the batch (all of it)
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        import oracle
+
+        n1 = aig.num_nodes
+        rp, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+        X0 = X[:n1].cpu().numpy()
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        Y64, _ = oracle.spmm_f64(rp, col, val, X0, want_abs=False)
+        t_cpu = time.perf_counter() - t0
+        cpu = {"value": round(2.0 * rp[-1] * F / t_cpu / 1e9, 3), "unit": "GFLOP/s", "cores": threads,
+               "kind": "oracle", "seconds": round(t_cpu, 3),
+               "sample": f"copy 0 of {batch}: {n1} rows, {int(rp[-1])} nnz, F={F} (fp64, row-parallel OpenMP)"}
+        # the oracle result doubles as a parity check of the timed configuration
+        run(G.GROOT_PHASE_ALL, 1)
+        torch.cuda.synchronize()
+        _, S = oracle.spmm_f64(rp, col, val, X0, want_abs=True)          # untimed: error scale
+        err = np.abs(Y[:n1].cpu().numpy().astype(np.float64) - Y64)
+        parity = float(np.max(err / (1e-5 * S + 1e-6)))
+
+    out = {
+        "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak), 1024-bit CSA AIG, F=64",
+        "value": round(gflops, 2),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": name, "multiplier_bits": bits, "batch": batch, "N": n, "nnz": nnz, "F": F,
+                   "degree_threshold": T, "n_hd_rows": n_hd, "nnz_hd": nnz_hd,
+                   "xcd_remap": args.xcd_remap if args.xcd_remap is not None else 1},
+        "hbm_gbps": round(gbps, 1),
+        "hbm_pct_of_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "algorithmic_bytes_per_step": bytes_all,
+        "roofline": {"bound": "hbm", "kernel": "ld_kernel", "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld},
+        "hd_ms": round(ms_hd, 4),
+        "copy_kernel_gbps": round(copy_gbps, 1),
+        "cpu_baseline": cpu,
+        "parity_max_err_over_tol": parity,
+        "setup_seconds": round(t_setup, 2),
+        "device": props.name,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

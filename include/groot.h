@@ -1,0 +1,196 @@
+/*
+ * groot.h -- C ABI of libgroot: the degree-split sparse aggregation Y = A_hat * X
+ * of GROOT (arXiv 2511.18297) for AMD MI355X (gfx950).
+ *
+ * The library covers the GPU hot path of the paper's GNN verification flow:
+ * the EDA-graph adjacency built from an And-Inverter Graph, the split of its
+ * rows into a high-degree and a low-degree class, the two kernels that
+ * multiply the adjacency with the node-feature matrix, and the partition of a
+ * large graph into sub-graphs whose boundary edges are re-grown.
+ *
+ * Conventions
+ *   - Every call returns a groot_status and never throws or aborts; on failure
+ *     *out is left untouched and groot_last_error() describes the reason.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the current device (e.g. torch.Tensor.data_ptr()).
+ *   - Input arrays are copied; the caller keeps ownership of everything it
+ *     passes in.  Objects returned through **out are owned by the caller and
+ *     released with the matching *_free (NULL is accepted).  Pointers returned
+ *     by the *_view calls are borrowed and live as long as the viewed object.
+ *   - Node ids and columns are int32 (N < 2^31), row pointers are int64.
+ *   - No global state except a thread-local error string and the tuning table
+ *     of groot_set_tuning().
+ */
+#ifndef GROOT_H
+#define GROOT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GROOT_OK     = 0,
+    GROOT_EINVAL = 1,   /* bad argument (NULL, misaligned, out of range, not topological, ...) */
+    GROOT_ENOMEM = 2,   /* host or device allocation failed */
+    GROOT_EHIP   = 3,   /* a HIP runtime call or kernel launch failed */
+    GROOT_ERANGE = 4    /* the graph does not fit the index types (N >= 2^31) */
+} groot_status;
+
+typedef struct groot_graph groot_graph;
+typedef struct groot_plan  groot_plan;
+typedef struct groot_parts groot_parts;
+
+/* flags of groot_graph_build */
+#define GROOT_SYMMETRIC  1u   /* store both directions of every AIG edge */
+#define GROOT_SELF_LOOPS 2u   /* add (v,v) for every node */
+#define GROOT_NORM_MEAN  4u   /* weight 1/(stored row length); otherwise 1 */
+/* flags of groot_partition_regrow */
+#define GROOT_REGROW     1u   /* add boundary nodes and crossing edges (0: plain induced sub-graphs) */
+/* phases of groot_spmm_execute_phases */
+#define GROOT_PHASE_LD     1u
+#define GROOT_PHASE_HD     2u
+#define GROOT_PHASE_FINISH 4u
+#define GROOT_PHASE_ALL    7u
+
+/* ---------------------------------------------------------------------------
+ * groot_graph_build -- EDA graph of an And-Inverter Graph.
+ * Paper: Section "Converting Netlists into Transitional Graph" (AIG: two-input
+ * AND nodes, inverted edges, primary inputs/outputs) and Section "Node Features
+ * and Node Label creation" (G=(V,E), adjacency A, degree D_ii = sum_j A_ij);
+ * the weights are those of GraphSAGE mean aggregation, A_hat = D^-1 A.
+ *
+ * n1, type, fanin0, fanin1 (host): one copy of the AIG, nodes in topological
+ *   order.  type[v]: 0 = primary input, 1 = AND, 2 = primary output.  A fanin
+ *   literal is 2*source + inverted; a PI holds -1,-1; a PO holds its driver
+ *   literal in both slots.
+ * batch: number of disjoint copies laid out block-diagonally (copy c shifts
+ *   all ids by c*n1), as in the paper's batch-16 workload.
+ * flags: GROOT_SYMMETRIC | GROOT_SELF_LOOPS | GROOT_NORM_MEAN in any mix.
+ * Result: CSR with strictly ascending columns per row, duplicate edges merged,
+ *   val = 1.0f/(float)row_length (correctly rounded) or 1, and one polarity
+ *   byte per entry (bit0 the edge is inverted, bit1 the column drives the row,
+ *   bit2 self-loop).
+ * Errors: EINVAL for NULL arrays, n1 < 1, batch < 1, unknown flag bits, a bad
+ *   type, a literal that is negative / not smaller than 2*v, a PI with fanins,
+ *   a PO whose two slots differ; ERANGE if n1*batch >= 2^31; ENOMEM.
+ * ------------------------------------------------------------------------- */
+groot_status groot_graph_build(int64_t n1, const uint8_t *type, const int32_t *fanin0,
+                               const int32_t *fanin1, int32_t batch, uint32_t flags,
+                               groot_graph **out);
+
+/* A graph from caller-supplied CSR arrays (host; copied).  Columns of a row
+ * must be strictly ascending and inside [0,n).  Weights are kept as given. */
+groot_status groot_graph_from_csr(int64_t n, const int64_t *rowptr, const int32_t *col,
+                                  const float *val, groot_graph **out);
+
+/* Borrowed host pointers to the CSR; any output pointer may be NULL.  *pol is
+ * set to NULL for graphs that did not come from an AIG. */
+groot_status groot_graph_view(const groot_graph *g, int64_t *n, int64_t *nnz,
+                              const int64_t **rowptr, const int32_t **col, const float **val,
+                              const uint8_t **pol);
+void groot_graph_free(groot_graph *g);
+
+/* ---------------------------------------------------------------------------
+ * groot_spmm_plan -- degree classes and row lists.
+ * Paper: Section "Kernel Design - GROOT-GPU": rows are served by an HD kernel
+ * or an LD kernel according to their degree; the LD side computes every row's
+ * degree from the row pointer and stably sorts rows by degree (count sort).
+ * One threshold: a row is high-degree iff its stored length >= degree_threshold.
+ * Host only; the graph must outlive the plan.
+ *   row_class[i]        1 = HD, 0 = LD
+ *   hd_rows, ld_rows    ids of each class, ascending
+ *   ld_rows_by_degree   LD ids by ascending degree, ties by ascending id
+ *   ld_deg_offsets[d]   number of LD rows with degree < d, d = 0..threshold
+ * Errors: EINVAL for NULL, degree_threshold < 1; ENOMEM.
+ * ------------------------------------------------------------------------- */
+groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_threshold, groot_plan **out);
+groot_status groot_plan_view(const groot_plan *plan, int64_t *n_hd, int64_t *n_ld,
+                             const uint8_t **row_class, const int32_t **hd_rows,
+                             const int32_t **ld_rows, const int32_t **ld_rows_by_degree,
+                             const int64_t **ld_deg_offsets);
+
+/* Copies the CSR and the kernel schedule of the plan to the current HIP
+ * device (allocates device memory owned by the plan; synchronous).  Must be
+ * called once before groot_spmm_execute; max_F (multiple of 4 in [4,512]) is
+ * the widest feature matrix the plan will be executed with and sizes the
+ * scratch for split high-degree rows.  Calling it again re-uploads.
+ * Errors: EINVAL, EHIP, ENOMEM. */
+groot_status groot_plan_upload(groot_plan *plan, int32_t max_F);
+
+/* ---------------------------------------------------------------------------
+ * groot_spmm_execute -- Y = A_hat * X with the HD and LD kernels.
+ * Paper: Section "Kernel Design - GROOT-GPU" (HD kernel: the non-zeros of a
+ * high-degree row are split statically over many wavefronts and reduced; LD
+ * kernel: many short rows per wavefront, results of consecutive rows written
+ * to one contiguous area).
+ * X_dev, Y_dev (device): row-major [N,F] fp32, 16-byte aligned, not
+ *   overlapping.  F: multiple of 4, 4 <= F <= 512.  Y is overwritten entirely;
+ *   empty rows give 0.  Accumulation is fp32.
+ * hip_stream: a hipStream_t (NULL = default stream).  The call only enqueues
+ *   work and never synchronises.  At most one execute per plan may be in
+ *   flight at a time (the plan owns the scratch for split rows).
+ * Errors: EINVAL (NULL, alignment, F, plan not uploaded), EHIP (launch failed).
+ * groot_spmm_execute_phases runs a subset of the kernels (bit-or of
+ * GROOT_PHASE_*), for per-kernel timing.
+ * ------------------------------------------------------------------------- */
+groot_status groot_spmm_execute(const groot_plan *plan, const float *X_dev, float *Y_dev,
+                                int32_t F, void *hip_stream);
+groot_status groot_spmm_execute_phases(const groot_plan *plan, const float *X_dev, float *Y_dev,
+                                       int32_t F, uint32_t phases, void *hip_stream);
+void groot_plan_free(groot_plan *plan);
+
+/* ---------------------------------------------------------------------------
+ * groot_partition_regrow -- partition into sub-graphs with re-grown boundary.
+ * Paper: Section "GNN and Edge Re-growth After Partition", Eq. (1), Eq. (2)
+ * and Algorithm 1.  For every part p with node set S_p:
+ *   B_p  = (union of one-hop neighbours of S_p) \ S_p          boundary nodes
+ *   C_p  = edges with one end in S_p and the other in B_p      crossing edges
+ *   S_p+ = S_p u B_p,   E_p+ = E[S_p] u C_p
+ * E is the stored pattern of g; the neighbours of a node are the other columns
+ * of its row.  Edges between two boundary nodes are not part of E_p+; a stored
+ * self-loop of a boundary node is kept.  Local ids: S_p ascending, then B_p
+ * ascending (global_id lists them).  Sub-graph weights: 1/(local row length)
+ * for mean-normalised graphs, 1 for unit-weight graphs, the original entry's
+ * weight for graphs from groot_graph_from_csr.  Rows of S_p keep their whole
+ * neighbourhood, so one aggregation on the sub-graph reproduces the full-graph
+ * result on them; rows of B_p are computed and dropped.
+ * num_parts: P >= 1.  part_of (host, may be NULL): part of every node in
+ *   [0,P); NULL selects the built-in rule, the p-th contiguous slice of every
+ *   copy: min(P-1, floor((v mod n1) * P / n1)).
+ * flags: GROOT_REGROW, or 0 for induced sub-graphs without boundary.
+ * n_crossing counts unordered pairs {i,j}, i in S_p, j in B_p.
+ * Errors: EINVAL (NULL, P < 1, P > N, part_of out of range, unknown flags);
+ *   ENOMEM.
+ * ------------------------------------------------------------------------- */
+groot_status groot_partition_regrow(const groot_graph *g, int32_t num_parts,
+                                    const int32_t *part_of, uint32_t flags, groot_parts **out);
+groot_status groot_parts_view(const groot_parts *parts, int32_t p, int64_t *n_owned,
+                              int64_t *n_halo, int64_t *n_crossing, const int64_t **global_id,
+                              const groot_graph **sub);
+int32_t groot_parts_count(const groot_parts *parts);
+void groot_parts_free(groot_parts *parts);
+
+/* Row gather / scatter for the partitioned mode (device pointers; ids int64):
+ *   gather : out[i,:]     = X[ids[i],:]      i < n
+ *   scatter: Y[ids[i],:]  = in[i,:]          i < n   (ids distinct)
+ * F as in groot_spmm_execute.  Only enqueues on hip_stream. */
+groot_status groot_rows_gather(const int64_t *ids_dev, int64_t n, const float *X_dev,
+                               float *out_dev, int32_t F, void *hip_stream);
+groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *in_dev,
+                                float *Y_dev, int32_t F, void *hip_stream);
+
+/* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
+ * groot_plan_upload) and "hd_chunk" (largest piece of a high-degree row,
+ * 64..4096 non-zeros, read by groot_spmm_plan).  Unknown names give EINVAL.
+ * Not needed for normal use. */
+groot_status groot_set_tuning(const char *name, int64_t value);
+
+/* Thread-local description of the last failure on this thread; never NULL. */
+const char *groot_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GROOT_H */

@@ -1,0 +1,257 @@
+"""ctypes binding of libgroot.so: argument marshalling only.
+
+Function names are those of ``include/groot.h``.  Host arrays are numpy, device
+arrays are torch CUDA tensors (used for their memory and their stream, nothing
+else); every step of the path runs inside the library.  There is no fallback:
+if the shared library has not been built, importing fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgroot.so")
+
+GROOT_OK, GROOT_EINVAL, GROOT_ENOMEM, GROOT_EHIP, GROOT_ERANGE = range(5)
+GROOT_SYMMETRIC, GROOT_SELF_LOOPS, GROOT_NORM_MEAN = 1, 2, 4
+GROOT_DEFAULT_FLAGS = GROOT_SYMMETRIC | GROOT_SELF_LOOPS | GROOT_NORM_MEAN
+GROOT_REGROW = 1
+GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
+
+EXPORTS = [
+    "groot_graph_build", "groot_graph_from_csr", "groot_graph_view", "groot_graph_free",
+    "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
+    "groot_spmm_execute_phases", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
+    "groot_set_tuning", "groot_last_error",
+]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_18297_amd.build` "
+                      "(or __graft_entry__.build()); there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp = ctypes.c_void_p
+_i64, _i32, _u32 = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
+_pp = ctypes.POINTER(ctypes.c_void_p)
+_pi64 = ctypes.POINTER(ctypes.c_int64)
+
+_lib.groot_graph_build.argtypes = [_i64, _vp, _vp, _vp, _i32, _u32, _pp]
+_lib.groot_graph_from_csr.argtypes = [_i64, _vp, _vp, _vp, _pp]
+_lib.groot_graph_view.argtypes = [_vp, _pi64, _pi64, _pp, _pp, _pp, _pp]
+_lib.groot_graph_free.argtypes = [_vp]
+_lib.groot_graph_free.restype = None
+_lib.groot_spmm_plan.argtypes = [_vp, _i32, _pp]
+_lib.groot_plan_view.argtypes = [_vp, _pi64, _pi64, _pp, _pp, _pp, _pp, _pp]
+_lib.groot_plan_upload.argtypes = [_vp, _i32]
+_lib.groot_spmm_execute.argtypes = [_vp, _vp, _vp, _i32, _vp]
+_lib.groot_spmm_execute_phases.argtypes = [_vp, _vp, _vp, _i32, _u32, _vp]
+_lib.groot_plan_free.argtypes = [_vp]
+_lib.groot_plan_free.restype = None
+_lib.groot_partition_regrow.argtypes = [_vp, _i32, _vp, _u32, _pp]
+_lib.groot_parts_view.argtypes = [_vp, _i32, _pi64, _pi64, _pi64, _pp, _pp]
+_lib.groot_parts_count.argtypes = [_vp]
+_lib.groot_parts_count.restype = _i32
+_lib.groot_parts_free.argtypes = [_vp]
+_lib.groot_parts_free.restype = None
+_lib.groot_rows_gather.argtypes = [_vp, _i64, _vp, _vp, _i32, _vp]
+_lib.groot_rows_scatter.argtypes = [_vp, _i64, _vp, _vp, _i32, _vp]
+_lib.groot_set_tuning.argtypes = [ctypes.c_char_p, _i64]
+_lib.groot_last_error.argtypes = []
+_lib.groot_last_error.restype = ctypes.c_char_p
+
+
+class GrootError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"groot status {status}: {message}")
+        self.status = status
+
+
+def groot_last_error() -> str:
+    return _lib.groot_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != GROOT_OK:
+        raise GrootError(status, groot_last_error())
+
+
+def _host(a, dtype):
+    if a is None:
+        return None, None
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data
+
+
+def _view(ptr, count, dtype, owner):
+    """numpy view (no copy) of library-owned host memory; the array keeps the
+    owning Python object alive through the buffer it is built on"""
+    if not ptr or count == 0:
+        return np.empty(0, dtype=dtype)
+    buf = (ctypes.c_char * (count * np.dtype(dtype).itemsize)).from_address(ptr)
+    buf._owner = owner
+    arr = np.frombuffer(buf, dtype=dtype, count=count)
+    arr.flags.writeable = False
+    return arr
+
+
+class Graph:
+    """Owner of a groot_graph handle (or a borrowed sub-graph of a Parts object)."""
+
+    def __init__(self, handle, owner=None):
+        self.handle = handle
+        self._owner = owner          # keeps the parent alive for borrowed handles
+
+    def __del__(self):
+        if getattr(self, "handle", None) and self._owner is None:
+            _lib.groot_graph_free(self.handle)
+            self.handle = None
+
+
+class Plan:
+    def __init__(self, handle, graph: Graph):
+        self.handle = handle
+        self.graph = graph           # the plan borrows its graph
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            _lib.groot_plan_free(self.handle)
+            self.handle = None
+
+
+class Parts:
+    def __init__(self, handle, graph: Graph):
+        self.handle = handle
+        self.graph = graph
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            _lib.groot_parts_free(self.handle)
+            self.handle = None
+
+
+def groot_graph_build(type_, fanin0, fanin1, batch: int = 1, flags: int = GROOT_DEFAULT_FLAGS) -> Graph:
+    t, tp = _host(type_, np.uint8)
+    a, ap = _host(fanin0, np.int32)
+    b, bp = _host(fanin1, np.int32)
+    n1 = 0 if t is None else t.shape[0]
+    out = ctypes.c_void_p()
+    _check(_lib.groot_graph_build(n1, tp, ap, bp, batch, flags, ctypes.byref(out)))
+    return Graph(out.value)
+
+
+def groot_graph_from_csr(rowptr, col, val) -> Graph:
+    r, rp = _host(rowptr, np.int64)
+    c, cp = _host(col, np.int32)
+    v, vp = _host(val, np.float32)
+    n = 0 if r is None else r.shape[0] - 1
+    out = ctypes.c_void_p()
+    _check(_lib.groot_graph_from_csr(n, rp, cp, vp, ctypes.byref(out)))
+    return Graph(out.value)
+
+
+def groot_graph_view(g: Graph) -> dict:
+    n, nnz = _i64(0), _i64(0)
+    rp, col, val, pol = (ctypes.c_void_p() for _ in range(4))
+    _check(_lib.groot_graph_view(g.handle, ctypes.byref(n), ctypes.byref(nnz), ctypes.byref(rp),
+                                 ctypes.byref(col), ctypes.byref(val), ctypes.byref(pol)))
+    return dict(n=n.value, nnz=nnz.value,
+                rowptr=_view(rp.value, n.value + 1, np.int64, g), col=_view(col.value, nnz.value, np.int32, g),
+                val=_view(val.value, nnz.value, np.float32, g),
+                pol=_view(pol.value, nnz.value, np.uint8, g) if pol.value else None)
+
+
+def groot_spmm_plan(g: Graph, degree_threshold: int) -> Plan:
+    out = ctypes.c_void_p()
+    _check(_lib.groot_spmm_plan(g.handle, degree_threshold, ctypes.byref(out)))
+    pl = Plan(out.value, g)
+    pl.degree_threshold = degree_threshold
+    return pl
+
+
+def groot_plan_view(pl: Plan) -> dict:
+    n_hd, n_ld = _i64(0), _i64(0)
+    rc, hd, ld, by, off = (ctypes.c_void_p() for _ in range(5))
+    _check(_lib.groot_plan_view(pl.handle, ctypes.byref(n_hd), ctypes.byref(n_ld), ctypes.byref(rc),
+                                ctypes.byref(hd), ctypes.byref(ld), ctypes.byref(by), ctypes.byref(off)))
+    n = n_hd.value + n_ld.value
+    return dict(n_hd=n_hd.value, n_ld=n_ld.value, row_class=_view(rc.value, n, np.uint8, pl),
+                hd_rows=_view(hd.value, n_hd.value, np.int32, pl), ld_rows=_view(ld.value, n_ld.value, np.int32, pl),
+                ld_rows_by_degree=_view(by.value, n_ld.value, np.int32, pl),
+                ld_deg_offsets=_view(off.value, pl.degree_threshold + 1, np.int64, pl))
+
+
+def groot_plan_upload(pl: Plan, max_F: int) -> None:
+    _check(_lib.groot_plan_upload(pl.handle, max_F))
+
+
+def _dev_ptr(t, what):
+    import torch
+
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise TypeError(f"{what} must be a contiguous CUDA tensor")
+    return t.data_ptr()
+
+
+def _stream_handle(stream):
+    import torch
+
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def groot_spmm_execute(pl: Plan, X, Y, F: int = None, stream=None) -> None:
+    import torch
+
+    if X.dtype != torch.float32 or Y.dtype != torch.float32:
+        raise TypeError("X and Y must be float32")
+    F = X.shape[1] if F is None else F
+    _check(_lib.groot_spmm_execute(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, _stream_handle(stream)))
+
+
+def groot_spmm_execute_phases(pl: Plan, X, Y, F: int, phases: int, stream=None) -> None:
+    _check(_lib.groot_spmm_execute_phases(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, phases,
+                                          _stream_handle(stream)))
+
+
+def groot_partition_regrow(g: Graph, num_parts: int, part_of=None, flags: int = GROOT_REGROW) -> Parts:
+    p, pp = _host(part_of, np.int32)
+    if p is not None and p.shape[0] != groot_graph_view(g)["n"]:
+        raise ValueError("part_of must have one entry per node")
+    out = ctypes.c_void_p()
+    _check(_lib.groot_partition_regrow(g.handle, num_parts, pp, flags, ctypes.byref(out)))
+    return Parts(out.value, g)
+
+
+def groot_parts_count(parts: Parts) -> int:
+    return _lib.groot_parts_count(parts.handle)
+
+
+def groot_parts_view(parts: Parts, p: int) -> dict:
+    a, b, c = _i64(0), _i64(0), _i64(0)
+    gid, sub = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(_lib.groot_parts_view(parts.handle, p, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c),
+                                 ctypes.byref(gid), ctypes.byref(sub)))
+    return dict(n_owned=a.value, n_halo=b.value, n_crossing=c.value,
+                global_id=_view(gid.value, a.value + b.value, np.int64, parts), sub=Graph(sub.value, owner=parts))
+
+
+def groot_rows_gather(ids, X, out, F: int = None, stream=None) -> None:
+    F = X.shape[1] if F is None else F
+    _check(_lib.groot_rows_gather(_dev_ptr(ids, "ids"), ids.shape[0], _dev_ptr(X, "X"), _dev_ptr(out, "out"), F,
+                                  _stream_handle(stream)))
+
+
+def groot_rows_scatter(ids, inp, Y, F: int = None, stream=None) -> None:
+    F = Y.shape[1] if F is None else F
+    _check(_lib.groot_rows_scatter(_dev_ptr(ids, "ids"), ids.shape[0], _dev_ptr(inp, "in"), _dev_ptr(Y, "Y"), F,
+                                   _stream_handle(stream)))
+
+
+def groot_set_tuning(name: str, value: int) -> None:
+    _check(_lib.groot_set_tuning(name.encode(), value))

@@ -1,0 +1,703 @@
+// Host side of libgroot: graph construction, degree plan, partition with
+// boundary edge re-growth, argument checking and the C ABI.  No HIP headers
+// here; device work goes through the launchers in groot_kernels.hip.
+#include <algorithm>
+#include <atomic>
+#include <cstring>
+#include <functional>
+#include <limits>
+#include <memory>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+#include "groot_internal.h"
+
+namespace groot {
+
+static thread_local std::string g_error;
+
+void set_error(const std::string &msg) { g_error = msg; }
+
+groot_status fail(groot_status st, const std::string &msg)
+{
+    g_error = msg;
+    return st;
+}
+
+Tuning &tuning()
+{
+    static Tuning t;
+    return t;
+}
+
+// Static split of [0,n) over the host threads.
+static void parallel_for(int64_t n, int64_t min_per_thread,
+                         const std::function<void(int64_t, int64_t)> &body)
+{
+    unsigned hw = std::thread::hardware_concurrency();
+    int64_t nt = std::max<int64_t>(1, std::min<int64_t>(hw ? hw : 1, n / std::max<int64_t>(1, min_per_thread)));
+    nt = std::min<int64_t>(nt, 32);
+    if (nt <= 1) { body(0, n); return; }
+    std::vector<std::thread> th;
+    int64_t per = (n + nt - 1) / nt;
+    for (int64_t t = 0; t < nt; ++t) {
+        int64_t lo = t * per, hi = std::min(n, lo + per);
+        if (lo >= hi) break;
+        th.emplace_back([=, &body] { body(lo, hi); });
+    }
+    for (auto &t : th) t.join();
+}
+
+}  // namespace groot
+
+using namespace groot;
+
+// ---------------------------------------------------------------------------
+// objects
+// ---------------------------------------------------------------------------
+struct groot_graph {
+    int64_t n = 0, nnz = 0;
+    int64_t n1 = 0;                 // nodes per copy (partition rule); == n for CSR graphs
+    WeightMode weight_mode = WeightMode::Explicit;
+    std::vector<int64_t> rowptr;
+    std::vector<int32_t> col;
+    std::vector<float> val;
+    std::vector<uint8_t> pol;       // empty for graphs not built from an AIG
+};
+
+struct groot_plan {
+    const groot_graph *g = nullptr;
+    int32_t threshold = 0;
+    std::vector<uint8_t> row_class;
+    std::vector<int32_t> hd_rows, ld_rows, ld_rows_by_degree;
+    std::vector<int64_t> ld_deg_offsets;
+    // kernel schedule
+    std::vector<HdChunk> chunks;
+    std::vector<HdSplitRow> split_rows;
+    int64_t n_partials = 0;
+    int32_t max_F = 0;
+    bool resident = false;
+    DevicePlan dev;
+};
+
+struct groot_parts {
+    struct Part {
+        int64_t n_owned = 0, n_halo = 0, n_crossing = 0;
+        std::vector<int64_t> global_id;
+        groot_graph sub;
+    };
+    std::vector<Part> parts;
+};
+
+// ---------------------------------------------------------------------------
+// graph construction
+// ---------------------------------------------------------------------------
+namespace {
+
+// Adjacency of one AIG copy.  Row v is assembled as [drivers..., self,
+// fanouts in ascending id], so only the (at most two) drivers can be out of
+// order or repeated; a short insertion pass puts the row in order and merges
+// repeats.
+groot_status build_one_copy(int64_t n1, const uint8_t *type, const int32_t *f0, const int32_t *f1,
+                            uint32_t flags, std::vector<int64_t> &rowptr, std::vector<int32_t> &col,
+                            std::vector<uint8_t> &pol)
+{
+    const bool sym = flags & GROOT_SYMMETRIC, loops = flags & GROOT_SELF_LOOPS;
+    for (int64_t v = 0; v < n1; ++v) {
+        if (type[v] > 2) return fail(GROOT_EINVAL, "node " + std::to_string(v) + ": unknown type");
+        if (type[v] == 0) {
+            if (f0[v] != -1 || f1[v] != -1)
+                return fail(GROOT_EINVAL, "primary input " + std::to_string(v) + " has fanins");
+            continue;
+        }
+        for (int32_t lit : {f0[v], f1[v]})
+            if (lit < 0 || (int64_t)(lit >> 1) >= v)
+                return fail(GROOT_EINVAL, "node " + std::to_string(v) + ": fanin literal " + std::to_string(lit) +
+                                              " is negative or not before its node (AIG must be topological)");
+        if (type[v] == 2 && f0[v] != f1[v])
+            return fail(GROOT_EINVAL, "primary output " + std::to_string(v) + ": the two fanin slots differ");
+    }
+    // upper bound of each row's length, then a prefix sum gives write cursors
+    std::vector<int64_t> cursor(n1 + 1, 0);
+    for (int64_t v = 0; v < n1; ++v) {
+        if (loops) cursor[v + 1] += 1;
+        if (type[v] == 0) continue;
+        cursor[v + 1] += 2;
+        if (sym) { cursor[(f0[v] >> 1) + 1] += 1; cursor[(f1[v] >> 1) + 1] += 1; }
+    }
+    for (int64_t v = 0; v < n1; ++v) cursor[v + 1] += cursor[v];
+    std::vector<int64_t> start(cursor.begin(), cursor.end() - 1);
+    std::vector<int32_t> tcol(cursor[n1]);
+    std::vector<uint8_t> tpol(cursor[n1]);
+    std::vector<int64_t> fill(start);
+    auto put = [&](int64_t row, int32_t c, uint8_t bits) {
+        int64_t p = fill[row]++;
+        tcol[p] = c;
+        tpol[p] = bits;
+    };
+    for (int64_t v = 0; v < n1; ++v) {
+        if (type[v] != 0) {
+            put(v, f0[v] >> 1, (uint8_t)((f0[v] & 1) | 2));
+            put(v, f1[v] >> 1, (uint8_t)((f1[v] & 1) | 2));
+        }
+        if (loops) put(v, (int32_t)v, 4);
+        if (type[v] != 0 && sym) {
+            put(f0[v] >> 1, (int32_t)v, (uint8_t)(f0[v] & 1));
+            put(f1[v] >> 1, (int32_t)v, (uint8_t)(f1[v] & 1));
+        }
+    }
+    // order + merge each row in place, then compact
+    rowptr.assign(n1 + 1, 0);
+    std::vector<int64_t> len(n1);
+    parallel_for(n1, 1 << 16, [&](int64_t lo, int64_t hi) {
+        for (int64_t v = lo; v < hi; ++v) {
+            int64_t b = start[v], e = fill[v];
+            for (int64_t i = b + 1; i < e; ++i) {          // insertion sort (rows are nearly sorted)
+                int32_t c = tcol[i];
+                uint8_t q = tpol[i];
+                int64_t j = i;
+                while (j > b && tcol[j - 1] > c) { tcol[j] = tcol[j - 1]; tpol[j] = tpol[j - 1]; --j; }
+                tcol[j] = c;
+                tpol[j] = q;
+            }
+            int64_t w = b;
+            for (int64_t i = b; i < e; ++i) {
+                if (w > b && tcol[w - 1] == tcol[i]) tpol[w - 1] |= tpol[i];
+                else { tcol[w] = tcol[i]; tpol[w] = tpol[i]; ++w; }
+            }
+            len[v] = w - b;
+        }
+    });
+    for (int64_t v = 0; v < n1; ++v) rowptr[v + 1] = rowptr[v] + len[v];
+    col.resize(rowptr[n1]);
+    pol.resize(rowptr[n1]);
+    parallel_for(n1, 1 << 16, [&](int64_t lo, int64_t hi) {
+        for (int64_t v = lo; v < hi; ++v) {
+            std::memcpy(&col[rowptr[v]], &tcol[start[v]], sizeof(int32_t) * len[v]);
+            std::memcpy(&pol[rowptr[v]], &tpol[start[v]], len[v]);
+        }
+    });
+    return GROOT_OK;
+}
+
+void fill_uniform_weights(groot_graph &g)
+{
+    g.val.resize(g.nnz);
+    const bool mean = g.weight_mode == WeightMode::Mean;
+    parallel_for(g.n, 1 << 16, [&](int64_t lo, int64_t hi) {
+        for (int64_t i = lo; i < hi; ++i) {
+            int64_t b = g.rowptr[i], e = g.rowptr[i + 1];
+            float w = mean ? 1.0f / (float)(e - b) : 1.0f;
+            for (int64_t p = b; p < e; ++p) g.val[p] = w;
+        }
+    });
+}
+
+}  // namespace
+
+extern "C" groot_status groot_graph_build(int64_t n1, const uint8_t *type, const int32_t *fanin0,
+                                          const int32_t *fanin1, int32_t batch, uint32_t flags,
+                                          groot_graph **out)
+{
+    if (!type || !fanin0 || !fanin1 || !out) return fail(GROOT_EINVAL, "groot_graph_build: NULL argument");
+    if (n1 < 1 || batch < 1) return fail(GROOT_EINVAL, "groot_graph_build: n1 and batch must be >= 1");
+    if (flags & ~(GROOT_SYMMETRIC | GROOT_SELF_LOOPS | GROOT_NORM_MEAN))
+        return fail(GROOT_EINVAL, "groot_graph_build: unknown flag bits");
+    if (n1 > (int64_t)std::numeric_limits<int32_t>::max() / batch)
+        return fail(GROOT_ERANGE, "groot_graph_build: n1*batch does not fit int32 node ids");
+    try {
+        std::unique_ptr<groot_graph> g(new groot_graph);
+        std::vector<int64_t> rp1;
+        std::vector<int32_t> col1;
+        std::vector<uint8_t> pol1;
+        groot_status st = build_one_copy(n1, type, fanin0, fanin1, flags, rp1, col1, pol1);
+        if (st != GROOT_OK) return st;
+        const int64_t nnz1 = rp1[n1];
+        g->n1 = n1;
+        g->n = n1 * batch;
+        g->nnz = nnz1 * batch;
+        g->weight_mode = (flags & GROOT_NORM_MEAN) ? WeightMode::Mean : WeightMode::Ones;
+        g->rowptr.resize(g->n + 1);
+        g->col.resize(g->nnz);
+        g->pol.resize(g->nnz);
+        for (int32_t c = 0; c < batch; ++c) {
+            const int64_t row0 = (int64_t)c * n1, p0 = (int64_t)c * nnz1;
+            const int32_t shift = (int32_t)row0;
+            parallel_for(n1, 1 << 18, [&](int64_t lo, int64_t hi) {
+                for (int64_t v = lo; v < hi; ++v) g->rowptr[row0 + v] = p0 + rp1[v];
+            });
+            parallel_for(nnz1, 1 << 18, [&](int64_t lo, int64_t hi) {
+                for (int64_t p = lo; p < hi; ++p) g->col[p0 + p] = col1[p] + shift;
+                std::memcpy(&g->pol[p0 + lo], &pol1[lo], (size_t)(hi - lo));
+            });
+        }
+        g->rowptr[g->n] = g->nnz;
+        fill_uniform_weights(*g);
+        *out = g.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, "groot_graph_build: out of host memory");
+    }
+}
+
+extern "C" groot_status groot_graph_from_csr(int64_t n, const int64_t *rowptr, const int32_t *col,
+                                             const float *val, groot_graph **out)
+{
+    if (!rowptr || !out) return fail(GROOT_EINVAL, "groot_graph_from_csr: NULL argument");
+    if (n < 1) return fail(GROOT_EINVAL, "groot_graph_from_csr: n must be >= 1");
+    if (n > std::numeric_limits<int32_t>::max()) return fail(GROOT_ERANGE, "groot_graph_from_csr: n >= 2^31");
+    if (rowptr[0] != 0) return fail(GROOT_EINVAL, "groot_graph_from_csr: rowptr[0] != 0");
+    for (int64_t i = 0; i < n; ++i)
+        if (rowptr[i + 1] < rowptr[i]) return fail(GROOT_EINVAL, "groot_graph_from_csr: rowptr decreases");
+    const int64_t nnz = rowptr[n];
+    if (nnz > 0 && (!col || !val)) return fail(GROOT_EINVAL, "groot_graph_from_csr: NULL col/val");
+    std::atomic<int64_t> bad_row{-1};
+    parallel_for(n, 1 << 16, [&](int64_t lo, int64_t hi) {
+        for (int64_t i = lo; i < hi; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
+                if (col[p] < 0 || col[p] >= n || (p > rowptr[i] && col[p - 1] >= col[p])) {
+                    bad_row.store(i);
+                    return;
+                }
+    });
+    if (bad_row.load() >= 0)
+        return fail(GROOT_EINVAL, "groot_graph_from_csr: row " + std::to_string(bad_row.load()) +
+                                      " has a column out of range or not strictly ascending");
+    try {
+        std::unique_ptr<groot_graph> g(new groot_graph);
+        g->n = g->n1 = n;
+        g->nnz = nnz;
+        g->weight_mode = WeightMode::Explicit;
+        g->rowptr.assign(rowptr, rowptr + n + 1);
+        g->col.assign(col, col + nnz);
+        g->val.assign(val, val + nnz);
+        *out = g.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, "groot_graph_from_csr: out of host memory");
+    }
+}
+
+extern "C" groot_status groot_graph_view(const groot_graph *g, int64_t *n, int64_t *nnz,
+                                         const int64_t **rowptr, const int32_t **col, const float **val,
+                                         const uint8_t **pol)
+{
+    if (!g) return fail(GROOT_EINVAL, "groot_graph_view: NULL graph");
+    if (n) *n = g->n;
+    if (nnz) *nnz = g->nnz;
+    if (rowptr) *rowptr = g->rowptr.data();
+    if (col) *col = g->col.data();
+    if (val) *val = g->val.data();
+    if (pol) *pol = g->pol.empty() ? nullptr : g->pol.data();
+    return GROOT_OK;
+}
+
+extern "C" void groot_graph_free(groot_graph *g) { delete g; }
+
+// ---------------------------------------------------------------------------
+// plan
+// ---------------------------------------------------------------------------
+extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_threshold, groot_plan **out)
+{
+    if (!g || !out) return fail(GROOT_EINVAL, "groot_spmm_plan: NULL argument");
+    if (degree_threshold < 1) return fail(GROOT_EINVAL, "groot_spmm_plan: degree_threshold must be >= 1");
+    try {
+        std::unique_ptr<groot_plan> pl(new groot_plan);
+        const int64_t n = g->n;
+        const int32_t T = degree_threshold;
+        pl->g = g;
+        pl->threshold = T;
+        pl->row_class.resize(n);
+        // histogram of low degrees and class of every row
+        std::vector<int64_t> hist(T + 1, 0);
+        int64_t n_hd = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            int64_t d = g->rowptr[i + 1] - g->rowptr[i];
+            bool hd = d >= T;
+            pl->row_class[i] = hd;
+            if (hd) ++n_hd; else ++hist[d];
+        }
+        const int64_t n_ld = n - n_hd;
+        pl->hd_rows.resize(n_hd);
+        pl->ld_rows.resize(n_ld);
+        pl->ld_rows_by_degree.resize(n_ld);
+        pl->ld_deg_offsets.assign(T + 1, 0);
+        for (int32_t d = 0; d < T; ++d) pl->ld_deg_offsets[d + 1] = pl->ld_deg_offsets[d] + hist[d];
+        // counting sort: walking ids upward keeps equal degrees in id order (stable)
+        std::vector<int64_t> cursor(pl->ld_deg_offsets.begin(), pl->ld_deg_offsets.end() - 1);
+        int64_t ih = 0, il = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            if (pl->row_class[i]) { pl->hd_rows[ih++] = (int32_t)i; continue; }
+            pl->ld_rows[il++] = (int32_t)i;
+            pl->ld_rows_by_degree[cursor[g->rowptr[i + 1] - g->rowptr[i]]++] = (int32_t)i;
+        }
+        // HD schedule: balanced pieces of at most hd_chunk non-zeros
+        const int64_t chunk = std::max(64, tuning().hd_chunk);
+        int64_t slots = 0;
+        for (int64_t k = 0; k < n_hd; ++k) {
+            int32_t row = pl->hd_rows[k];
+            int64_t b = g->rowptr[row], d = g->rowptr[row + 1] - b;
+            int64_t pieces = (d + chunk - 1) / chunk;
+            if (pieces > std::numeric_limits<int32_t>::max() / 2 || slots + pieces > std::numeric_limits<int32_t>::max())
+                return fail(GROOT_ERANGE, "groot_spmm_plan: too many high-degree pieces");
+            int64_t per = (d + pieces - 1) / pieces;
+            if (pieces > 1) pl->split_rows.push_back(HdSplitRow{row, (int32_t)slots, (int32_t)pieces, 0});
+            for (int64_t c = 0; c < pieces; ++c) {
+                int64_t lo = c * per, hi = std::min(d, lo + per);
+                HdChunk ch;
+                ch.begin = b + lo;
+                ch.len = (int32_t)std::max<int64_t>(0, hi - lo);
+                ch.row = row;
+                ch.slot = pieces > 1 ? (int32_t)(slots + c) : -1;
+                ch.pad = 0;
+                pl->chunks.push_back(ch);
+            }
+            if (pieces > 1) slots += pieces;
+        }
+        pl->n_partials = slots;
+        *out = pl.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, "groot_spmm_plan: out of host memory");
+    }
+}
+
+extern "C" groot_status groot_plan_view(const groot_plan *plan, int64_t *n_hd, int64_t *n_ld,
+                                        const uint8_t **row_class, const int32_t **hd_rows,
+                                        const int32_t **ld_rows, const int32_t **ld_rows_by_degree,
+                                        const int64_t **ld_deg_offsets)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_plan_view: NULL plan");
+    if (n_hd) *n_hd = (int64_t)plan->hd_rows.size();
+    if (n_ld) *n_ld = (int64_t)plan->ld_rows.size();
+    if (row_class) *row_class = plan->row_class.data();
+    if (hd_rows) *hd_rows = plan->hd_rows.data();
+    if (ld_rows) *ld_rows = plan->ld_rows.data();
+    if (ld_rows_by_degree) *ld_rows_by_degree = plan->ld_rows_by_degree.data();
+    if (ld_deg_offsets) *ld_deg_offsets = plan->ld_deg_offsets.data();
+    return GROOT_OK;
+}
+
+namespace {
+void release_device(groot_plan *pl)
+{
+    DevicePlan &d = pl->dev;
+    dev_free(d.rowptr); dev_free(d.col); dev_free(d.val);
+    dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials);
+    d = DevicePlan{};
+    pl->resident = false;
+}
+
+template <class T>
+groot_status to_device(T **dst, const T *src, size_t count, const char *what)
+{
+    *dst = nullptr;
+    if (count == 0) return GROOT_OK;
+    void *p = nullptr;
+    int err = dev_alloc(&p, count * sizeof(T));
+    if (err) return fail(GROOT_ENOMEM, std::string("groot_plan_upload: device allocation of ") + what +
+                                           " failed: " + hip_error_text(err));
+    *dst = (T *)p;
+    if (src) {
+        err = dev_upload(p, src, count * sizeof(T));
+        if (err) return fail(GROOT_EHIP, std::string("groot_plan_upload: copy of ") + what +
+                                             " failed: " + hip_error_text(err));
+    }
+    return GROOT_OK;
+}
+}  // namespace
+
+extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_plan_upload: NULL plan");
+    if (max_F < 4 || max_F > 512 || max_F % 4) return fail(GROOT_EINVAL, "groot_plan_upload: max_F must be a multiple of 4 in [4,512]");
+    if (plan->resident) release_device(plan);
+    const groot_graph *g = plan->g;
+    DevicePlan &d = plan->dev;
+    d.n = g->n;
+    d.nnz = g->nnz;
+    d.threshold = plan->threshold;
+    d.xcd_remap = tuning().xcd_remap;
+    groot_status st;
+    if ((st = to_device(&d.rowptr, g->rowptr.data(), g->rowptr.size(), "rowptr")) != GROOT_OK ||
+        (st = to_device(&d.col, g->col.data(), g->col.size(), "col")) != GROOT_OK ||
+        (st = to_device(&d.val, g->val.data(), g->val.size(), "val")) != GROOT_OK ||
+        (st = to_device(&d.chunks, plan->chunks.data(), plan->chunks.size(), "HD schedule")) != GROOT_OK ||
+        (st = to_device(&d.split_rows, plan->split_rows.data(), plan->split_rows.size(), "HD split rows")) != GROOT_OK ||
+        (st = to_device<float>(&d.partials, nullptr, (size_t)plan->n_partials * max_F, "HD partial sums")) != GROOT_OK) {
+        std::string keep = groot_last_error();
+        release_device(plan);
+        set_error(keep);
+        return st;
+    }
+    d.n_chunks = (int64_t)plan->chunks.size();
+    d.n_split_rows = (int64_t)plan->split_rows.size();
+    d.n_partials = plan->n_partials;
+    plan->max_F = max_F;
+    plan->resident = true;
+    return GROOT_OK;
+}
+
+namespace {
+groot_status check_features(const char *who, const void *a, const void *b, int32_t F)
+{
+    if (!a || !b) return fail(GROOT_EINVAL, std::string(who) + ": NULL device pointer");
+    if (((uintptr_t)a | (uintptr_t)b) & 15) return fail(GROOT_EINVAL, std::string(who) + ": pointers must be 16-byte aligned");
+    if (F < 4 || F > 512 || F % 4) return fail(GROOT_EINVAL, std::string(who) + ": F must be a multiple of 4 in [4,512]");
+    return GROOT_OK;
+}
+}  // namespace
+
+extern "C" groot_status groot_spmm_execute_phases(const groot_plan *plan, const float *X_dev, float *Y_dev,
+                                                  int32_t F, uint32_t phases, void *hip_stream)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_spmm_execute: NULL plan");
+    groot_status st = check_features("groot_spmm_execute", X_dev, Y_dev, F);
+    if (st != GROOT_OK) return st;
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_spmm_execute: plan is not on the device (call groot_plan_upload)");
+    if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_spmm_execute: F exceeds the max_F given to groot_plan_upload");
+    if (phases & ~GROOT_PHASE_ALL) return fail(GROOT_EINVAL, "groot_spmm_execute: unknown phase bits");
+    const char *a = (const char *)X_dev, *b = (const char *)Y_dev;
+    const int64_t bytes = plan->dev.n * (int64_t)F * 4;
+    if (a < b + bytes && b < a + bytes) return fail(GROOT_EINVAL, "groot_spmm_execute: X and Y overlap");
+    int err = 0;
+    if (!err && (phases & GROOT_PHASE_LD)) err = launch_ld(plan->dev, X_dev, Y_dev, F, hip_stream);
+    if (!err && (phases & GROOT_PHASE_HD) && plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, Y_dev, F, hip_stream);
+    if (!err && (phases & GROOT_PHASE_FINISH) && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, Y_dev, F, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_spmm_execute: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_spmm_execute(const groot_plan *plan, const float *X_dev, float *Y_dev,
+                                           int32_t F, void *hip_stream)
+{
+    return groot_spmm_execute_phases(plan, X_dev, Y_dev, F, GROOT_PHASE_ALL, hip_stream);
+}
+
+extern "C" void groot_plan_free(groot_plan *plan)
+{
+    if (!plan) return;
+    if (plan->resident) release_device(plan);
+    delete plan;
+}
+
+// ---------------------------------------------------------------------------
+// partition + boundary edge re-growth
+// ---------------------------------------------------------------------------
+namespace {
+
+// Sub-graph of one part.  local_of is a scratch array of n entries, all -1 on
+// entry and on exit.
+void build_part(const groot_graph &g, const int32_t *part_of, int32_t p, bool regrow,
+                const std::vector<int32_t> &owned, std::vector<int32_t> &local_of,
+                groot_parts::Part &out)
+{
+    const int64_t n_owned = (int64_t)owned.size();
+    for (int64_t k = 0; k < n_owned; ++k) local_of[owned[k]] = (int32_t)k;
+    // boundary nodes: columns of owned rows that live in another part
+    std::vector<int32_t> halo;
+    if (regrow) {
+        for (int32_t v : owned)
+            for (int64_t q = g.rowptr[v]; q < g.rowptr[v + 1]; ++q) {
+                int32_t u = g.col[q];
+                if (part_of[u] != p && local_of[u] == -1) { local_of[u] = -2; halo.push_back(u); }
+            }
+        std::sort(halo.begin(), halo.end());
+        for (size_t k = 0; k < halo.size(); ++k) local_of[halo[k]] = (int32_t)(n_owned + (int64_t)k);
+    }
+    const int64_t n_halo = (int64_t)halo.size(), n_loc = n_owned + n_halo;
+    out.n_owned = n_owned;
+    out.n_halo = n_halo;
+    out.global_id.resize(n_loc);
+    for (int64_t k = 0; k < n_owned; ++k) out.global_id[k] = owned[k];
+    for (int64_t k = 0; k < n_halo; ++k) out.global_id[n_owned + k] = halo[k];
+
+    groot_graph &s = out.sub;
+    s.n = s.n1 = n_loc;
+    s.weight_mode = g.weight_mode;
+    s.rowptr.assign(n_loc + 1, 0);
+    // row lengths
+    int64_t crossing = 0;
+    for (int64_t k = 0; k < n_owned; ++k) {
+        int32_t v = owned[k];
+        int64_t len = 0;
+        for (int64_t q = g.rowptr[v]; q < g.rowptr[v + 1]; ++q) {
+            int32_t lu = local_of[g.col[q]];
+            if (lu >= 0) { ++len; if (lu >= n_owned) ++crossing; }
+        }
+        s.rowptr[k + 1] = len;
+    }
+    for (int64_t k = 0; k < n_halo; ++k) {
+        int32_t u = halo[k];
+        int64_t len = 0;
+        for (int64_t q = g.rowptr[u]; q < g.rowptr[u + 1]; ++q) {
+            int32_t v = g.col[q];
+            if (v == u) { ++len; continue; }
+            int32_t lv = local_of[v];
+            if (lv >= 0 && lv < n_owned) {
+                ++len;
+                // an edge stored only in this direction is a crossing pair not yet counted
+                const int32_t *b = &g.col[g.rowptr[v]], *e = &g.col[g.rowptr[v + 1]];
+                if (!std::binary_search(b, e, u)) ++crossing;
+            }
+        }
+        s.rowptr[n_owned + k + 1] = len;
+    }
+    for (int64_t k = 0; k < n_loc; ++k) s.rowptr[k + 1] += s.rowptr[k];
+    s.nnz = s.rowptr[n_loc];
+    s.col.resize(s.nnz);
+    s.val.resize(s.nnz);
+    out.n_crossing = crossing;
+    const bool explicit_w = g.weight_mode == WeightMode::Explicit;
+    // Local ids are monotone in the global id inside the owned block and inside
+    // the boundary block, so a row sorted by global column becomes sorted by
+    // local column by writing its owned columns first and its boundary columns after.
+    for (int64_t k = 0; k < n_loc; ++k) {
+        int32_t v = (int32_t)out.global_id[k];
+        const bool row_owned = k < n_owned;
+        int64_t w = s.rowptr[k];
+        for (int pass = 0; pass < 2; ++pass)
+            for (int64_t q = g.rowptr[v]; q < g.rowptr[v + 1]; ++q) {
+                int32_t c = g.col[q], lc = local_of[c];
+                if (lc < 0) continue;
+                bool col_owned = lc < n_owned;
+                if (col_owned != (pass == 0)) continue;
+                if (!row_owned && !col_owned && c != v) continue;   // boundary-boundary edge: not in E_p+
+                s.col[w] = lc;
+                if (explicit_w) s.val[w] = g.val[q];
+                ++w;
+            }
+    }
+    if (!explicit_w) fill_uniform_weights(s);
+    for (int32_t v : owned) local_of[v] = -1;
+    for (int32_t u : halo) local_of[u] = -1;
+}
+
+}  // namespace
+
+extern "C" groot_status groot_partition_regrow(const groot_graph *g, int32_t num_parts,
+                                               const int32_t *part_of, uint32_t flags, groot_parts **out)
+{
+    if (!g || !out) return fail(GROOT_EINVAL, "groot_partition_regrow: NULL argument");
+    if (num_parts < 1 || num_parts > g->n) return fail(GROOT_EINVAL, "groot_partition_regrow: num_parts must be in [1,N]");
+    if (flags & ~GROOT_REGROW) return fail(GROOT_EINVAL, "groot_partition_regrow: unknown flag bits");
+    try {
+        const int64_t n = g->n;
+        const int32_t P = num_parts;
+        std::vector<int32_t> rule;
+        if (!part_of) {
+            rule.resize(n);
+            const int64_t n1 = g->n1;
+            parallel_for(n, 1 << 18, [&](int64_t lo, int64_t hi) {
+                for (int64_t v = lo; v < hi; ++v) {
+                    int64_t q = ((v % n1) * P) / n1;
+                    rule[v] = (int32_t)std::min<int64_t>(q, P - 1);
+                }
+            });
+            part_of = rule.data();
+        } else {
+            for (int64_t v = 0; v < n; ++v)
+                if (part_of[v] < 0 || part_of[v] >= P)
+                    return fail(GROOT_EINVAL, "groot_partition_regrow: part_of[" + std::to_string(v) + "] outside [0,P)");
+        }
+        // owned lists by counting
+        std::vector<int64_t> count(P + 1, 0);
+        for (int64_t v = 0; v < n; ++v) ++count[part_of[v] + 1];
+        std::vector<std::vector<int32_t>> owned(P);
+        for (int32_t p = 0; p < P; ++p) owned[p].reserve(count[p + 1]);
+        for (int64_t v = 0; v < n; ++v) owned[part_of[v]].push_back((int32_t)v);
+
+        std::unique_ptr<groot_parts> res(new groot_parts);
+        res->parts.resize(P);
+        // parts are independent: a few worker threads, each with its own scratch map
+        unsigned hw = std::thread::hardware_concurrency();
+        int workers = (int)std::max(1u, std::min<unsigned>({hw ? hw : 1u, (unsigned)P, 8u}));
+        if (n < (1 << 20)) workers = 1;
+        std::atomic<int32_t> next{0};
+        std::atomic<bool> oom{false};
+        auto work = [&] {
+            try {
+                std::vector<int32_t> local_of(n, -1);
+                for (int32_t p = next++; p < P; p = next++)
+                    build_part(*g, part_of, p, flags & GROOT_REGROW, owned[p], local_of, res->parts[p]);
+            } catch (const std::bad_alloc &) {
+                oom = true;
+            }
+        };
+        if (workers == 1) work();
+        else {
+            std::vector<std::thread> th;
+            for (int t = 0; t < workers; ++t) th.emplace_back(work);
+            for (auto &t : th) t.join();
+        }
+        if (oom) return fail(GROOT_ENOMEM, "groot_partition_regrow: out of host memory");
+        *out = res.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, "groot_partition_regrow: out of host memory");
+    }
+}
+
+extern "C" int32_t groot_parts_count(const groot_parts *parts) { return parts ? (int32_t)parts->parts.size() : 0; }
+
+extern "C" groot_status groot_parts_view(const groot_parts *parts, int32_t p, int64_t *n_owned, int64_t *n_halo,
+                                         int64_t *n_crossing, const int64_t **global_id, const groot_graph **sub)
+{
+    if (!parts) return fail(GROOT_EINVAL, "groot_parts_view: NULL parts");
+    if (p < 0 || p >= (int32_t)parts->parts.size()) return fail(GROOT_EINVAL, "groot_parts_view: part index out of range");
+    const groot_parts::Part &pt = parts->parts[p];
+    if (n_owned) *n_owned = pt.n_owned;
+    if (n_halo) *n_halo = pt.n_halo;
+    if (n_crossing) *n_crossing = pt.n_crossing;
+    if (global_id) *global_id = pt.global_id.data();
+    if (sub) *sub = &pt.sub;
+    return GROOT_OK;
+}
+
+extern "C" void groot_parts_free(groot_parts *parts) { delete parts; }
+
+// ---------------------------------------------------------------------------
+// row gather / scatter, tuning, errors
+// ---------------------------------------------------------------------------
+extern "C" groot_status groot_rows_gather(const int64_t *ids_dev, int64_t n, const float *X_dev, float *out_dev,
+                                          int32_t F, void *hip_stream)
+{
+    if (n < 0) return fail(GROOT_EINVAL, "groot_rows_gather: negative n");
+    if (n == 0) return GROOT_OK;
+    if (!ids_dev) return fail(GROOT_EINVAL, "groot_rows_gather: NULL ids");
+    groot_status st = check_features("groot_rows_gather", X_dev, out_dev, F);
+    if (st != GROOT_OK) return st;
+    int err = launch_rows_gather(ids_dev, n, X_dev, out_dev, F, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_rows_gather: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *in_dev, float *Y_dev,
+                                           int32_t F, void *hip_stream)
+{
+    if (n < 0) return fail(GROOT_EINVAL, "groot_rows_scatter: negative n");
+    if (n == 0) return GROOT_OK;
+    if (!ids_dev) return fail(GROOT_EINVAL, "groot_rows_scatter: NULL ids");
+    groot_status st = check_features("groot_rows_scatter", in_dev, Y_dev, F);
+    if (st != GROOT_OK) return st;
+    int err = launch_rows_scatter(ids_dev, n, in_dev, Y_dev, F, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_rows_scatter: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
+{
+    if (!name) return fail(GROOT_EINVAL, "groot_set_tuning: NULL name");
+    std::string k(name);
+    if (k == "xcd_remap") { tuning().xcd_remap = value ? 1 : 0; return GROOT_OK; }
+    if (k == "hd_chunk") {
+        if (value < 64 || value > 4096) return fail(GROOT_EINVAL, "groot_set_tuning: hd_chunk must be in [64,4096]");
+        tuning().hd_chunk = (int)value;
+        return GROOT_OK;
+    }
+    return fail(GROOT_EINVAL, "groot_set_tuning: unknown knob '" + k + "'");
+}
+
+extern "C" const char *groot_last_error(void) { return g_error.c_str(); }

@@ -1,0 +1,73 @@
+// Internal declarations shared by the host side and the HIP kernels of libgroot.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "groot.h"
+
+namespace groot {
+
+enum class WeightMode : int { Ones = 0, Mean = 1, Explicit = 2 };
+
+void set_error(const std::string &msg);
+groot_status fail(groot_status st, const std::string &msg);
+
+// One piece of a high-degree row: nnz range [begin, begin+len) of row `row`.
+// slot >= 0: the partial sum goes to partials[slot]; slot < 0: the row has a
+// single piece and its sum goes straight to Y.
+struct HdChunk {
+    int64_t begin;
+    int32_t len;
+    int32_t row;
+    int32_t slot;
+    int32_t pad;
+};
+
+// A high-degree row that was split: Y[row] = sum of partials[first .. first+count)
+struct HdSplitRow {
+    int32_t row;
+    int32_t first;
+    int32_t count;
+    int32_t pad;
+};
+
+struct Tuning {
+    int xcd_remap = 1;
+    int hd_chunk = 512;
+};
+Tuning &tuning();
+
+// Device-resident part of a plan.
+struct DevicePlan {
+    int64_t n = 0, nnz = 0;
+    int32_t threshold = 0;
+    int64_t *rowptr = nullptr;
+    int32_t *col = nullptr;
+    float *val = nullptr;
+    HdChunk *chunks = nullptr;
+    int64_t n_chunks = 0;
+    HdSplitRow *split_rows = nullptr;
+    int64_t n_split_rows = 0;
+    float *partials = nullptr;      // [n_partials, partial_stride]
+    int64_t n_partials = 0;
+    int64_t partial_stride = 512;   // floats per slot (max F)
+    int xcd_remap = 1;
+    int hd_chunk = 512;
+};
+
+// Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).
+int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
+int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
+int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream);
+int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
+int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
+const char *hip_error_text(int err);
+
+// Device memory helpers (groot_kernels.hip, so that the host file needs no HIP headers).
+int dev_alloc(void **p, size_t bytes);
+void dev_free(void *p);
+int dev_upload(void *dst, const void *src, size_t bytes);
+
+}  // namespace groot

@@ -1,0 +1,313 @@
+// HIP kernels of libgroot for gfx950 (wave64): the low-degree and high-degree
+// aggregation kernels, the reduction of split high-degree rows, and the row
+// gather / scatter of the partitioned mode.
+//
+// Feature rows are handled as float4 slices: a row of F floats is covered by
+// a "lane group" of L lanes (L = smallest power of two >= F/4, at most 64), so
+// one wavefront works on 64/L rows at a time and every load/store of a group
+// is one contiguous F*4-byte segment.
+#include <hip/hip_runtime.h>
+
+#include "groot_internal.h"
+
+namespace groot {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;                  // threads per workgroup (4 wavefronts)
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kLdTileRows = 64;              // consecutive rows per wavefront tile
+constexpr int kLdTileCap = 512;              // non-zeros of a tile that are staged in LDS
+constexpr int kXcds = 8;                     // workgroups are dealt round-robin over 8 XCDs
+
+// Each XCD has its own L2.  Consecutive hardware workgroup ids land on
+// different XCDs, so the logical block index is transposed: XCD x walks the
+// x-th contiguous eighth of the blocks in ascending order.
+__device__ __forceinline__ int64_t logical_block(int64_t blocks_per_xcd, int remap)
+{
+    int64_t b = blockIdx.x;
+    return remap ? (b % kXcds) * blocks_per_xcd + b / kXcds : b;
+}
+
+// ---------------------------------------------------------------------------
+// LD kernel.  A wavefront owns 64 consecutive rows.  When none of them is
+// high-degree and the tile's non-zeros fit, the wavefront first copies the
+// tile's column indices and weights to LDS with fully coalesced loads; lane
+// groups then walk their rows (group g takes rows g, g+G, g+2G, ...), gather
+// the feature slices of all neighbours of a row before accumulating them in
+// registers, and store the finished slice.  The G groups of a wavefront always
+// store G consecutive rows, i.e. one contiguous G*F*4-byte area per store.
+// High-degree rows are skipped (the HD kernel writes them).
+// ---------------------------------------------------------------------------
+template <int L, bool kStaged>
+__device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *__restrict__ cols,
+                                          const float *__restrict__ vals, const v4f *__restrict__ X,
+                                          int32_t F4, int32_t ff)
+{
+    v4f acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t p = s; p < e; p += 8) {
+        v4f x[8];
+        float w[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            if (p + k < e) {
+                int32_t c = kStaged ? cols[p + k] : __builtin_nontemporal_load(&cols[p + k]);
+                w[k] = kStaged ? vals[p + k] : __builtin_nontemporal_load(&vals[p + k]);
+                x[k] = X[(int64_t)c * F4 + ff];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (p + k < e) acc += w[k] * x[k];
+    }
+    return acc;
+}
+
+template <int L>
+__global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ rowptr,
+                                                    const int32_t *__restrict__ col,
+                                                    const float *__restrict__ val,
+                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
+                                                    int64_t n, int32_t F4, int32_t T,
+                                                    int64_t blocks_per_xcd, int remap)
+{
+    __shared__ int32_t s_col[kWavesPerBlock][kLdTileCap];
+    __shared__ float s_val[kWavesPerBlock][kLdTileCap];
+    __shared__ int32_t s_rel[kWavesPerBlock][kLdTileRows + 1];
+
+    constexpr int G = kWave / L;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int64_t blk = logical_block(blocks_per_xcd, remap);
+    const int64_t base = (blk * kWavesPerBlock + wave) * kLdTileRows;   // may lie beyond n: empty tile
+
+    const int64_t r = base + lane;
+    int64_t rp0 = 0, rp1 = 0;
+    if (r < n) { rp0 = rowptr[r]; rp1 = rowptr[r + 1]; }
+    const int64_t tile_begin = rowptr[base < n ? base : n];
+    const int64_t tile_end = rowptr[base + kLdTileRows < n ? base + kLdTileRows : n];
+    const bool any_hd = __ballot(rp1 - rp0 >= T) != 0;
+    const bool staged = !any_hd && (tile_end - tile_begin) <= kLdTileCap;
+
+    if (staged) {
+        const int m = (int)(tile_end - tile_begin);
+        s_rel[wave][lane] = (r < n) ? (int32_t)(rp0 - tile_begin) : m;
+        if (lane == 0) s_rel[wave][kLdTileRows] = m;
+        for (int p = lane; p < m; p += kWave) {
+            s_col[wave][p] = __builtin_nontemporal_load(&col[tile_begin + p]);
+            s_val[wave][p] = __builtin_nontemporal_load(&val[tile_begin + p]);
+        }
+    }
+    __syncthreads();
+
+    const int g = lane / L, f = lane % L;
+    for (int it = 0; it < kLdTileRows / G; ++it) {
+        const int lr = it * G + g;
+        const int64_t row = base + lr;
+        if (row >= n) break;
+        if (staged) {
+            const int64_t s = s_rel[wave][lr], e = s_rel[wave][lr + 1];
+            for (int32_t ff = f; ff < F4; ff += L) {
+                v4f acc = ld_row_sum<L, true>(s, e, s_col[wave], s_val[wave], X, F4, ff);
+                __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
+            }
+        } else {
+            const int64_t s = rowptr[row], e = rowptr[row + 1];
+            if (e - s >= T) continue;
+            for (int32_t ff = f; ff < F4; ff += L) {
+                v4f acc = ld_row_sum<L, false>(s, e, col, val, X, F4, ff);
+                __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// HD kernel.  One workgroup per piece of a high-degree row (the plan cuts a
+// row into balanced pieces).  The 256/L lane groups of the workgroup stride
+// over the piece's non-zeros, each keeping a register accumulator for its
+// float4 slice; the group sums meet in LDS and are added by a tree.  The
+// result goes to Y (single-piece rows) or to the row's slot of partial sums.
+// ---------------------------------------------------------------------------
+template <int L>
+__global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ chunks,
+                                                    const int32_t *__restrict__ col,
+                                                    const float *__restrict__ val,
+                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
+                                                    v4f *__restrict__ partials, int32_t F4)
+{
+    constexpr int G = kBlock / L;
+    __shared__ v4f s_red[G][L];
+    const HdChunk ch = chunks[blockIdx.x];
+    const int g = threadIdx.x / L, f = threadIdx.x % L;
+    const int64_t end = ch.begin + ch.len;
+
+    for (int32_t fb = 0; fb < F4; fb += L) {
+        const int32_t ff = fb + f;
+        const bool live = ff < F4;
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        if (live) {
+            int64_t p = ch.begin + g;
+            for (; p + 3 * G < end; p += 4 * G) {
+                int32_t c0 = col[p], c1 = col[p + G], c2 = col[p + 2 * G], c3 = col[p + 3 * G];
+                float w0 = val[p], w1 = val[p + G], w2 = val[p + 2 * G], w3 = val[p + 3 * G];
+                v4f x0 = X[(int64_t)c0 * F4 + ff], x1 = X[(int64_t)c1 * F4 + ff];
+                v4f x2 = X[(int64_t)c2 * F4 + ff], x3 = X[(int64_t)c3 * F4 + ff];
+                acc += w0 * x0;
+                acc += w1 * x1;
+                acc += w2 * x2;
+                acc += w3 * x3;
+            }
+            for (; p < end; p += G) acc += val[p] * X[(int64_t)col[p] * F4 + ff];
+        }
+        s_red[g][f] = acc;
+        __syncthreads();
+#pragma unroll
+        for (int stride = G / 2; stride > 0; stride /= 2) {
+            if (g < stride) s_red[g][f] += s_red[g + stride][f];
+            __syncthreads();
+        }
+        if (g == 0 && live) {
+            v4f sum = s_red[0][f];
+            if (ch.slot < 0) Y[(int64_t)ch.row * F4 + ff] = sum;
+            else partials[(int64_t)ch.slot * F4 + ff] = sum;
+        }
+        __syncthreads();
+    }
+}
+
+// Y[row] = partials[first] + ... + partials[first+count-1], in that order.
+template <int L>
+__global__ __launch_bounds__(kBlock) void hd_finish_kernel(const HdSplitRow *__restrict__ rows,
+                                                           int64_t n_rows,
+                                                           const v4f *__restrict__ partials,
+                                                           v4f *__restrict__ Y, int32_t F4)
+{
+    constexpr int G = kBlock / L;
+    const int64_t k = (int64_t)blockIdx.x * G + threadIdx.x / L;
+    if (k >= n_rows) return;
+    const HdSplitRow sr = rows[k];
+    for (int32_t ff = threadIdx.x % L; ff < F4; ff += L) {
+        v4f acc = {0.f, 0.f, 0.f, 0.f};
+        for (int32_t c = 0; c < sr.count; ++c) acc += partials[(int64_t)(sr.first + c) * F4 + ff];
+        Y[(int64_t)sr.row * F4 + ff] = acc;
+    }
+}
+
+// out[i] = X[ids[i]]  (kScatter = false)   or   Y[ids[i]] = in[i]  (kScatter = true)
+template <int L, bool kScatter>
+__global__ __launch_bounds__(kBlock) void rows_move_kernel(const int64_t *__restrict__ ids, int64_t n,
+                                                           const v4f *__restrict__ src,
+                                                           v4f *__restrict__ dst, int32_t F4)
+{
+    constexpr int G = kBlock / L;
+    const int64_t i = (int64_t)blockIdx.x * G + threadIdx.x / L;
+    if (i >= n) return;
+    const int64_t id = ids[i];
+    for (int32_t ff = threadIdx.x % L; ff < F4; ff += L) {
+        if (kScatter) dst[id * F4 + ff] = src[i * F4 + ff];
+        else dst[i * F4 + ff] = src[id * F4 + ff];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------
+static int lanes_for(int32_t F4)
+{
+    int L = 1;
+    while (L < F4 && L < kWave) L *= 2;
+    return L;
+}
+
+#define GROOT_DISPATCH_L(L, CALL)        \
+    switch (L) {                         \
+    case 1: { constexpr int kL = 1; CALL; } break;   \
+    case 2: { constexpr int kL = 2; CALL; } break;   \
+    case 4: { constexpr int kL = 4; CALL; } break;   \
+    case 8: { constexpr int kL = 8; CALL; } break;   \
+    case 16: { constexpr int kL = 16; CALL; } break; \
+    case 32: { constexpr int kL = 32; CALL; } break; \
+    default: { constexpr int kL = 64; CALL; } break; \
+    }
+
+static bool grid_ok(int64_t blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
+
+int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
+{
+    const int32_t F4 = F / 4;
+    const int64_t rows_per_block = (int64_t)kWavesPerBlock * kLdTileRows;
+    const int64_t n_blocks = (dp.n + rows_per_block - 1) / rows_per_block;
+    const int64_t per_xcd = (n_blocks + kXcds - 1) / kXcds;
+    const int remap = dp.xcd_remap && n_blocks >= 4 * kXcds;
+    const int64_t grid = remap ? per_xcd * kXcds : n_blocks;
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    GROOT_DISPATCH_L(lanes_for(F4),
+                     (ld_kernel<kL><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                         dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)Y, dp.n, F4, dp.threshold, per_xcd, remap)));
+    return (int)hipGetLastError();
+}
+
+int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
+{
+    const int32_t F4 = F / 4;
+    if (!grid_ok(dp.n_chunks)) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    GROOT_DISPATCH_L(lanes_for(F4),
+                     (hd_kernel<kL><<<dim3((unsigned)dp.n_chunks), dim3(kBlock), 0, st>>>(
+                         dp.chunks, dp.col, dp.val, (const v4f *)X, (v4f *)Y, (v4f *)dp.partials, F4)));
+    return (int)hipGetLastError();
+}
+
+int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream)
+{
+    const int32_t F4 = F / 4;
+    const int L = lanes_for(F4);
+    const int64_t grid = (dp.n_split_rows + kBlock / L - 1) / (kBlock / L);
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    GROOT_DISPATCH_L(L, (hd_finish_kernel<kL><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                            dp.split_rows, dp.n_split_rows, (const v4f *)dp.partials, (v4f *)Y, F4)));
+    return (int)hipGetLastError();
+}
+
+int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream)
+{
+    const int32_t F4 = F / 4;
+    const int L = lanes_for(F4);
+    const int64_t grid = (n + kBlock / L - 1) / (kBlock / L);
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    GROOT_DISPATCH_L(L, (rows_move_kernel<kL, false><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                            ids, n, (const v4f *)X, (v4f *)out, F4)));
+    return (int)hipGetLastError();
+}
+
+int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream)
+{
+    const int32_t F4 = F / 4;
+    const int L = lanes_for(F4);
+    const int64_t grid = (n + kBlock / L - 1) / (kBlock / L);
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    hipStream_t st = (hipStream_t)stream;
+    GROOT_DISPATCH_L(L, (rows_move_kernel<kL, true><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                            ids, n, (const v4f *)in, (v4f *)Y, F4)));
+    return (int)hipGetLastError();
+}
+
+const char *hip_error_text(int err) { return hipGetErrorString((hipError_t)err); }
+
+int dev_alloc(void **p, size_t bytes) { return (int)hipMalloc(p, bytes); }
+
+void dev_free(void *p)
+{
+    if (p) (void)hipFree(p);
+}
+
+int dev_upload(void *dst, const void *src, size_t bytes)
+{
+    return (int)hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice);
+}
+
+}  // namespace groot

@@ -1,0 +1,237 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element on the same seeded inputs.  Tolerance per element, as stated for
+this build: |y_gpu - y_fp64| <= 1e-5 * sum_j |a_ij x_jk| + 1e-6 (fp32
+accumulation against an fp64 reference)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import assert_close_to_oracle, ensure_built
+
+pytestmark = pytest.mark.gpu
+
+ensure_built()
+import paper_2511_18297_amd as G  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    torch.cuda.set_device(0)
+    return torch
+
+
+def _run(torch, g, T, X_np, guard_rows=3, phases=None):
+    """execute with canary rows around Y; returns Y as numpy"""
+    n = G.groot_graph_view(g)["n"]
+    F = X_np.shape[1]
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F)
+    X = torch.from_numpy(X_np).cuda()
+    buf = torch.full((n + 2 * guard_rows, F), float("nan"), dtype=torch.float32, device="cuda")
+    buf[:guard_rows] = 12345.0
+    buf[n + guard_rows:] = 12345.0
+    Y = buf[guard_rows:n + guard_rows]
+    G.groot_spmm_execute(plan, X, Y, F)
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert (out[:guard_rows] == 12345.0).all() and (out[n + guard_rows:] == 12345.0).all(), "wrote outside Y"
+    return out[guard_rows:n + guard_rows], plan, X, Y
+
+
+def _aig_case(n, batch, flags=G.GROOT_DEFAULT_FLAGS):
+    aig = wl.csa_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch, flags)
+    o = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch, flags)
+    return aig, g, o
+
+
+def test_config1_32bit_structural_features(torch_cuda):
+    """32-bit multiplier, F = 32, node-type / polarity columns + U(-1,1), T = 32."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(32, 1)
+    X = wl.aig_node_features(aig, 0, 32)
+    Y, plan, _, _ = _run(torch_cuda, g, 32, X)
+    assert G.groot_plan_view(plan)["n_hd"] == 64
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, "config 1")
+
+
+def test_config2_256bit(torch_cuda):
+    """256-bit multiplier (522,496 nodes), F = 64, seed 1, T = 32."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(256, 1)
+    X = wl.uniform_features_numpy(1, 0, aig.num_nodes, 64)
+    Y, plan, Xd, Yd = _run(torch_cuda, g, 32, X)
+    assert G.groot_plan_view(plan)["n_hd"] == 512
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, "config 2")
+    # no atomics anywhere: a second run is bitwise identical
+    Yd.fill_(float("nan"))
+    G.groot_spmm_execute(plan, Xd, Yd, 64)
+    torch_cuda.cuda.synchronize()
+    assert np.array_equal(Yd.cpu().numpy(), Y)
+
+
+@pytest.mark.parametrize("F", [4, 8, 12, 20, 36, 64, 100, 128, 132, 256, 260, 512])
+def test_feature_widths(torch_cuda, F):
+    aig, g, (rowptr, col, val, pol) = _aig_case(24, 2)
+    X = wl.uniform_features_numpy(10 + F, 0, 2 * aig.num_nodes, F)
+    Y, _, _, _ = _run(torch_cuda, g, 8, X)
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, f"F={F}")
+
+
+@pytest.mark.parametrize("n,batch,T", [(2, 1, 32), (2, 1, 1), (3, 5, 4), (17, 1, 18), (17, 3, 5), (40, 1, 41), (40, 1, 42)])
+def test_row_counts_and_thresholds(torch_cuda, n, batch, T):
+    """ragged tails (N not a multiple of 64 or 256), every row high-degree (T = 1),
+    no row high-degree (T above the largest row)."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n, batch)
+    X = wl.uniform_features_numpy(n, 0, batch * aig.num_nodes, 32)
+    Y, _, _, _ = _run(torch_cuda, g, T, X)
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, f"n={n} batch={batch} T={T}")
+
+
+@pytest.mark.parametrize("flags", [0, 1, 3, 5])
+def test_flag_variants_with_empty_rows(torch_cuda, flags):
+    """directed / no self-loops: primary inputs (and isolated nodes) have empty rows -> 0"""
+    aig, g, (rowptr, col, val, pol) = _aig_case(16, 2, flags)
+    X = wl.uniform_features_numpy(3, 0, 2 * aig.num_nodes, 16)
+    Y, _, _, _ = _run(torch_cuda, g, 6, X)
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, f"flags={flags}")
+    empty = np.diff(rowptr) == 0
+    if flags & 2 == 0:
+        assert empty.any()
+    assert (Y[empty] == 0).all()
+
+
+def test_tiny_graphs(torch_cuda):
+    # a single row; and a graph whose only non-empty row is the last one
+    g = G.groot_graph_from_csr(np.array([0, 1]), np.array([0], dtype=np.int32), np.array([2.0], dtype=np.float32))
+    X = np.arange(8, dtype=np.float32)[None, :]
+    Y, _, _, _ = _run(torch_cuda, g, 32, X)
+    assert np.array_equal(Y, 2 * X)
+    n = 300
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    rowptr[-1] = n
+    col = np.arange(n, dtype=np.int32)
+    val = np.full(n, 0.5, dtype=np.float32)
+    X = wl.uniform_features_numpy(1, 0, n, 8)
+    for T in (32, 400):
+        g = G.groot_graph_from_csr(rowptr, col, val)
+        Y, _, _, _ = _run(torch_cuda, g, T, X)
+        Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+        assert_close_to_oracle(Y, Y64, S, "last-row graph")
+        assert (Y[:-1] == 0).all()
+
+
+@pytest.mark.parametrize("T", [16, 32, 64, 128])
+def test_stress_graph_threshold_sweep(torch_cuda, T):
+    """Polarized degrees (scaled-down law of the 16M-row stress workload): rows
+    of up to 16,385 non-zeros are split over several workgroups."""
+    s = wl.stress_graph(4, 1 << 16, window=4096, dmin=64, dmax=16384)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    X = wl.uniform_features_numpy(4, 0, s.n, 128)
+    Y, plan, _, _ = _run(torch_cuda, g, T, X)
+    deg = np.diff(s.rowptr)
+    assert G.groot_plan_view(plan)["n_hd"] == int((deg >= T).sum())
+    Y64, S = oracle.spmm_f64(s.rowptr, s.col, s.val, X)
+    assert_close_to_oracle(Y, Y64, S, f"stress T={T}")
+
+
+def test_tuning_knobs_do_not_change_results(torch_cuda):
+    aig, g, (rowptr, col, val, pol) = _aig_case(64, 2)
+    X = wl.uniform_features_numpy(8, 0, 2 * aig.num_nodes, 64)
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    try:
+        for remap in (0, 1):
+            for chunk in (64, 4096):
+                G.groot_set_tuning("xcd_remap", remap)
+                G.groot_set_tuning("hd_chunk", chunk)
+                Y, _, _, _ = _run(torch_cuda, g, 12, X)
+                assert_close_to_oracle(Y, Y64, S, f"remap={remap} chunk={chunk}")
+    finally:
+        G.groot_set_tuning("xcd_remap", 1)
+        G.groot_set_tuning("hd_chunk", 512)
+
+
+def test_phases_cover_disjoint_rows(torch_cuda):
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(32, 1)
+    n, F = aig.num_nodes, 32
+    plan = G.groot_spmm_plan(g, 16)
+    G.groot_plan_upload(plan, F)
+    pv = G.groot_plan_view(plan)
+    X = wl.uniform_features(2, 0, n, F, device="cuda")
+    Y = torch.full((n, F), float("nan"), device="cuda")
+    G.groot_spmm_execute_phases(plan, X, Y, F, G.GROOT_PHASE_LD)
+    torch.cuda.synchronize()
+    written = ~torch.isnan(Y).any(dim=1).cpu().numpy()
+    assert np.array_equal(written, pv["row_class"] == 0)
+    G.groot_spmm_execute_phases(plan, X, Y, F, G.GROOT_PHASE_HD | G.GROOT_PHASE_FINISH)
+    torch.cuda.synchronize()
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X.cpu().numpy())
+    assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "phases")
+    # F larger than the uploaded maximum is refused
+    with pytest.raises(G.GrootError):
+        G.groot_spmm_execute(plan, torch.zeros(n, 64, device="cuda"), torch.zeros(n, 64, device="cuda"), 64)
+    with pytest.raises(G.GrootError):      # overlap
+        G.groot_spmm_execute(plan, X, X, F)
+
+
+def test_execute_on_side_stream(torch_cuda):
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(48, 1)
+    F = 64
+    plan = G.groot_spmm_plan(g, 32)
+    G.groot_plan_upload(plan, F)
+    X = wl.uniform_features(5, 0, aig.num_nodes, F, device="cuda")
+    Y = torch.empty_like(X)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        G.groot_spmm_execute(plan, X, Y, F)          # picks up the current (side) stream
+    side.synchronize()
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X.cpu().numpy())
+    assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "side stream")
+
+
+@pytest.mark.parametrize("n,batch,P,regrow", [(32, 2, 4, 1), (64, 1, 16, 1), (32, 1, 3, 0)])
+def test_partitioned_mode_scatters_back_to_full_result(torch_cuda, n, batch, P, regrow):
+    """rows_gather -> per-part SpMM -> rows_scatter reproduces the full-graph
+    oracle on every owned row (with re-growth); without re-growth it equals the
+    oracle evaluated on the induced sub-graphs."""
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(n, batch)
+    N, F = batch * aig.num_nodes, 64
+    X_np = wl.uniform_features_numpy(6, 0, N, F)
+    X = torch.from_numpy(X_np).cuda()
+    Y = torch.full((N, F), float("nan"), device="cuda")
+    parts = G.groot_partition_regrow(g, P, None, G.GROOT_REGROW if regrow else 0)
+    part_of = oracle.part_of_default(N, aig.num_nodes, P)
+    Y64 = np.empty((N, F))
+    S = np.empty((N, F))
+    for p in range(P):
+        pv = G.groot_parts_view(parts, p)
+        ids = torch.from_numpy(pv["global_id"].copy()).cuda()
+        n_loc = ids.shape[0]
+        Xp = torch.empty((n_loc, F), device="cuda")
+        Yp = torch.empty((n_loc, F), device="cuda")
+        G.groot_rows_gather(ids, X, Xp, F)
+        plan = G.groot_spmm_plan(pv["sub"], 32)
+        G.groot_plan_upload(plan, F)
+        G.groot_spmm_execute(plan, Xp, Yp, F)
+        G.groot_rows_scatter(ids[:pv["n_owned"]], Yp, Y, F)
+        torch.cuda.synchronize()
+        assert np.array_equal(Xp.cpu().numpy(), X_np[pv["global_id"]])
+        if not regrow:
+            want = oracle.regrow_part(rowptr, col, val, part_of, p, 0, 1)
+            yp, sp = oracle.spmm_f64(want["rowptr"], want["col"], want["val"], X_np[want["global_id"]])
+            Y64[want["global_id"]] = yp
+            S[want["global_id"]] = sp
+    if regrow:
+        Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
+    assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "partitioned")

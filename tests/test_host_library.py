@@ -1,0 +1,214 @@
+"""Host side of the library against the oracle, bit for bit (no GPU): CSR,
+weights, polarity bytes, plan lists, partition outputs, error paths, and the
+exported symbol table."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import ensure_built
+
+ensure_built()
+import paper_2511_18297_amd as G  # noqa: E402
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "groot.h")).read()
+    declared = set(re.findall(r"\b(groot_[a-z_]+)\s*\(", header))
+    assert declared == set(G.EXPORTS)
+    lib = ctypes.CDLL(G.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+@pytest.mark.parametrize("n,batch,flags", [
+    (2, 1, 7), (3, 2, 7), (8, 1, 7), (32, 1, 7), (32, 3, 7), (64, 2, 7),
+    (8, 1, 0), (8, 2, 1), (8, 1, 2), (8, 1, 3), (8, 1, 5), (8, 1, 6),
+])
+def test_graph_build_bit_exact(n, batch, flags):
+    aig = wl.csa_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch, flags)
+    v = G.groot_graph_view(g)
+    rowptr, col, val, pol = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch, flags)
+    assert v["n"] == aig.num_nodes * batch and v["nnz"] == rowptr[-1]
+    assert np.array_equal(v["rowptr"], rowptr)
+    assert np.array_equal(v["col"], col)
+    assert np.array_equal(v["val"].view(np.uint32), val.view(np.uint32))
+    assert np.array_equal(v["pol"], pol)
+
+
+def test_graph_build_hand_made_aig_with_repeated_fanin():
+    # node 3 = AND(x, !x) on the same driver, node 4 = AND(!2, 3), PO on !4
+    typ = np.array([0, 0, 1, 1, 1, 2], dtype=np.uint8)
+    f0 = np.array([-1, -1, 0, 4, 5, 9], dtype=np.int32)
+    f1 = np.array([-1, -1, 2, 5, 6, 9], dtype=np.int32)
+    for flags in (7, 0, 3):
+        g = G.groot_graph_build(typ, f0, f1, 2, flags)
+        v = G.groot_graph_view(g)
+        o = oracle.csr_build(typ, f0, f1, 2, flags)
+        for a, b in zip((v["rowptr"], v["col"], v["val"], v["pol"]), o):
+            assert np.array_equal(a, b)
+
+
+def test_graph_build_rejects_bad_input():
+    aig = wl.csa_multiplier_aig(4)
+    t, a, b = aig.type.copy(), aig.fanin0.copy(), aig.fanin1.copy()
+
+    def expect(status, **kw):
+        args = dict(type_=t, fanin0=a, fanin1=b, batch=1, flags=7)
+        args.update(kw)
+        with pytest.raises(G.GrootError) as e:
+            G.groot_graph_build(**args)
+        assert e.value.status == status and len(str(e.value)) > 20
+
+    expect(G.GROOT_EINVAL, batch=0)
+    expect(G.GROOT_EINVAL, flags=8)
+    bad = a.copy(); bad[10] = 2 * 10          # literal pointing at itself: not topological
+    expect(G.GROOT_EINVAL, fanin0=bad)
+    bad = a.copy(); bad[10] = -1
+    expect(G.GROOT_EINVAL, fanin0=bad)
+    bad = a.copy(); bad[0] = 2                # primary input with a fanin
+    expect(G.GROOT_EINVAL, fanin0=bad)
+    bad = a.copy(); bad[-1] ^= 1              # PO slots differ
+    expect(G.GROOT_EINVAL, fanin0=bad)
+    bad = t.copy(); bad[7] = 3
+    expect(G.GROOT_EINVAL, type_=bad)
+    expect(G.GROOT_ERANGE, batch=2 ** 31 // aig.num_nodes + 1)
+    status = G.binding._lib.groot_graph_build(4, None, None, None, 1, 7, None)
+    assert status == G.GROOT_EINVAL and "NULL" in G.groot_last_error()
+
+
+def test_from_csr_roundtrip_and_checks():
+    g0 = wl.stress_graph(3, 1 << 12, window=64, dmin=64, dmax=512)
+    g = G.groot_graph_from_csr(g0.rowptr, g0.col, g0.val)
+    v = G.groot_graph_view(g)
+    assert np.array_equal(v["rowptr"], g0.rowptr) and np.array_equal(v["col"], g0.col)
+    assert np.array_equal(v["val"], g0.val) and v["pol"] is None
+    bad = g0.col.copy(); bad[1], bad[0] = bad[0], bad[1]
+    with pytest.raises(G.GrootError):
+        G.groot_graph_from_csr(g0.rowptr, bad, g0.val)
+    bad = g0.col.copy(); bad[5] = g0.n
+    with pytest.raises(G.GrootError):
+        G.groot_graph_from_csr(g0.rowptr, bad, g0.val)
+    rp = g0.rowptr.copy(); rp[3] = rp[4] + 1
+    with pytest.raises(G.GrootError):
+        G.groot_graph_from_csr(rp, g0.col, g0.val)
+
+
+@pytest.mark.parametrize("n,batch,T", [(8, 1, 7), (8, 3, 9), (32, 1, 32), (32, 2, 33), (32, 1, 34), (32, 1, 1),
+                                       (64, 1, 4), (64, 1, 6), (256, 1, 32)])
+def test_plan_bit_exact(n, batch, T):
+    aig = wl.csa_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    pv = G.groot_plan_view(G.groot_spmm_plan(g, T))
+    rowptr = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch)[0]
+    want = oracle.plan(rowptr, T)
+    for k, w in want.items():
+        assert np.array_equal(pv[k], w), k
+    assert pv["n_hd"] == len(want["hd_rows"]) and pv["n_ld"] == len(want["ld_rows"])
+
+
+@pytest.mark.parametrize("T", [16, 32, 64, 128])
+def test_plan_bit_exact_on_stress_graph(T):
+    g0 = wl.stress_graph(4, 1 << 15, window=256, dmin=64, dmax=1024)
+    g = G.groot_graph_from_csr(g0.rowptr, g0.col, g0.val)
+    pv = G.groot_plan_view(G.groot_spmm_plan(g, T))
+    want = oracle.plan(g0.rowptr, T)
+    for k, w in want.items():
+        assert np.array_equal(pv[k], w), k
+
+
+def _compare_parts(g, rowptr, col, val, part_of, P, flags, weight_mode):
+    parts = G.groot_partition_regrow(g, P, part_of, flags)
+    assert G.groot_parts_count(parts) == P
+    po = part_of
+    for p in range(P):
+        got = G.groot_parts_view(parts, p)
+        want = oracle.regrow_part(rowptr, col, val, po, p, flags, weight_mode)
+        sub = G.groot_graph_view(got["sub"])
+        for k in ("n_owned", "n_halo", "n_crossing"):
+            assert got[k] == want[k], (p, k)
+        assert np.array_equal(got["global_id"], want["global_id"])
+        assert np.array_equal(sub["rowptr"], want["rowptr"])
+        assert np.array_equal(sub["col"], want["col"])
+        assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
+
+
+@pytest.mark.parametrize("n,batch,P", [(2, 1, 2), (4, 2, 3), (8, 1, 5), (16, 2, 16), (32, 1, 7)])
+@pytest.mark.parametrize("flags", [G.GROOT_REGROW, 0])
+def test_partition_bit_exact_default_rule(n, batch, P, flags):
+    aig = wl.csa_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    part_of = oracle.part_of_default(len(rowptr) - 1, aig.num_nodes, P)
+    parts = G.groot_partition_regrow(g, P, None, flags)
+    for p in range(P):
+        got = G.groot_parts_view(parts, p)
+        want = oracle.regrow_part(rowptr, col, val, part_of, p, flags, 1)
+        sub = G.groot_graph_view(got["sub"])
+        assert (got["n_owned"], got["n_halo"], got["n_crossing"]) == (want["n_owned"], want["n_halo"], want["n_crossing"])
+        assert np.array_equal(got["global_id"], want["global_id"])
+        assert np.array_equal(sub["rowptr"], want["rowptr"]) and np.array_equal(sub["col"], want["col"])
+        assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
+
+
+def test_partition_bit_exact_user_parts_and_weight_modes():
+    rng = np.random.default_rng(5)
+    aig = wl.csa_multiplier_aig(8)
+    # random assignment on the mean-normalised graph
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    part_of = rng.integers(0, 4, size=aig.num_nodes).astype(np.int32)
+    _compare_parts(g, rowptr, col, val, part_of, 4, G.GROOT_REGROW, 1)
+    # unit weights
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1, 3)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1, 3)
+    _compare_parts(g, rowptr, col, val, part_of, 4, G.GROOT_REGROW, 0)
+    # directed graph with explicit weights (one-way crossing edges)
+    s = wl.stress_graph(9, 1 << 11, window=32, dmin=64, dmax=256)
+    w = rng.random(len(s.col)).astype(np.float32)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, w)
+    part_of = rng.integers(0, 3, size=s.n).astype(np.int32)
+    _compare_parts(g, s.rowptr, s.col, w, part_of, 3, G.GROOT_REGROW, 2)
+    _compare_parts(g, s.rowptr, s.col, w, part_of, 3, 0, 2)
+    # an empty part is legal
+    part_of[:] = 0
+    _compare_parts(g, s.rowptr, s.col, w, part_of, 2, G.GROOT_REGROW, 2)
+
+
+def test_partition_and_misc_error_paths():
+    aig = wl.csa_multiplier_aig(4)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    for kw in (dict(num_parts=0), dict(num_parts=aig.num_nodes + 1), dict(num_parts=2, flags=2),
+               dict(num_parts=2, part_of=np.full(aig.num_nodes, 2, dtype=np.int32))):
+        with pytest.raises(G.GrootError) as e:
+            G.groot_partition_regrow(g, **kw)
+        assert e.value.status == G.GROOT_EINVAL
+    parts = G.groot_partition_regrow(g, 2)
+    with pytest.raises(G.GrootError):
+        G.groot_parts_view(parts, 2)
+    with pytest.raises(G.GrootError):
+        G.groot_set_tuning("no_such_knob", 1)
+    with pytest.raises(G.GrootError):
+        G.groot_set_tuning("hd_chunk", 7)
+    G.groot_set_tuning("hd_chunk", 512)
+    plan = G.groot_spmm_plan(g, 32)
+    # executing without device residency is refused on the host, before any HIP call
+    lib = G.binding._lib
+    assert lib.groot_spmm_execute(plan.handle, 16, 32, 64, None) == G.GROOT_EINVAL
+    assert "groot_plan_upload" in G.groot_last_error()
+    assert lib.groot_spmm_execute(plan.handle, None, 32, 64, None) == G.GROOT_EINVAL
+    assert lib.groot_spmm_execute(plan.handle, 16, 36, 64, None) == G.GROOT_EINVAL      # misaligned
+    assert lib.groot_spmm_execute(plan.handle, 16, 32, 6, None) == G.GROOT_EINVAL       # F % 4
+    assert lib.groot_rows_gather(None, 5, 16, 32, 64, None) == G.GROOT_EINVAL
+    assert lib.groot_rows_gather(None, 0, 16, 32, 64, None) == G.GROOT_OK               # empty: no-op
+    assert lib.groot_plan_upload(plan.handle, 6) == G.GROOT_EINVAL
+    G.binding._lib.groot_graph_free(None)
+    G.binding._lib.groot_plan_free(None)
+    G.binding._lib.groot_parts_free(None)

@@ -1,0 +1,31 @@
+"""Helpers shared by the tests."""
+import os
+
+import numpy as np
+
+
+def ensure_built():
+    """Load what is built; build only if nothing is."""
+    from paper_2511_18297_amd import build as groot_build
+
+    if not os.path.exists(groot_build.LIB_PATH):
+        groot_build.build()
+
+
+def tolerance(S):
+    """Accepted fp32-vs-fp64 deviation per element: 1e-5 * sum|a_ij x_jk| + 1e-6."""
+    return 1e-5 * S + 1e-6
+
+
+def assert_close_to_oracle(Y_gpu, Y64, S, what=""):
+    Y_gpu = np.asarray(Y_gpu, dtype=np.float64)
+    assert Y_gpu.shape == Y64.shape, (Y_gpu.shape, Y64.shape)
+    assert np.isfinite(Y_gpu).all(), f"{what}: non-finite output (a row was not written?)"
+    err = np.abs(Y_gpu - Y64)
+    tol = tolerance(S)
+    bad = err > tol
+    if bad.any():
+        i, k = np.argwhere(bad)[0]
+        raise AssertionError(f"{what}: {bad.sum()} elements out of tolerance, first at row {i} col {k}: "
+                             f"gpu {Y_gpu[i, k]!r} oracle {Y64[i, k]!r} tol {tol[i, k]!r}")
+    return float(np.max(err / tol))
