@@ -33,6 +33,12 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_18297_amd.build` "
                       "(or __graft_entry__.build()); there is no fallback path")
 
+# torch is imported first on purpose: it carries its own HIP runtime
+# (libamdhip64.so.7) and the process must hold exactly one.  Loaded afterwards,
+# libgroot.so binds to that same runtime through the shared soname, so device
+# pointers and streams made by torch are valid inside the library.
+import torch  # noqa: E402,F401
+
 _lib = ctypes.CDLL(LIB_PATH)
 
 _vp = ctypes.c_void_p

@@ -94,7 +94,7 @@ def test_row_counts_and_thresholds(torch_cuda, n, batch, T):
     assert_close_to_oracle(Y, Y64, S, f"n={n} batch={batch} T={T}")
 
 
-@pytest.mark.parametrize("flags", [0, 1, 3, 5])
+@pytest.mark.parametrize("flags", [0, 1, 3, 4, 5])
 def test_flag_variants_with_empty_rows(torch_cuda, flags):
     """directed / no self-loops: primary inputs (and isolated nodes) have empty rows -> 0"""
     aig, g, (rowptr, col, val, pol) = _aig_case(16, 2, flags)
@@ -103,7 +103,7 @@ def test_flag_variants_with_empty_rows(torch_cuda, flags):
     Y64, S = oracle.spmm_f64(rowptr, col, val, X)
     assert_close_to_oracle(Y, Y64, S, f"flags={flags}")
     empty = np.diff(rowptr) == 0
-    if flags & 2 == 0:
+    if flags & 3 == 0:      # directed, no self-loops: primary inputs aggregate nothing
         assert empty.any()
     assert (Y[empty] == 0).all()
 
