@@ -30,6 +30,11 @@ WORKLOADS = {
 }
 
 
+# HBM-side traffic of one ld_kernel launch in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
+# (see profiles/); filled in per workload once measured, None otherwise.
+TRAFFIC = {}
+
+
 def algorithmic_bytes(n, nnz, F):
     """row pointers + column indices + weights + X read once + Y written once"""
     return 8 * (n + 1) + 4 * nnz + 4 * nnz + 4 * n * F + 4 * n * F
@@ -43,6 +48,7 @@ def main():
     ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--xcd-remap", type=int, default=None)
+    ap.add_argument("--hd-chunk", type=int, default=None)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU by design); "
@@ -64,6 +70,8 @@ def main():
     props = torch.cuda.get_device_properties(0)
     if args.xcd_remap is not None:
         G.groot_set_tuning("xcd_remap", args.xcd_remap)
+    if args.hd_chunk is not None:
+        G.groot_set_tuning("hd_chunk", args.hd_chunk)
 
     name = args.workload
     if name is None:
@@ -114,8 +122,9 @@ def main():
         return start.elapsed_time(stop) / args.steps
 
     ms_ld = timed_phase(G.GROOT_PHASE_LD)
-    ms_hd = timed_phase(G.GROOT_PHASE_HD | G.GROOT_PHASE_FINISH) if n_hd else 0.0
-    # LD launch: whole rowptr, the LD rows' indices and weights, X once, the LD rows of Y
+    ms_hd = timed_phase(G.GROOT_PHASE_HD) if n_hd else 0.0
+    ms_fin = timed_phase(G.GROOT_PHASE_FINISH) if n_hd else 0.0
+    # LD launch, algorithmic bytes: all row pointers, the LD rows' indices and weights, X once, the LD rows of Y
     bytes_ld = 8 * (n + 1) + 8 * (nnz - nnz_hd) + 4 * n * F + 4 * n_ld * F
     ld_gbps = bytes_ld / (ms_ld * 1e-3) / 1e9
 
@@ -175,9 +184,10 @@ def main():
         "hbm_pct_of_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": bytes_all,
         "roofline": {"bound": "hbm", "kernel": "ld_kernel", "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC.get(name),
                      "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld},
         "hd_ms": round(ms_hd, 4),
+        "finish_ms": round(ms_fin, 4),
         "copy_kernel_gbps": round(copy_gbps, 1),
         "cpu_baseline": cpu,
         "parity_max_err_over_tol": parity,

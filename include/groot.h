@@ -48,7 +48,7 @@ typedef struct groot_parts groot_parts;
 #define GROOT_NORM_MEAN  4u   /* weight 1/(stored row length); otherwise 1 */
 /* flags of groot_partition_regrow */
 #define GROOT_REGROW     1u   /* add boundary nodes and crossing edges (0: plain induced sub-graphs) */
-/* phases of groot_spmm_execute_phases */
+/* phases of groot_spmm_execute_phases: one kernel launch each */
 #define GROOT_PHASE_LD     1u
 #define GROOT_PHASE_HD     2u
 #define GROOT_PHASE_FINISH 4u

@@ -340,7 +340,7 @@ extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_thr
             int32_t row = pl->hd_rows[k];
             int64_t b = g->rowptr[row], d = g->rowptr[row + 1] - b;
             int64_t pieces = (d + chunk - 1) / chunk;
-            if (pieces > std::numeric_limits<int32_t>::max() / 2 || slots + pieces > std::numeric_limits<int32_t>::max())
+            if (slots + pieces > std::numeric_limits<int32_t>::max() / 2)
                 return fail(GROOT_ERANGE, "groot_spmm_plan: too many high-degree pieces");
             int64_t per = (d + pieces - 1) / pieces;
             if (pieces > 1) pl->split_rows.push_back(HdSplitRow{row, (int32_t)slots, (int32_t)pieces, 0});
@@ -351,7 +351,7 @@ extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_thr
                 ch.len = (int32_t)std::max<int64_t>(0, hi - lo);
                 ch.row = row;
                 ch.slot = pieces > 1 ? (int32_t)(slots + c) : -1;
-                ch.pad = 0;
+                ch.row_nnz = (int32_t)std::min<int64_t>(d, std::numeric_limits<int32_t>::max());
                 pl->chunks.push_back(ch);
             }
             if (pieces > 1) slots += pieces;
@@ -420,10 +420,12 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
     d.nnz = g->nnz;
     d.threshold = plan->threshold;
     d.xcd_remap = tuning().xcd_remap;
+    d.weight_mode = (int)g->weight_mode;
+    const bool need_val = g->weight_mode == WeightMode::Explicit;   // row-uniform weights are recomputed on the device
     groot_status st;
     if ((st = to_device(&d.rowptr, g->rowptr.data(), g->rowptr.size(), "rowptr")) != GROOT_OK ||
         (st = to_device(&d.col, g->col.data(), g->col.size(), "col")) != GROOT_OK ||
-        (st = to_device(&d.val, g->val.data(), g->val.size(), "val")) != GROOT_OK ||
+        (st = to_device(&d.val, g->val.data(), need_val ? g->val.size() : 0, "val")) != GROOT_OK ||
         (st = to_device(&d.chunks, plan->chunks.data(), plan->chunks.size(), "HD schedule")) != GROOT_OK ||
         (st = to_device(&d.split_rows, plan->split_rows.data(), plan->split_rows.size(), "HD split rows")) != GROOT_OK ||
         (st = to_device<float>(&d.partials, nullptr, (size_t)plan->n_partials * max_F, "HD partial sums")) != GROOT_OK) {
@@ -433,6 +435,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         return st;
     }
     d.n_chunks = (int64_t)plan->chunks.size();
+    d.n_tiles = (g->n + kRowsPerLdTile - 1) / kRowsPerLdTile;
     d.n_split_rows = (int64_t)plan->split_rows.size();
     d.n_partials = plan->n_partials;
     plan->max_F = max_F;

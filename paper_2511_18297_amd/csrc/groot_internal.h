@@ -22,7 +22,7 @@ struct HdChunk {
     int32_t len;
     int32_t row;
     int32_t slot;
-    int32_t pad;
+    int32_t row_nnz;   // stored length of the whole row (row-uniform weights are 1/row_nnz)
 };
 
 // A high-degree row that was split: Y[row] = sum of partials[first .. first+count)
@@ -46,16 +46,18 @@ struct DevicePlan {
     int64_t *rowptr = nullptr;
     int32_t *col = nullptr;
     float *val = nullptr;
+    int weight_mode = 0;            // WeightMode; val is NULL unless Explicit
+    int64_t n_tiles = 0;            // LD tiles of kRowsPerLdTile rows
     HdChunk *chunks = nullptr;
     int64_t n_chunks = 0;
     HdSplitRow *split_rows = nullptr;
     int64_t n_split_rows = 0;
     float *partials = nullptr;      // [n_partials, partial_stride]
     int64_t n_partials = 0;
-    int64_t partial_stride = 512;   // floats per slot (max F)
     int xcd_remap = 1;
-    int hd_chunk = 512;
 };
+
+constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64 rows)
 
 // Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);

@@ -23,24 +23,36 @@ constexpr int kXcds = 8;                     // workgroups are dealt round-robin
 
 // Each XCD has its own L2.  Consecutive hardware workgroup ids land on
 // different XCDs, so the logical block index is transposed: XCD x walks the
-// x-th contiguous eighth of the blocks in ascending order.
+// x-th contiguous eighth of the tiles in ascending order.
 __device__ __forceinline__ int64_t logical_block(int64_t blocks_per_xcd, int remap)
 {
     int64_t b = blockIdx.x;
     return remap ? (b % kXcds) * blocks_per_xcd + b / kXcds : b;
 }
 
+// Weight of the entries of a row: kExplicit reads val[]; kMean and kOnes are
+// the row-uniform weights of graphs built from an AIG and need no weight array
+// (1/row length is recomputed in registers, correctly rounded, from the row
+// pointer; this saves 4 bytes of HBM traffic per non-zero).
+enum : int { kOnes = (int)WeightMode::Ones, kMean = (int)WeightMode::Mean, kExplicit = (int)WeightMode::Explicit };
+
+template <int W>
+__device__ __forceinline__ float row_weight(int64_t row_nnz)
+{
+    return W == kMean ? (row_nnz > 0 ? 1.0f / (float)row_nnz : 0.0f) : 1.0f;
+}
+
 // ---------------------------------------------------------------------------
-// LD kernel.  A wavefront owns 64 consecutive rows.  When none of them is
+// LD part.  A wavefront owns 64 consecutive rows.  When none of them is
 // high-degree and the tile's non-zeros fit, the wavefront first copies the
-// tile's column indices and weights to LDS with fully coalesced loads; lane
+// tile's column indices (and weights) to LDS with fully coalesced loads; lane
 // groups then walk their rows (group g takes rows g, g+G, g+2G, ...), gather
 // the feature slices of all neighbours of a row before accumulating them in
 // registers, and store the finished slice.  The G groups of a wavefront always
 // store G consecutive rows, i.e. one contiguous G*F*4-byte area per store.
-// High-degree rows are skipped (the HD kernel writes them).
+// High-degree rows are skipped (HD pieces write them).
 // ---------------------------------------------------------------------------
-template <int L, bool kStaged>
+template <int W, bool kStaged>
 __device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *__restrict__ cols,
                                           const float *__restrict__ vals, const v4f *__restrict__ X,
                                           int32_t F4, int32_t ff)
@@ -53,33 +65,35 @@ __device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *_
         for (int k = 0; k < 8; ++k) {
             if (p + k < e) {
                 int32_t c = kStaged ? cols[p + k] : __builtin_nontemporal_load(&cols[p + k]);
-                w[k] = kStaged ? vals[p + k] : __builtin_nontemporal_load(&vals[p + k]);
+                if (W == kExplicit) w[k] = kStaged ? vals[p + k] : __builtin_nontemporal_load(&vals[p + k]);
                 x[k] = X[(int64_t)c * F4 + ff];
             }
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k)
-            if (p + k < e) acc += w[k] * x[k];
+            if (p + k < e) {
+                if (W == kExplicit) acc += w[k] * x[k];
+                else acc += x[k];
+            }
     }
+    if (W != kExplicit) acc *= row_weight<W>(e - s);
     return acc;
 }
 
-template <int L>
-__global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ rowptr,
-                                                    const int32_t *__restrict__ col,
-                                                    const float *__restrict__ val,
-                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
-                                                    int64_t n, int32_t F4, int32_t T,
-                                                    int64_t blocks_per_xcd, int remap)
-{
-    __shared__ int32_t s_col[kWavesPerBlock][kLdTileCap];
-    __shared__ float s_val[kWavesPerBlock][kLdTileCap];
-    __shared__ int32_t s_rel[kWavesPerBlock][kLdTileRows + 1];
+constexpr int kLdsBytes = kWavesPerBlock * (2 * kLdTileCap + kLdTileRows + 1) * 4;
 
+template <int L, int W>
+__device__ __forceinline__ void ld_tile(char *smem, int64_t tile, const int64_t *__restrict__ rowptr,
+                                        const int32_t *__restrict__ col, const float *__restrict__ val,
+                                        const v4f *__restrict__ X, v4f *__restrict__ Y, int64_t n,
+                                        int32_t F4, int32_t T)
+{
     constexpr int G = kWave / L;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int64_t blk = logical_block(blocks_per_xcd, remap);
-    const int64_t base = (blk * kWavesPerBlock + wave) * kLdTileRows;   // may lie beyond n: empty tile
+    int32_t *s_col = (int32_t *)smem + wave * kLdTileCap;
+    float *s_val = (float *)smem + (kWavesPerBlock + wave) * kLdTileCap;
+    int32_t *s_rel = (int32_t *)smem + 2 * kWavesPerBlock * kLdTileCap + wave * (kLdTileRows + 1);
+    const int64_t base = (tile * kWavesPerBlock + wave) * kLdTileRows;   // may lie beyond n: empty tile
 
     const int64_t r = base + lane;
     int64_t rp0 = 0, rp1 = 0;
@@ -91,11 +105,11 @@ __global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ 
 
     if (staged) {
         const int m = (int)(tile_end - tile_begin);
-        s_rel[wave][lane] = (r < n) ? (int32_t)(rp0 - tile_begin) : m;
-        if (lane == 0) s_rel[wave][kLdTileRows] = m;
+        s_rel[lane] = (r < n) ? (int32_t)(rp0 - tile_begin) : m;
+        if (lane == 0) s_rel[kLdTileRows] = m;
         for (int p = lane; p < m; p += kWave) {
-            s_col[wave][p] = __builtin_nontemporal_load(&col[tile_begin + p]);
-            s_val[wave][p] = __builtin_nontemporal_load(&val[tile_begin + p]);
+            s_col[p] = __builtin_nontemporal_load(&col[tile_begin + p]);
+            if (W == kExplicit) s_val[p] = __builtin_nontemporal_load(&val[tile_begin + p]);
         }
     }
     __syncthreads();
@@ -106,16 +120,16 @@ __global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ 
         const int64_t row = base + lr;
         if (row >= n) break;
         if (staged) {
-            const int64_t s = s_rel[wave][lr], e = s_rel[wave][lr + 1];
+            const int64_t s = s_rel[lr], e = s_rel[lr + 1];
             for (int32_t ff = f; ff < F4; ff += L) {
-                v4f acc = ld_row_sum<L, true>(s, e, s_col[wave], s_val[wave], X, F4, ff);
+                v4f acc = ld_row_sum<W, true>(s, e, s_col, s_val, X, F4, ff);
                 __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
             }
         } else {
             const int64_t s = rowptr[row], e = rowptr[row + 1];
             if (e - s >= T) continue;
             for (int32_t ff = f; ff < F4; ff += L) {
-                v4f acc = ld_row_sum<L, false>(s, e, col, val, X, F4, ff);
+                v4f acc = ld_row_sum<W, false>(s, e, col, val, X, F4, ff);
                 __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
             }
         }
@@ -123,24 +137,22 @@ __global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------
-// HD kernel.  One workgroup per piece of a high-degree row (the plan cuts a
-// row into balanced pieces).  The 256/L lane groups of the workgroup stride
-// over the piece's non-zeros, each keeping a register accumulator for its
-// float4 slice; the group sums meet in LDS and are added by a tree.  The
-// result goes to Y (single-piece rows) or to the row's slot of partial sums.
+// HD part.  One workgroup per piece of a high-degree row (the plan cuts a row
+// into balanced pieces).  The 256/L lane groups of the workgroup stride over
+// the piece's non-zeros, each keeping a register accumulator for its float4
+// slice; the group sums meet in LDS and are added by a tree.  The result goes
+// to Y (single-piece rows) or to the row's slot of partial sums.
 // ---------------------------------------------------------------------------
-template <int L>
-__global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ chunks,
-                                                    const int32_t *__restrict__ col,
-                                                    const float *__restrict__ val,
-                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
-                                                    v4f *__restrict__ partials, int32_t F4)
+template <int L, int W>
+__device__ __forceinline__ void hd_piece(char *smem, const HdChunk ch, const int32_t *__restrict__ col,
+                                         const float *__restrict__ val, const v4f *__restrict__ X,
+                                         v4f *__restrict__ Y, v4f *__restrict__ partials, int32_t F4)
 {
     constexpr int G = kBlock / L;
-    __shared__ v4f s_red[G][L];
-    const HdChunk ch = chunks[blockIdx.x];
+    v4f(*s_red)[L] = (v4f(*)[L])smem;                    // [G][L]
     const int g = threadIdx.x / L, f = threadIdx.x % L;
     const int64_t end = ch.begin + ch.len;
+    const float rw = row_weight<W>(ch.row_nnz);
 
     for (int32_t fb = 0; fb < F4; fb += L) {
         const int32_t ff = fb + f;
@@ -150,15 +162,23 @@ __global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ 
             int64_t p = ch.begin + g;
             for (; p + 3 * G < end; p += 4 * G) {
                 int32_t c0 = col[p], c1 = col[p + G], c2 = col[p + 2 * G], c3 = col[p + 3 * G];
-                float w0 = val[p], w1 = val[p + G], w2 = val[p + 2 * G], w3 = val[p + 3 * G];
                 v4f x0 = X[(int64_t)c0 * F4 + ff], x1 = X[(int64_t)c1 * F4 + ff];
                 v4f x2 = X[(int64_t)c2 * F4 + ff], x3 = X[(int64_t)c3 * F4 + ff];
-                acc += w0 * x0;
-                acc += w1 * x1;
-                acc += w2 * x2;
-                acc += w3 * x3;
+                if (W == kExplicit) {
+                    acc += val[p] * x0;
+                    acc += val[p + G] * x1;
+                    acc += val[p + 2 * G] * x2;
+                    acc += val[p + 3 * G] * x3;
+                } else {
+                    acc += (x0 + x1) + (x2 + x3);
+                }
             }
-            for (; p < end; p += G) acc += val[p] * X[(int64_t)col[p] * F4 + ff];
+            for (; p < end; p += G) {
+                v4f x = X[(int64_t)col[p] * F4 + ff];
+                if (W == kExplicit) acc += val[p] * x;
+                else acc += x;
+            }
+            if (W != kExplicit) acc *= rw;
         }
         s_red[g][f] = acc;
         __syncthreads();
@@ -174,6 +194,33 @@ __global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ 
         }
         __syncthreads();
     }
+}
+
+// Block t of the LD launch computes the tile of rows [256 t, 256 t + 256).
+template <int L, int W>
+__global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ rowptr,
+                                                    const int32_t *__restrict__ col,
+                                                    const float *__restrict__ val,
+                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
+                                                    int64_t n, int32_t F4, int32_t T, int64_t n_tiles,
+                                                    int64_t blocks_per_xcd, int remap)
+{
+    __shared__ __align__(16) char smem[kLdsBytes];
+    const int64_t tile = logical_block(blocks_per_xcd, remap);
+    if (tile >= n_tiles) return;
+    ld_tile<L, W>(smem, tile, rowptr, col, val, X, Y, n, F4, T);
+}
+
+// Block k of the HD launch computes piece k.
+template <int L, int W>
+__global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ chunks,
+                                                    const int32_t *__restrict__ col,
+                                                    const float *__restrict__ val,
+                                                    const v4f *__restrict__ X, v4f *__restrict__ Y,
+                                                    v4f *__restrict__ partials, int32_t F4)
+{
+    __shared__ __align__(16) char smem[kBlock * sizeof(v4f)];
+    hd_piece<L, W>(smem, chunks[blockIdx.x], col, val, X, Y, partials, F4);
 }
 
 // Y[row] = partials[first] + ... + partials[first+count-1], in that order.
@@ -233,19 +280,32 @@ static int lanes_for(int32_t F4)
 
 static bool grid_ok(int64_t blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
 
+#define GROOT_DISPATCH_LW(L, W, CALL)                                  \
+    switch (W) {                                                       \
+    case kOnes: { constexpr int kW = kOnes; GROOT_DISPATCH_L(L, CALL) } break; \
+    case kMean: { constexpr int kW = kMean; GROOT_DISPATCH_L(L, CALL) } break; \
+    default: { constexpr int kW = kExplicit; GROOT_DISPATCH_L(L, CALL) } break; \
+    }
+
+static bool weights_ok(const DevicePlan &dp)
+{
+    // explicit weights need the weight array on the device; the other modes never touch it
+    return dp.weight_mode == kOnes || dp.weight_mode == kMean || dp.val != nullptr || dp.nnz == 0;
+}
+
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
 {
     const int32_t F4 = F / 4;
-    const int64_t rows_per_block = (int64_t)kWavesPerBlock * kLdTileRows;
-    const int64_t n_blocks = (dp.n + rows_per_block - 1) / rows_per_block;
-    const int64_t per_xcd = (n_blocks + kXcds - 1) / kXcds;
-    const int remap = dp.xcd_remap && n_blocks >= 4 * kXcds;
-    const int64_t grid = remap ? per_xcd * kXcds : n_blocks;
+    const int64_t per_xcd = (dp.n_tiles + kXcds - 1) / kXcds;
+    const int remap = dp.xcd_remap && dp.n_tiles >= 4 * kXcds;
+    const int64_t grid = remap ? per_xcd * kXcds : dp.n_tiles;
     if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    if (!weights_ok(dp)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    GROOT_DISPATCH_L(lanes_for(F4),
-                     (ld_kernel<kL><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                         dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)Y, dp.n, F4, dp.threshold, per_xcd, remap)));
+    GROOT_DISPATCH_LW(lanes_for(F4), dp.weight_mode,
+                      (ld_kernel<kL, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                          dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)Y, dp.n, F4, dp.threshold, dp.n_tiles,
+                          per_xcd, remap)));
     return (int)hipGetLastError();
 }
 
@@ -253,10 +313,11 @@ int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *s
 {
     const int32_t F4 = F / 4;
     if (!grid_ok(dp.n_chunks)) return (int)hipErrorInvalidConfiguration;
+    if (!weights_ok(dp)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    GROOT_DISPATCH_L(lanes_for(F4),
-                     (hd_kernel<kL><<<dim3((unsigned)dp.n_chunks), dim3(kBlock), 0, st>>>(
-                         dp.chunks, dp.col, dp.val, (const v4f *)X, (v4f *)Y, (v4f *)dp.partials, F4)));
+    GROOT_DISPATCH_LW(lanes_for(F4), dp.weight_mode,
+                      (hd_kernel<kL, kW><<<dim3((unsigned)dp.n_chunks), dim3(kBlock), 0, st>>>(
+                          dp.chunks, dp.col, dp.val, (const v4f *)X, (v4f *)Y, (v4f *)dp.partials, F4)));
     return (int)hipGetLastError();
 }
 
