@@ -1,0 +1,187 @@
+"""GPU parity at the workload sizes the benchmark runs (1024-bit multiplier,
+batch 1 and batch 16), in the launch configuration bench.py times.
+
+Batch 1 (8.4 M rows) is compared with the oracle element by element, and runs
+the two-layer GraphSAGE-mean forward pass (aggregation through the library,
+dense layers through torch).  Batch 16 (134 M rows) is too large for a full
+CPU pass, so it is checked (a) by a property that holds at any size and
+involves every row -- with X = 1 every mean-normalised row sums to
+deg * fl(1/deg) -- and (b) on sampled rows the oracle computes one by one from
+its own adjacency of one copy and the block-diagonal batch rule; the
+16-way partitioned mode must scatter back to the same result, and two of its
+parts are compared bit for bit with the oracle's re-growth."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from util import assert_close_to_oracle, ensure_built, tolerance
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
+
+ensure_built()
+import paper_2511_18297_amd as G  # noqa: E402
+
+BITS, F, T = 1024, 64, 32
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    torch.cuda.set_device(0)
+    return torch
+
+
+@pytest.fixture(scope="module")
+def one_copy():
+    aig = wl.csa_multiplier_aig(BITS)
+    rowptr, col, val, pol = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    return aig, rowptr, col, val
+
+
+def test_config3_spmm_and_graphsage_forward(torch_cuda, one_copy):
+    torch = torch_cuda
+    aig, rowptr, col, val = one_copy
+    n = aig.num_nodes
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    view = G.groot_graph_view(g)
+    assert view["nnz"] == rowptr[-1] and np.array_equal(view["col"], col) and np.array_equal(view["val"], val)
+    plan = G.groot_spmm_plan(g, T)
+    assert G.groot_plan_view(plan)["n_hd"] == 2 * BITS
+    G.groot_plan_upload(plan, F)
+    X = wl.uniform_features(2, 0, n, F, device="cuda")
+    X_np = X.cpu().numpy()
+    Y = torch.full_like(X, float("nan"))
+    G.groot_spmm_execute(plan, X, Y, F)
+    torch.cuda.synchronize()
+    A1, S1 = oracle.spmm_f64(rowptr, col, val, X_np)
+    assert_close_to_oracle(Y.cpu().numpy(), A1, S1, "config 3 SpMM")
+
+    # two GraphSAGE-mean layers, hidden 64, weights U(-1/8, 1/8) from a fixed seed
+    rng = np.random.default_rng(2)
+    W1n, W1s, W2n, W2s = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(4))
+    b1, b2 = (rng.uniform(-0.125, 0.125, F).astype(np.float32) for _ in range(2))
+    dev = lambda a: torch.from_numpy(a).cuda()
+    H1 = torch.relu(Y @ dev(W1n) + X @ dev(W1s) + dev(b1))
+    A2 = torch.full_like(H1, float("nan"))
+    G.groot_spmm_execute(plan, H1, A2, F)
+    H2 = A2 @ dev(W2n) + H1 @ dev(W2s) + dev(b2)
+    torch.cuda.synchronize()
+    H1_ref, H2_ref = oracle.sage_forward_f64(rowptr, col, val, X_np, W1n, W1s, b1, W2n, W2s, b2)
+    # error model: fp32 dot products of length 64 (|err| <= ~64 eps * sum|terms|) on top of the SpMM tolerance
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale1 = np.abs(A1) @ a64(W1n) + a64(X_np) @ a64(W1s) + a64(b1)
+    tol1 = tolerance(S1) @ a64(W1n) + 2e-5 * scale1 + 1e-6
+    err1 = np.abs(H1.cpu().numpy().astype(np.float64) - H1_ref.astype(np.float64))
+    assert (err1 <= tol1).all(), f"layer 1: max err/tol {np.max(err1 / tol1)}"
+    A2_ref, S2 = oracle.spmm_f64(rowptr, col, val, H1_ref)
+    P1, _ = oracle.spmm_f64(rowptr, col, val, tol1.astype(np.float32), want_abs=False)   # layer-1 error pushed through A_hat
+    scale2 = np.abs(A2_ref) @ a64(W2n) + a64(H1_ref) @ a64(W2s) + a64(b2)
+    tol2 = (tolerance(S2) + 1.001 * P1) @ a64(W2n) + 1.001 * tol1 @ a64(W2s) + 2e-5 * scale2 + 1e-6
+    err2 = np.abs(H2.cpu().numpy().astype(np.float64) - H2_ref)
+    assert np.isfinite(err2).all() and (err2 <= tol2).all(), f"layer 2: max err/tol {np.max(err2 / tol2)}"
+
+
+def _sample_rows(rng, n1, batch, n_random):
+    picks = [rng.integers(0, n1 * batch, size=n_random)]
+    for c in range(batch):
+        picks.append(np.arange(c * n1, c * n1 + 300))                 # primary inputs: high-degree rows
+        picks.append(np.arange((c + 1) * n1 - 300, (c + 1) * n1))     # primary outputs, copy boundary
+    picks.append(np.arange(0, 2 * BITS))                              # every HD row of copy 0
+    picks.append(np.arange(7 * n1, 7 * n1 + 2 * BITS))                # ... and of copy 7
+    return np.unique(np.concatenate(picks))
+
+
+def _oracle_rows(rows, n1, rowptr, col, val, X_dev, torch):
+    """fp64 rows of A_hat X for global row ids, from the one-copy oracle adjacency shifted by the copy offset"""
+    copy, local = rows // n1, rows % n1
+    lens = (rowptr[local + 1] - rowptr[local]).astype(np.int64)
+    sub_rowptr = np.concatenate([[0], np.cumsum(lens)])
+    idx = np.concatenate([np.arange(rowptr[v], rowptr[v + 1]) for v in local])
+    gcol = col[idx].astype(np.int64) + np.repeat(copy * n1, lens)
+    uniq, inv = np.unique(gcol, return_inverse=True)
+    Xs = X_dev[torch.from_numpy(uniq).cuda()].cpu().numpy()
+    return oracle.spmm_f64(sub_rowptr, inv.astype(np.int32), val[idx], Xs)
+
+
+def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
+    torch = torch_cuda
+    if torch.cuda.get_device_properties(0).total_memory < 150e9:
+        pytest.skip("needs ~100 GB of device memory")
+    aig, rowptr, col, val = one_copy
+    n1, batch = aig.num_nodes, 16
+    n = n1 * batch
+    assert n == 134103040
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    view = G.groot_graph_view(g)
+    assert view["nnz"] == 670318592
+    plan = G.groot_spmm_plan(g, T)
+    pv = G.groot_plan_view(plan)
+    assert pv["n_hd"] == 2 * BITS * batch
+    assert np.array_equal(pv["hd_rows"].reshape(batch, -1), np.arange(2 * BITS)[None, :] + (np.arange(batch) * n1)[:, None])
+    G.groot_plan_upload(plan, F)
+
+    # (a) X = 1: every row of the mean-normalised graph sums to deg * fl(1/deg), within 2^-23 of 1
+    X = torch.ones((n, F), dtype=torch.float32, device="cuda")
+    Y = torch.full((n, F), float("nan"), dtype=torch.float32, device="cuda")
+    G.groot_spmm_execute(plan, X, Y, F)
+    torch.cuda.synchronize()
+    dev_max = 0.0
+    for lo in range(0, n, 1 << 24):
+        dev_max = max(dev_max, float((Y[lo:lo + (1 << 24)] - 1.0).abs().max()))
+    assert dev_max <= 2.0 ** -22, dev_max          # NaN (an unwritten row) fails this too
+
+    # (b) the benchmark's inputs, sampled rows against the oracle
+    wl.uniform_features(3, 0, n, F, out=X)
+    Y.fill_(float("nan"))
+    G.groot_spmm_execute(plan, X, Y, F)
+    torch.cuda.synchronize()
+    rows = _sample_rows(np.random.default_rng(4), n1, batch, 20000)
+    Y64, S = _oracle_rows(rows, n1, rowptr, col, val, X, torch)
+    Y_rows = Y[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert_close_to_oracle(Y_rows, Y64, S, "config 4 sampled rows")
+    assert not bool(torch.isnan(Y).any())
+
+    # (c) 16-way partition with re-grown boundary: gather -> per-part SpMM -> scatter
+    parts = G.groot_partition_regrow(g, 16)
+    Yp_full = torch.full((n, F), float("nan"), dtype=torch.float32, device="cuda")
+    total_cross = 0
+    for p in range(16):
+        pw = G.groot_parts_view(parts, p)
+        assert pw["n_owned"] == n // 16 or p == 15 or abs(pw["n_owned"] - n // 16) <= batch
+        total_cross += pw["n_crossing"]
+        ids = torch.from_numpy(pw["global_id"].copy()).cuda()
+        Xp = torch.empty((ids.shape[0], F), dtype=torch.float32, device="cuda")
+        Yp = torch.empty_like(Xp)
+        G.groot_rows_gather(ids, X, Xp, F)
+        sub_plan = G.groot_spmm_plan(pw["sub"], T)
+        G.groot_plan_upload(sub_plan, F)
+        G.groot_spmm_execute(sub_plan, Xp, Yp, F)
+        G.groot_rows_scatter(ids[:pw["n_owned"]], Yp, Yp_full, F)
+        torch.cuda.synchronize()
+        del sub_plan, Xp, Yp, ids
+    # boundary edges: about a tenth of the undirected edges are cut
+    undirected = (view["nnz"] - n) // 2
+    assert 0.08 < (total_cross / 2) / undirected < 0.16
+    Yp_rows = Yp_full[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert_close_to_oracle(Yp_rows, Y64, S, "config 4 partitioned, sampled rows")
+    # owned rows see their whole neighbourhood: same sums up to fp32 re-association
+    worst = 0.0
+    for lo in range(0, n, 1 << 24):
+        a, b = Yp_full[lo:lo + (1 << 24)], Y[lo:lo + (1 << 24)]
+        worst = max(worst, float((a - b).abs().max()))
+    assert worst <= 1e-5, worst
+
+    # two parts, bit for bit against the oracle's Eq. (1)-(2)
+    full_rowptr, full_col, full_val = view["rowptr"], view["col"], view["val"]
+    part_of = oracle.part_of_default(n, n1, 16)
+    for p in (0, 9):
+        pw = G.groot_parts_view(parts, p)
+        want = oracle.regrow_part(full_rowptr, full_col, full_val, part_of, p)
+        sub = G.groot_graph_view(pw["sub"])
+        assert (pw["n_owned"], pw["n_halo"], pw["n_crossing"]) == (want["n_owned"], want["n_halo"], want["n_crossing"])
+        assert np.array_equal(pw["global_id"], want["global_id"])
+        assert np.array_equal(sub["rowptr"], want["rowptr"]) and np.array_equal(sub["col"], want["col"])
+        assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
