@@ -32,7 +32,7 @@ WORKLOADS = {
 
 # HBM-side traffic of one ld_kernel launch in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
 # (see profiles/); filled in per workload once measured, None otherwise.
-TRAFFIC = {}
+TRAFFIC = {"csa1024_b16_F64": 80.52e9}   # 46.20 GB read + 34.32 GB written
 
 
 def algorithmic_bytes(n, nnz, F):
