@@ -238,6 +238,19 @@ def test_regrow_hand_cases(self_loops):
             assert bare["rowptr"][-1] == 2 * (want["kept"] - want["crossing"]) + (no if self_loops else 0)
 
 
+def test_partition_rule_closed_form():
+    """part(v) = min(P-1, floor((v mod n1) P / n1)): a hand-evaluated case and the slice sizes
+    ceil((p+1) n1 / P) - ceil(p n1 / P) that follow from the floor."""
+    assert list(oracle.part_of_default(10, 10, 3)) == [0, 0, 0, 0, 1, 1, 1, 2, 2, 2]
+    assert list(oracle.part_of_default(8, 4, 2)) == [0, 0, 1, 1, 0, 0, 1, 1]
+    for n1, P, copies in ((51, 4, 1), (1000, 7, 3), (18, 16, 2), (522496, 16, 1)):
+        part = oracle.part_of_default(n1 * copies, n1, P)
+        ceil = lambda a, b: -(-a // b)
+        want = [ceil((p + 1) * n1, P) - ceil(p * n1, P) for p in range(P)]
+        assert list(np.bincount(part, minlength=P)) == [w * copies for w in want]
+        assert part[0] == 0 and part[n1 - 1] == P - 1 and (np.diff(part[:n1]) >= 0).all()
+
+
 def _sets_bruteforce(rowptr, col, part_of, p):
     """Eq. (1)-(2) with Python sets."""
     n = len(rowptr) - 1
