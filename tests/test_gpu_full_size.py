@@ -185,3 +185,37 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
         assert np.array_equal(pw["global_id"], want["global_id"])
         assert np.array_equal(sub["rowptr"], want["rowptr"]) and np.array_equal(sub["col"], want["col"])
         assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
+
+
+def test_config5_stress_graph_long_rows(torch_cuda):
+    """Polarized stress workload at 2^20 rows with the full degree law (Zipf(1.2) draws clipped to
+    [64, 262144], F = 128): rows of up to ~230k stored entries are cut into hundreds of pieces.
+    Sampled rows (every class, the longest rows) against the oracle; threshold sweep as in the workload."""
+    torch = torch_cuda
+    n, Fw = 1 << 20, 128
+    s = wl.stress_graph(4, n, window=4096, dmin=64, dmax=262144)
+    deg = np.diff(s.rowptr)
+    assert deg.max() > 100000 and s.rowptr[-1] > 150e6
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    X = wl.uniform_features(4, 0, n, Fw, device="cuda")
+    rng = np.random.default_rng(5)
+    heavy = np.nonzero(deg >= 16)[0]
+    rows = np.unique(np.concatenate([rng.integers(0, n, 4000), rng.choice(heavy, 300, replace=False),
+                                     heavy[np.argsort(deg[heavy])[-8:]], [0, n - 1]]))
+    lens = deg[rows]
+    sub_rowptr = np.concatenate([[0], np.cumsum(lens)])
+    idx = np.concatenate([np.arange(s.rowptr[v], s.rowptr[v + 1]) for v in rows])
+    uniq, inv = np.unique(s.col[idx], return_inverse=True)
+    Xs = X[torch.from_numpy(uniq.astype(np.int64)).cuda()].cpu().numpy()
+    Y64, S = oracle.spmm_f64(sub_rowptr, inv.astype(np.int32), s.val[idx], Xs)
+    rows_dev = torch.from_numpy(rows).cuda()
+    for T_sweep in (16, 32, 64, 128):
+        plan = G.groot_spmm_plan(g, T_sweep)
+        assert G.groot_plan_view(plan)["n_hd"] == int((deg >= T_sweep).sum())
+        G.groot_plan_upload(plan, Fw)
+        Y = torch.full((n, Fw), float("nan"), dtype=torch.float32, device="cuda")
+        G.groot_spmm_execute(plan, X, Y, Fw)
+        torch.cuda.synchronize()
+        assert not bool(torch.isnan(Y).any())
+        assert_close_to_oracle(Y[rows_dev].cpu().numpy(), Y64, S, f"stress 2^20 T={T_sweep}")
+        del plan, Y
