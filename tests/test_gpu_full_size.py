@@ -10,6 +10,8 @@ deg * fl(1/deg) -- and (b) on sampled rows the oracle computes one by one from
 its own adjacency of one copy and the block-diagonal batch rule; the
 16-way partitioned mode must scatter back to the same result, and two of its
 parts are compared bit for bit with the oracle's re-growth."""
+import os
+
 import numpy as np
 import pytest
 
@@ -187,16 +189,17 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
         assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
 
 
-def test_config5_stress_graph_long_rows(torch_cuda):
-    """Polarized stress workload at 2^20 rows with the full degree law (Zipf(1.2) draws clipped to
-    [64, 262144], F = 128): rows of up to ~230k stored entries are cut into hundreds of pieces.
-    Sampled rows (every class, the longest rows) against the oracle; threshold sweep as in the workload."""
-    torch = torch_cuda
-    n, Fw = 1 << 20, 128
-    s = wl.stress_graph(4, n, window=4096, dmin=64, dmax=262144)
+def _stress_case(torch, log2n, thresholds):
+    import time
+
+    n, Fw = 1 << log2n, 128
+    t0 = time.time()
+    s = wl.stress_graph(4, n, window=4096, dmin=64, dmax=262144, verbose=True)
     deg = np.diff(s.rowptr)
+    print(f"stress graph 2^{log2n}: nnz {s.rowptr[-1]}, longest row {deg.max()}, generated in {time.time() - t0:.0f} s", flush=True)
     assert deg.max() > 100000 and s.rowptr[-1] > 150e6
     g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    print("graph object built", flush=True)
     X = wl.uniform_features(4, 0, n, Fw, device="cuda")
     rng = np.random.default_rng(5)
     heavy = np.nonzero(deg >= 16)[0]
@@ -209,13 +212,42 @@ def test_config5_stress_graph_long_rows(torch_cuda):
     Xs = X[torch.from_numpy(uniq.astype(np.int64)).cuda()].cpu().numpy()
     Y64, S = oracle.spmm_f64(sub_rowptr, inv.astype(np.int32), s.val[idx], Xs)
     rows_dev = torch.from_numpy(rows).cuda()
-    for T_sweep in (16, 32, 64, 128):
+    for T_sweep in thresholds:
         plan = G.groot_spmm_plan(g, T_sweep)
         assert G.groot_plan_view(plan)["n_hd"] == int((deg >= T_sweep).sum())
         G.groot_plan_upload(plan, Fw)
+        print(f"  T={T_sweep}: plan resident", flush=True)
         Y = torch.full((n, Fw), float("nan"), dtype=torch.float32, device="cuda")
         G.groot_spmm_execute(plan, X, Y, Fw)
         torch.cuda.synchronize()
         assert not bool(torch.isnan(Y).any())
-        assert_close_to_oracle(Y[rows_dev].cpu().numpy(), Y64, S, f"stress 2^20 T={T_sweep}")
+        assert_close_to_oracle(Y[rows_dev].cpu().numpy(), Y64, S, f"stress 2^{log2n} T={T_sweep}")
+        if log2n >= 24:          # the full-size instance also reports its time
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record()
+            for _ in range(3):
+                G.groot_spmm_execute(plan, X, Y, Fw)
+            stop.record()
+            stop.synchronize()
+            ms = start.elapsed_time(stop) / 3
+            print(f"  T={T_sweep}: n_hd {G.groot_plan_view(plan)['n_hd']}, {ms:.1f} ms per SpMM, "
+                  f"{2.0 * s.rowptr[-1] * Fw / ms / 1e9:.2f} TFLOP/s, gather demand "
+                  f"{4.0 * Fw * s.rowptr[-1] / ms / 1e9:.2f} TB/s", flush=True)
         del plan, Y
+    return s.rowptr[-1]
+
+
+def test_config5_stress_graph_long_rows(torch_cuda):
+    """Polarized stress workload at 2^20 rows with the full degree law (Zipf(1.2) draws clipped to
+    [64, 262144], F = 128): rows of up to ~230k stored entries are cut into hundreds of pieces.
+    Sampled rows (every class, the longest rows) against the oracle; threshold sweep as in the workload."""
+    _stress_case(torch_cuda, 20, (16, 32, 64, 128))
+
+
+@pytest.mark.skipif(os.environ.get("GROOT_RUN_HUGE") != "1",
+                    reason="16.7 M rows / ~4e9 non-zeros: minutes of host generation and ~70 GB of host memory; "
+                           "set GROOT_RUN_HUGE=1 to run")
+def test_config5_stress_graph_full_size(torch_cuda):
+    """The stress workload at its stated size (N = 2^24, more than 2^31 stored entries: 64-bit row pointers)."""
+    nnz = _stress_case(torch_cuda, 24, (16, 32, 64, 128))
+    assert nnz > 2 ** 31

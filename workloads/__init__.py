@@ -203,7 +203,8 @@ class Csr:
     val: np.ndarray     # float32 [nnz]
 
 
-def stress_graph(seed: int, n: int, window: int = 4096, dmin: int = 64, dmax: int = 262144) -> Csr:
+def stress_graph(seed: int, n: int, window: int = 4096, dmin: int = 64, dmax: int = 262144,
+                 verbose: bool = False) -> Csr:
     """1 % heavy rows (Zipf(1.2) draws clipped to [dmin, dmax], uniform
     columns), 99 % light rows (2-4 neighbours within +-window), self-loops,
     weights 1/row length.  Directed."""
@@ -214,6 +215,8 @@ def stress_graph(seed: int, n: int, window: int = 4096, dmin: int = 64, dmax: in
     nnz = lib.wl_stress_rowptr(seed, n, window, dmin, dmax, _ptr(rowptr, ctypes.c_int64))
     if nnz < 0:
         raise MemoryError("stress graph generation failed")
+    if verbose:
+        print(f"stress graph: row lengths done, {nnz} stored entries", flush=True)
     col = np.empty(nnz, dtype=np.int32)
     val = np.empty(nnz, dtype=np.float32)
     rc = lib.wl_stress_fill(seed, n, window, dmin, dmax, _ptr(rowptr, ctypes.c_int64),
