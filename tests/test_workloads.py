@@ -48,10 +48,13 @@ def test_two_bit_example_matches_paper():
     nodes, labels, features, functions, product = _parse_example()
     aig = wl.csa_multiplier_aig(2)
     assert aig.num_nodes == nodes
-    # node classes: label 4 -> PI, 0 -> PO, 1/2/3 -> internal AND node
+    # node classes: label 4 -> PI, 0 -> PO, 1/2/3 -> internal AND node; the generator's own
+    # classes (XOR root, MAJ/carry root, plain AND) are the paper's ground-truth labels
+    assert len(labels) == nodes
     for nid, lab in labels.items():
         want = wl.PI if lab == 4 else wl.PO if lab == 0 else wl.AND
         assert aig.type[nid - 1] == want, nid
+        assert aig.label[nid - 1] == lab, nid
     # feature bits: type bits 00 PI / 11 AND; polarity bits = (left inverted, right inverted)
     for nid, bits in features.items():
         v = nid - 1
@@ -71,6 +74,26 @@ def test_two_bit_example_matches_paper():
     pat = a | (b << 2)
     got = sum(((int(words[14 + k]) >> pat) & 1) << k for k in range(4))
     assert got == m == a * b
+
+
+@pytest.mark.parametrize("n", [2, 3, 8, 32])
+def test_label_counts_and_functions(n):
+    """n half adders and n(n-2) full adders: one MAJ root per adder, one XOR root per half adder and two
+    per full adder; every XOR root computes the xor of its grandparents' inputs, every MAJ root a carry."""
+    aig = wl.csa_multiplier_aig(n)
+    hist = np.bincount(aig.label, minlength=5)
+    ha, fa = n, n * (n - 2)
+    assert hist[4] == 2 * n and hist[0] == 2 * n
+    assert hist[1] == ha + fa and hist[2] == ha + 2 * fa
+    assert hist[3] == (8 * n * n - 11 * n) - hist[1] - hist[2]
+    rng = np.random.default_rng(n)
+    words = oracle.aig_simulate(aig.type, aig.fanin0, aig.fanin1, rng.integers(0, 2 ** 63, 2 * n, dtype=np.uint64))
+    lit = lambda l: words[l >> 1] ^ (np.uint64(0xFFFFFFFFFFFFFFFF) if l & 1 else np.uint64(0))
+    for v in np.nonzero(aig.label == 2)[0]:
+        # xor root t = AND(!g, !h) with g = AND(x, y), h = AND(!x, !y)
+        g = aig.fanin0[v] >> 1
+        x, y = aig.fanin0[g], aig.fanin1[g]
+        assert words[v] == lit(x) ^ lit(y)
 
 
 def test_paper_node_and_edge_count():

@@ -57,6 +57,8 @@ def _load():
         lib.wl_csa_num_nodes.argtypes = [ctypes.c_int32]
         lib.wl_csa_generate.restype = ctypes.c_int64
         lib.wl_csa_generate.argtypes = [ctypes.c_int32, u8p, i32p, i32p, i32p]
+        lib.wl_csa_generate_labeled.restype = ctypes.c_int64
+        lib.wl_csa_generate_labeled.argtypes = [ctypes.c_int32, u8p, i32p, i32p, i32p, u8p]
         lib.wl_stress_rowptr.restype = ctypes.c_int64
         lib.wl_stress_rowptr.argtypes = [ctypes.c_uint64] + [ctypes.c_int64] * 4 + [i64p]
         lib.wl_stress_fill.restype = ctypes.c_int32
@@ -79,6 +81,7 @@ class Aig:
     fanin0: np.ndarray     # int32 [N1]
     fanin1: np.ndarray     # int32 [N1]
     po_driver: np.ndarray  # int32 [2n] literal driving each product bit m_k
+    label: np.ndarray      # uint8 [N1] the paper's node classes: 4 PI, 3 AND, 2 XOR, 1 MAJ, 0 PO
 
     @property
     def num_nodes(self) -> int:
@@ -92,11 +95,13 @@ def csa_multiplier_aig(n_bits: int) -> Aig:
     f0 = np.empty(n1, dtype=np.int32)
     f1 = np.empty(n1, dtype=np.int32)
     po = np.empty(2 * n_bits, dtype=np.int32)
-    got = lib.wl_csa_generate(n_bits, _ptr(typ, ctypes.c_uint8), _ptr(f0, ctypes.c_int32),
-                              _ptr(f1, ctypes.c_int32), _ptr(po, ctypes.c_int32))
+    label = np.empty(n1, dtype=np.uint8)
+    got = lib.wl_csa_generate_labeled(n_bits, _ptr(typ, ctypes.c_uint8), _ptr(f0, ctypes.c_int32),
+                                      _ptr(f1, ctypes.c_int32), _ptr(po, ctypes.c_int32),
+                                      _ptr(label, ctypes.c_uint8))
     if got != n1:
         raise RuntimeError(f"CSA generator wrote {got} nodes, expected {n1}")
-    return Aig(n_bits, typ, f0, f1, po)
+    return Aig(n_bits, typ, f0, f1, po, label)
 
 
 # ----------------------------------------------------------------------------

@@ -24,12 +24,16 @@
 
 enum { WL_PI = 0, WL_AND = 1, WL_PO = 2 };
 
+/* node classes of the paper's ground truth (Section "Node Features and Node Label creation") */
+enum { WL_LABEL_PO = 0, WL_LABEL_MAJ = 1, WL_LABEL_XOR = 2, WL_LABEL_AND = 3, WL_LABEL_PI = 4 };
+
 typedef struct {
     int n;
     int64_t next;          /* next free node id */
     uint8_t *type;
     int32_t *f0, *f1;
     int32_t *pp;           /* n*n memo of partial-product literals, -1 = not emitted */
+    uint8_t *label;        /* optional: class of every node */
 } gen_t;
 
 static int32_t lit_not(int32_t l) { return l ^ 1; }
@@ -40,7 +44,13 @@ static int32_t emit_and(gen_t *g, int32_t x, int32_t y)
     g->type[id] = WL_AND;
     g->f0[id] = x;
     g->f1[id] = y;
+    if (g->label) g->label[id] = WL_LABEL_AND;
     return (int32_t)(2 * id);
+}
+
+static void set_label(gen_t *g, int32_t lit, uint8_t label)
+{
+    if (g->label) g->label[lit >> 1] = label;
 }
 
 /* partial product a_j & b_i, emitted the first time it is used */
@@ -58,12 +68,16 @@ static int32_t emit_xor(gen_t *g, int32_t x, int32_t y, int32_t *carry)
     int32_t both = emit_and(g, x, y);
     int32_t none = emit_and(g, lit_not(x), lit_not(y));
     *carry = both;
-    return emit_and(g, lit_not(both), lit_not(none));
+    int32_t top = emit_and(g, lit_not(both), lit_not(none));
+    set_label(g, top, WL_LABEL_XOR);          /* the node with both inputs inverted is the xor root */
+    return top;
 }
 
 static int32_t half_adder(gen_t *g, int32_t x, int32_t y, int32_t *carry)
 {
-    return emit_xor(g, x, y, carry);
+    int32_t sum = emit_xor(g, x, y, carry);
+    set_label(g, *carry, WL_LABEL_MAJ);       /* x&y is the majority of (x, y, 0): the carry root */
+    return sum;
 }
 
 /* full adder: two xors (6 ANDs) plus one AND whose inverted output is the carry */
@@ -73,6 +87,7 @@ static int32_t full_adder(gen_t *g, int32_t x, int32_t y, int32_t z, int32_t *ca
     int32_t t1 = emit_xor(g, x, y, &g1);
     int32_t s = emit_xor(g, t1, z, &g2);
     int32_t k = emit_and(g, lit_not(g1), lit_not(g2));
+    set_label(g, k, WL_LABEL_MAJ);            /* !k = g1 | g2 = maj(x, y, z): the carry root */
     *carry = lit_not(k);
     return s;
 }
@@ -84,13 +99,24 @@ int64_t wl_csa_num_nodes(int32_t n) { return 8LL * n * n - 7LL * n; }
  * po_driver[2n] (the literal that drives each m_k).  Returns the number of
  * nodes written, or -1 on bad arguments / allocation failure.
  */
+int64_t wl_csa_generate_labeled(int32_t n, uint8_t *type, int32_t *fanin0, int32_t *fanin1,
+                                int32_t *po_driver, uint8_t *label);
+
 int64_t wl_csa_generate(int32_t n, uint8_t *type, int32_t *fanin0, int32_t *fanin1,
                         int32_t *po_driver)
+{
+    return wl_csa_generate_labeled(n, type, fanin0, fanin1, po_driver, NULL);
+}
+
+/* Same, and label[N1] (may be NULL) receives the class of every node:
+   4 = PI, 3 = plain AND, 2 = XOR root, 1 = MAJ (carry) root, 0 = PO. */
+int64_t wl_csa_generate_labeled(int32_t n, uint8_t *type, int32_t *fanin0, int32_t *fanin1,
+                                int32_t *po_driver, uint8_t *label)
 {
     if (n < 2 || n > 4096 || !type || !fanin0 || !fanin1) return -1;
     gen_t g;
     g.n = n;
-    g.type = type; g.f0 = fanin0; g.f1 = fanin1;
+    g.type = type; g.f0 = fanin0; g.f1 = fanin1; g.label = label;
     g.pp = (int32_t *)malloc(sizeof(int32_t) * (size_t)n * n);
     int32_t *s = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
     int32_t *c = (int32_t *)malloc(sizeof(int32_t) * (size_t)n);
@@ -98,7 +124,10 @@ int64_t wl_csa_generate(int32_t n, uint8_t *type, int32_t *fanin0, int32_t *fani
     if (!g.pp || !s || !c || !m) { free(g.pp); free(s); free(c); free(m); return -1; }
     for (size_t t = 0; t < (size_t)n * n; ++t) g.pp[t] = -1;
 
-    for (int v = 0; v < 2 * n; ++v) { type[v] = WL_PI; fanin0[v] = -1; fanin1[v] = -1; }
+    for (int v = 0; v < 2 * n; ++v) {
+        type[v] = WL_PI; fanin0[v] = -1; fanin1[v] = -1;
+        if (label) label[v] = WL_LABEL_PI;
+    }
     g.next = 2 * n;
 
     m[0] = pp(&g, 0, 0);
@@ -138,6 +167,7 @@ int64_t wl_csa_generate(int32_t n, uint8_t *type, int32_t *fanin0, int32_t *fani
         type[id] = WL_PO;
         fanin0[id] = m[k];
         fanin1[id] = m[k];
+        if (label) label[id] = WL_LABEL_PO;
         if (po_driver) po_driver[k] = m[k];
     }
     int64_t written = g.next;
