@@ -24,6 +24,8 @@ HBM_PEAK_GBPS = 8000.0
 # name -> (multiplier bits, batch copies, F, feature seed, degree threshold)
 WORKLOADS = {
     "csa1024_b16_F64": (1024, 16, 64, 3, 32),    # the headline graph: 134,103,040 nodes
+    "csa1024_b16_F32": (1024, 16, 32, 3, 32),    # embedding width of the paper's kernel evaluation
+    "csa1024_b16_F128": (1024, 16, 128, 3, 32),
     "csa1024_b1_F64": (1024, 1, 64, 2, 32),
     "csa256_b1_F64": (256, 1, 64, 1, 32),
     "csa32_b1_F32": (32, 1, 32, 0, 32),
