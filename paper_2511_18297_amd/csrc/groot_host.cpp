@@ -356,6 +356,12 @@ extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_thr
             }
             if (pieces > 1) slots += pieces;
         }
+        // Pieces run in the order of their first column: pieces of different rows that read the same
+        // stretch of feature rows (in an array multiplier: the a_j and b_i rows over the same partial
+        // products) then run close together, and the second reader finds the rows in the last-level cache.
+        std::stable_sort(pl->chunks.begin(), pl->chunks.end(), [&](const HdChunk &a, const HdChunk &b) {
+            return g->col[a.begin] < g->col[b.begin];
+        });
         pl->n_partials = slots;
         *out = pl.release();
         return GROOT_OK;
