@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
+    ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--hd-chunk", type=int, default=None)
     args = ap.parse_args()
@@ -85,6 +86,8 @@ def main():
     t0 = time.time()
     aig = wl.csa_multiplier_aig(bits)
     g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    if args.transposed:
+        g = G.groot_graph_transpose(g)
     view = G.groot_graph_view(g)
     n, nnz = view["n"], view["nnz"]
     plan = G.groot_spmm_plan(g, T)
@@ -153,6 +156,8 @@ def main():
 
         n1 = aig.num_nodes
         rp, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+        if args.transposed:
+            rp, col, val = oracle.csr_transpose(rp, col, val)
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         copies = min(batch, args.cpu_copies)
         run(G.GROOT_PHASE_ALL, 1)
@@ -185,14 +190,14 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": name, "multiplier_bits": bits, "batch": batch, "N": n, "nnz": nnz, "F": F,
+        "config": {"workload": name + ("_transposed" if args.transposed else ""), "multiplier_bits": bits, "batch": batch, "N": n, "nnz": nnz, "F": F,
                    "degree_threshold": T, "n_hd_rows": n_hd, "nnz_hd": nnz_hd,
                    "xcd_remap": args.xcd_remap if args.xcd_remap is not None else 1},
         "hbm_gbps": round(gbps, 1),
         "hbm_pct_of_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": bytes_all,
         "roofline": {"bound": "hbm", "kernel": "ld_kernel", "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": TRAFFIC.get(name),
+                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": None if args.transposed else TRAFFIC.get(name),
                      "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld},
         "hd_ms": round(ms_hd, 4),
         "finish_ms": round(ms_fin, 4),

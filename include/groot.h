@@ -85,6 +85,16 @@ groot_status groot_graph_build(int64_t n1, const uint8_t *type, const int32_t *f
 groot_status groot_graph_from_csr(int64_t n, const int64_t *rowptr, const int32_t *col,
                                   const float *val, groot_graph **out);
 
+/* groot_graph_transpose -- the graph of A_hat^T (host; a new graph owned by the
+ * caller).  The backward pass of a GNN layer multiplies by the transpose of the
+ * forward aggregation (the paper motivates its kernels by training time,
+ * Section "Accuracy and Accuracy Recovery of Various Multipliers"): plan and
+ * execute on the transposed graph give dX = A_hat^T dY with the same kernels.
+ * Entry (j,i) carries the weight of (i,j) as an explicit weight; rows list
+ * their columns ascending; no polarity bytes; the copy size of a batched
+ * graph is kept.  Errors: EINVAL (NULL), ENOMEM. */
+groot_status groot_graph_transpose(const groot_graph *g, groot_graph **out);
+
 /* Borrowed host pointers to the CSR; any output pointer may be NULL.  *pol is
  * set to NULL for graphs that did not come from an AIG. */
 groot_status groot_graph_view(const groot_graph *g, int64_t *n, int64_t *nnz,

@@ -52,6 +52,10 @@ def _load():
         lib.orc_csr_build.argtypes = [I64, _u8p, _i32p, _i32p, I32, U32, _i64p, _i32p, _f32p, _u8p]
         lib.orc_spmm_f64.restype = None
         lib.orc_spmm_f64.argtypes = [I64, _i64p, _i32p, _f32p, _f32p, I32, _f64p, _f64p]
+        lib.orc_spmm_t_f64.restype = None
+        lib.orc_spmm_t_f64.argtypes = [I64, _i64p, _i32p, _f32p, _f32p, I32, _f64p, _f64p]
+        lib.orc_csr_transpose.restype = None
+        lib.orc_csr_transpose.argtypes = [I64, _i64p, _i32p, _f32p, _i64p, _i32p, _f32p]
         lib.orc_plan.restype = I32
         lib.orc_plan.argtypes = [I64, _i64p, I32, _u8p, _i32p, _i32p, _i32p, _i64p, _i64p, _i64p]
         lib.orc_part_of_default.restype = None
@@ -114,6 +118,32 @@ def spmm_f64(rowptr, col, val, X, want_abs=True):
     lib.orc_spmm_f64(n, _p(rowptr, _i64p), _p(col, _i32p), _p(val, _f32p), _p(X, _f32p), F,
                      _p(Y, _f64p), _p(S, _f64p) if want_abs else None)
     return Y, S
+
+
+def spmm_t_f64(rowptr, col, val, G, want_abs=True):
+    """(A_hat^T G) by the scatter definition -> (fp64 [N,F], sum of |terms| or None)"""
+    lib = _load()
+    rowptr, col, val = _c(rowptr, np.int64), _c(col, np.int32), _c(val, np.float32)
+    G = _c(G, np.float32)
+    n, F = rowptr.shape[0] - 1, G.shape[1]
+    out = np.empty((n, F), dtype=np.float64)
+    S = np.empty((n, F), dtype=np.float64) if want_abs else None
+    lib.orc_spmm_t_f64(n, _p(rowptr, _i64p), _p(col, _i32p), _p(val, _f32p), _p(G, _f32p), F,
+                       _p(out, _f64p), _p(S, _f64p) if want_abs else None)
+    return out, S
+
+
+def csr_transpose(rowptr, col, val):
+    """A_hat^T as (rowptr, col, val)"""
+    lib = _load()
+    rowptr, col, val = _c(rowptr, np.int64), _c(col, np.int32), _c(val, np.float32)
+    n = rowptr.shape[0] - 1
+    t_rowptr = np.empty(n + 1, dtype=np.int64)
+    t_col = np.empty(col.shape[0], dtype=np.int32)
+    t_val = np.empty(col.shape[0], dtype=np.float32)
+    lib.orc_csr_transpose(n, _p(rowptr, _i64p), _p(col, _i32p), _p(val, _f32p), _p(t_rowptr, _i64p),
+                          _p(t_col, _i32p), _p(t_val, _f32p))
+    return t_rowptr, t_col, t_val
 
 
 def plan(rowptr, T):

@@ -11,6 +11,7 @@
  *   orc_aig_simulate      bit-parallel evaluation of an And-Inverter Graph
  *   orc_csr_nnz/_build    EDA-graph adjacency A, degree D, mean weights D^-1 A
  *   orc_spmm_f64          Y = A_hat * X row by row in fp64, plus sum of |terms|
+ *   orc_spmm_t_f64, orc_csr_transpose   transposed aggregation (backward pass)
  *   orc_plan              degree classes and the stable degree sort
  *   orc_part_of_default   level-contiguous partition rule
  *   orc_regrow_*          boundary sets, crossing edges, augmented sub-graphs
@@ -18,7 +19,8 @@
  * Pins (tests/, "not gpu"): the paper's two-bit multiplier example and its
  * printed node/edge counts; AIG simulation == integer product; closed-form
  * node/edge/degree counts; X = ones; dense brute force on <= 64 nodes;
- * hand-evaluated Eq. (1)-(2) sets on tiny graphs.
+ * hand-evaluated Eq. (1)-(2) sets on tiny graphs; dense transpose and the
+ * adjoint identity <A x, y> = <x, A^T y> for the transposed aggregation.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -334,4 +336,45 @@ int32_t orc_regrow_fill(int64_t n, const int64_t *rowptr, const int32_t *col, co
     }
     free(local_of);
     return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Transposed aggregation (the backward pass of a GNN layer applies the
+ * transpose of the forward aggregation; the paper motivates its kernels by
+ * training time, Section "Accuracy and Accuracy Recovery of Various
+ * Multipliers"):  (A_hat^T G)[j,k] = sum_i a_hat_ij * G[i,k].
+ * orc_spmm_t_f64 is that definition as a scatter over the rows of A_hat, in
+ * fp64, serially.  orc_csr_transpose writes A_hat^T as a CSR (entry (j,i)
+ * carries the weight of (i,j); rows of the result list i ascending).
+ * ------------------------------------------------------------------------ */
+void orc_spmm_t_f64(int64_t n, const int64_t *rowptr, const int32_t *col, const float *val,
+                    const float *G, int32_t F, double *out, double *S)
+{
+    for (int64_t t = 0; t < n * F; ++t) { out[t] = 0.0; if (S) S[t] = 0.0; }
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            const int64_t j = col[p];
+            for (int32_t k = 0; k < F; ++k) {
+                double term = (double)val[p] * (double)G[i * F + k];
+                out[j * F + k] += term;
+                if (S) S[j * F + k] += fabs(term);
+            }
+        }
+}
+
+void orc_csr_transpose(int64_t n, const int64_t *rowptr, const int32_t *col, const float *val,
+                       int64_t *t_rowptr, int32_t *t_col, float *t_val)
+{
+    for (int64_t j = 0; j <= n; ++j) t_rowptr[j] = 0;
+    for (int64_t p = 0; p < rowptr[n]; ++p) t_rowptr[col[p] + 1] += 1;
+    for (int64_t j = 0; j < n; ++j) t_rowptr[j + 1] += t_rowptr[j];
+    int64_t *cursor = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n + 1));
+    for (int64_t j = 0; j < n; ++j) cursor[j] = t_rowptr[j];
+    for (int64_t i = 0; i < n; ++i)                        /* i ascending => each result row ascending */
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            int64_t q = cursor[col[p]]++;
+            t_col[q] = (int32_t)i;
+            t_val[q] = val[p];
+        }
+    free(cursor);
 }

@@ -22,7 +22,7 @@ GROOT_REGROW = 1
 GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 
 EXPORTS = [
-    "groot_graph_build", "groot_graph_from_csr", "groot_graph_view", "groot_graph_free",
+    "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
     "groot_spmm_execute_phases", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
@@ -48,6 +48,7 @@ _pi64 = ctypes.POINTER(ctypes.c_int64)
 
 _lib.groot_graph_build.argtypes = [_i64, _vp, _vp, _vp, _i32, _u32, _pp]
 _lib.groot_graph_from_csr.argtypes = [_i64, _vp, _vp, _vp, _pp]
+_lib.groot_graph_transpose.argtypes = [_vp, _pp]
 _lib.groot_graph_view.argtypes = [_vp, _pi64, _pi64, _pp, _pp, _pp, _pp]
 _lib.groot_graph_free.argtypes = [_vp]
 _lib.groot_graph_free.restype = None
@@ -157,6 +158,12 @@ def groot_graph_from_csr(rowptr, col, val) -> Graph:
     n = 0 if r is None else r.shape[0] - 1
     out = ctypes.c_void_p()
     _check(_lib.groot_graph_from_csr(n, rp, cp, vp, ctypes.byref(out)))
+    return Graph(out.value)
+
+
+def groot_graph_transpose(g: Graph) -> Graph:
+    out = ctypes.c_void_p()
+    _check(_lib.groot_graph_transpose(g.handle, ctypes.byref(out)))
     return Graph(out.value)
 
 

@@ -280,6 +280,36 @@ extern "C" groot_status groot_graph_from_csr(int64_t n, const int64_t *rowptr, c
     }
 }
 
+extern "C" groot_status groot_graph_transpose(const groot_graph *g, groot_graph **out)
+{
+    if (!g || !out) return fail(GROOT_EINVAL, "groot_graph_transpose: NULL argument");
+    try {
+        std::unique_ptr<groot_graph> t(new groot_graph);
+        const int64_t n = g->n;
+        t->n = n;
+        t->n1 = g->n1;
+        t->nnz = g->nnz;
+        t->weight_mode = WeightMode::Explicit;
+        t->rowptr.assign(n + 1, 0);
+        t->col.resize(g->nnz);
+        t->val.resize(g->nnz);
+        for (int64_t p = 0; p < g->nnz; ++p) ++t->rowptr[g->col[p] + 1];
+        for (int64_t j = 0; j < n; ++j) t->rowptr[j + 1] += t->rowptr[j];
+        std::vector<int64_t> cursor(t->rowptr.begin(), t->rowptr.end() - 1);
+        // rows of g are visited in ascending order, so every row of the transpose fills in ascending column order
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t p = g->rowptr[i]; p < g->rowptr[i + 1]; ++p) {
+                const int64_t q = cursor[g->col[p]]++;
+                t->col[q] = (int32_t)i;
+                t->val[q] = g->val[p];
+            }
+        *out = t.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, "groot_graph_transpose: out of host memory");
+    }
+}
+
 extern "C" groot_status groot_graph_view(const groot_graph *g, int64_t *n, int64_t *nnz,
                                          const int64_t **rowptr, const int32_t **col, const float **val,
                                          const uint8_t **pol)

@@ -142,6 +142,24 @@ def test_stress_graph_threshold_sweep(torch_cuda, T):
     assert_close_to_oracle(Y, Y64, S, f"stress T={T}")
 
 
+@pytest.mark.parametrize("case", ["aig", "stress"])
+def test_transposed_spmm(torch_cuda, case):
+    """dX = A_hat^T dY through groot_graph_transpose + the ordinary plan/execute, against the oracle's
+    scatter definition of the transposed product."""
+    if case == "aig":
+        aig, g, (rowptr, col, val, pol) = _aig_case(48, 2)
+        n, T, F = 2 * aig.num_nodes, 32, 64
+    else:
+        s = wl.stress_graph(7, 1 << 15, window=1024, dmin=64, dmax=4096)
+        g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+        rowptr, col, val, n, T, F = s.rowptr, s.col, s.val, s.n, 32, 32
+    dY = wl.uniform_features_numpy(13, 0, n, F)
+    gt = G.groot_graph_transpose(g)
+    dX, _, _, _ = _run(torch_cuda, gt, T, dY)
+    want, S = oracle.spmm_t_f64(rowptr, col, val, dY)
+    assert_close_to_oracle(dX, want, S, f"transposed {case}")
+
+
 def test_tuning_knobs_do_not_change_results(torch_cuda):
     aig, g, (rowptr, col, val, pol) = _aig_case(64, 2)
     X = wl.uniform_features_numpy(8, 0, 2 * aig.num_nodes, 64)

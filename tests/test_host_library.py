@@ -101,6 +101,24 @@ def test_from_csr_roundtrip_and_checks():
         G.groot_graph_from_csr(rp, g0.col, g0.val)
 
 
+@pytest.mark.parametrize("case", ["aig", "aig_directed", "stress"])
+def test_graph_transpose_bit_exact(case):
+    if case == "stress":
+        s = wl.stress_graph(2, 1 << 12, window=64, dmin=64, dmax=512)
+        g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+        rowptr, col, val = s.rowptr, s.col, s.val
+    else:
+        aig = wl.csa_multiplier_aig(16)
+        flags = 7 if case == "aig" else 4
+        g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 2, flags)
+        rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 2, flags)
+    t = G.groot_graph_view(G.groot_graph_transpose(g))
+    want = oracle.csr_transpose(rowptr, col, val)
+    assert np.array_equal(t["rowptr"], want[0]) and np.array_equal(t["col"], want[1])
+    assert np.array_equal(t["val"].view(np.uint32), want[2].view(np.uint32)) and t["pol"] is None
+    assert G.binding._lib.groot_graph_transpose(None, None) == G.GROOT_EINVAL
+
+
 @pytest.mark.parametrize("n,batch,T", [(8, 1, 7), (8, 3, 9), (32, 1, 32), (32, 2, 33), (32, 1, 34), (32, 1, 1),
                                        (64, 1, 4), (64, 1, 6), (256, 1, 32)])
 def test_plan_bit_exact(n, batch, T):

@@ -334,3 +334,42 @@ def test_sage_forward_reduces_to_spmm():
     assert np.array_equal(H1, Y1.astype(np.float32)) and np.allclose(H2, Y2, atol=1e-15)
     H1s, H2s = oracle.sage_forward_f64(rowptr, col, val, X, Z, I, z, Z, I, z + 1)
     assert np.array_equal(H1s, X) and np.allclose(H2s, X.astype(np.float64) + 1)
+
+
+# ---------------------------------------------------------- transposed SpMM
+@pytest.mark.parametrize("n,flags", [(2, 7), (3, 7), (3, 0), (3, 4)])
+def test_transposed_spmm_equals_dense_transpose(n, flags):
+    aig, (rowptr, col, val, pol) = _csr(n, 1, flags)
+    A = oracle.dense_adjacency(rowptr, col, val)
+    Gm = wl.uniform_features_numpy(21, 0, aig.num_nodes, 6)
+    out, S = oracle.spmm_t_f64(rowptr, col, val, Gm)
+    assert np.allclose(out, A.T @ Gm.astype(np.float64), rtol=0, atol=1e-15)
+    assert np.allclose(S, np.abs(A.T) @ np.abs(Gm.astype(np.float64)), rtol=0, atol=1e-15)
+    t_rowptr, t_col, t_val = oracle.csr_transpose(rowptr, col, val)
+    assert np.array_equal(oracle.dense_adjacency(t_rowptr, t_col, t_val), A.T)
+    for j in range(aig.num_nodes):
+        assert (np.diff(t_col[t_rowptr[j]:t_rowptr[j + 1]]) > 0).all()
+    # forward product with the transposed matrix adds the same terms in the same order
+    fwd, fS = oracle.spmm_f64(t_rowptr, t_col, t_val, Gm)
+    assert np.array_equal(fwd, out) and np.array_equal(fS, S)
+
+
+def test_transposed_spmm_adjoint_identity():
+    """<A x, y> = <x, A^T y> ties the transposed product to the (separately pinned) forward product."""
+    for graph in ("aig", "stress"):
+        if graph == "aig":
+            aig, (rowptr, col, val, pol) = _csr(16, 2)
+            n = 2 * aig.num_nodes
+        else:
+            g = wl.stress_graph(8, 1 << 13, window=128, dmin=64, dmax=1024)
+            rowptr, col, val, n = g.rowptr, g.col, g.val, g.n
+        x = wl.uniform_features_numpy(31, 0, n, 3)
+        y = wl.uniform_features_numpy(32, 0, n, 3)
+        Ax, _ = oracle.spmm_f64(rowptr, col, val, x)
+        Aty, _ = oracle.spmm_t_f64(rowptr, col, val, y)
+        lhs, rhs = float((Ax * y).sum()), float((x.astype(np.float64) * Aty).sum())
+        assert abs(lhs - rhs) <= 1e-9 * max(1.0, abs(lhs))
+        # transposing twice gives the matrix back
+        t = oracle.csr_transpose(rowptr, col, val)
+        tt = oracle.csr_transpose(*t)
+        assert np.array_equal(tt[0], rowptr) and np.array_equal(tt[1], col) and np.array_equal(tt[2], val)

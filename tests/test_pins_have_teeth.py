@@ -33,6 +33,8 @@ MUTATIONS = [
     ("crossing counted from one side only", "if (!i_owned && j_owned && !has_entry(rowptr, col, j, i)) ++cross;", ""),
     ("AND evaluated as OR", "(type[v] == 1) ? (w0 & w1) : w0", "(type[v] == 1) ? (w0 | w1) : w0"),
     ("inverter ignored", "word[l1 >> 1] ^ ((l1 & 1) ? ~0ULL : 0ULL)", "word[l1 >> 1]"),
+    ("transposed product scatters to the row", "out[j * F + k] += term;", "out[i * F + k] += term;"),
+    ("transpose keeps the weight of another entry", "t_val[q] = val[p];", "t_val[q] = val[q];"),
     ("partition rule rounds up", "int64_t q = ((v % n1) * P) / n1;", "int64_t q = ((v % n1) * P + n1 - 1) / n1;"),
 ]
 
@@ -49,6 +51,8 @@ PIN_CALLS = [
     lambda: [pins.test_regrow_on_multipliers(*a) for a in ((2, 2), (3, 3), (4, 3))],
     lambda: pins.test_regrow_one_way_edges_and_weight_modes(),
     lambda: pins.test_partition_rule_closed_form(),
+    lambda: [pins.test_transposed_spmm_equals_dense_transpose(n, 7) for n in (2, 3)],
+    lambda: pins.test_transposed_spmm_adjoint_identity(),
     lambda: wpins.test_two_bit_example_matches_paper(),
     lambda: wpins.test_multiplier_function_equals_integer_product(5),
 ]
