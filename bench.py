@@ -42,6 +42,55 @@ def algorithmic_bytes(n, nnz, F):
     return 8 * (n + 1) + 4 * nnz + 4 * nnz + 4 * n * F + 4 * n * F
 
 
+def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props):
+    """Fused layer against the unfused form (library SpMM, then torch for the dense part)."""
+    assert F == 64, "the fused layer is built for F = 64"
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    Wn, Ws = ((torch.rand((F, F), generator=gen, device="cuda") - 0.5) * 0.25 for _ in range(2))
+    b = (torch.rand(F, generator=gen, device="cuda") - 0.5) * 0.25
+    H = torch.empty_like(X)
+
+    def fused():
+        G.groot_sage_layer_forward(plan, X, Wn, Ws, b, True, H, F)
+
+    def unfused():
+        G.groot_spmm_execute(plan, X, Y, F)
+        out = torch.addmm(b, Y, Wn)
+        out.addmm_(X, Ws)
+        return torch.relu_(out)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms_fused = timed(fused, args.steps, args.warmup)
+    ms_unfused = timed(unfused, max(3, args.steps // 4), 1)
+    ref = unfused()
+    fused()
+    torch.cuda.synchronize()
+    worst = 0.0
+    for lo in range(0, n, 1 << 24):
+        worst = max(worst, float((H[lo:lo + (1 << 24)] - ref[lo:lo + (1 << 24)]).abs().max()))
+    flops = 2.0 * nnz * F + 2.0 * n * (2 * F) * F
+    tflops = flops / (ms_fused * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "GraphSAGE-mean layer forward H = relu((A_hat X) Wn + X Ws + b), fused, 1024-bit CSA AIG, F=64",
+        "value": round(tflops * 1e3, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_fused, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name + "_sage_layer", "batch": batch, "N": n, "nnz": nnz, "F": F},
+        "roofline": {"bound": "mfma", "kernel": "sage_kernel (+ hd_kernel)", "achieved": round(tflops, 2),
+                     "peak": 157.3, "unit": "TFLOP/s", "frac": round(tflops / 157.3, 4), "traffic": None},
+        "unfused_ms_per_step": round(ms_unfused, 4), "speedup_vs_unfused": round(ms_unfused / ms_fused, 3),
+        "max_abs_diff_vs_unfused": worst, "device": props.name}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,6 +100,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
+    ap.add_argument("--sage-layer", action="store_true",
+                    help="time the fused GraphSAGE-mean layer H = relu((A_hat X) Wn + X Ws + b) instead (F = 64)")
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--hd-chunk", type=int, default=None)
     args = ap.parse_args()
@@ -103,6 +154,10 @@ def main():
     def run(phases, count):
         for _ in range(count):
             G.groot_spmm_execute_phases(plan, X, Y, F, phases)
+
+    if args.sage_layer:
+        sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props)
+        return
 
     # ---- whole path: W warm-up steps, then exactly K timed steps
     run(G.GROOT_PHASE_ALL, args.warmup)

@@ -149,6 +149,23 @@ groot_status groot_spmm_execute(const groot_plan *plan, const float *X_dev, floa
                                 int32_t F, void *hip_stream);
 groot_status groot_spmm_execute_phases(const groot_plan *plan, const float *X_dev, float *Y_dev,
                                        int32_t F, uint32_t phases, void *hip_stream);
+/* ---------------------------------------------------------------------------
+ * groot_sage_layer_forward -- one GraphSAGE-mean layer with the aggregation fused in:
+ *     H = act( (A_hat X) Wn + X Ws + b ),   act = ReLU if relu != 0, identity otherwise.
+ * Paper: Section "GNN and Edge Re-growth After Partition" (the GraphSAGE layer takes
+ * the graph with node features and aggregates them; the aggregation is the product
+ * the paper's kernels compute).  The aggregated rows stay on chip and feed the dense
+ * products on the matrix cores, so A_hat X is neither written nor re-read.
+ * X_dev, H_dev (device): row-major [N,F] fp32, 16-byte aligned, not overlapping.
+ * Wn_dev, Ws_dev (device): row-major [F,F] fp32 (input feature major: H = X W);
+ * bias_dev: [F] fp32 or NULL.  F must be 64 (input = output width).  fp32 throughout.
+ * The plan must be uploaded with max_F >= 64.  Only enqueues on hip_stream; one
+ * call per plan in flight.  Errors: EINVAL (NULL, alignment, F != 64, plan not
+ * uploaded), EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
+                                      const float *Ws_dev, const float *bias_dev, int32_t relu,
+                                      float *H_dev, int32_t F, void *hip_stream);
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------

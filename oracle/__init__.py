@@ -205,6 +205,16 @@ def dense_adjacency(rowptr, col, val):
     return A
 
 
+def sage_layer_f64(rowptr, col, val, X, Wn, Ws, b, relu):
+    """One GraphSAGE-mean layer in fp64: act((A_hat X) Wn + X Ws + b); also returns A_hat X and its
+    sum of absolute terms (for the error scale)."""
+    A, S = spmm_f64(rowptr, col, val, X)
+    H = A @ Wn.astype(np.float64) + np.asarray(X, dtype=np.float64) @ Ws.astype(np.float64)
+    if b is not None:
+        H = H + b.astype(np.float64)
+    return (np.maximum(H, 0.0) if relu else H), A, S
+
+
 def sage_forward_f64(rowptr, col, val, X, W1n, W1s, b1, W2n, W2s, b2):
     """Two GraphSAGE-mean layers (Section "GNN and Edge Re-growth After
     Partition": the layer aggregates neighbour features, then transforms):

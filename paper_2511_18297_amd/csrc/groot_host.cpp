@@ -515,6 +515,29 @@ extern "C" groot_status groot_spmm_execute(const groot_plan *plan, const float *
     return groot_spmm_execute_phases(plan, X_dev, Y_dev, F, GROOT_PHASE_ALL, hip_stream);
 }
 
+extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
+                                                 const float *Ws_dev, const float *bias_dev, int32_t relu,
+                                                 float *H_dev, int32_t F, void *hip_stream)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL plan");
+    if (F != 64) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F must be 64");
+    groot_status st = check_features("groot_sage_layer_forward", X_dev, H_dev, F);
+    if (st != GROOT_OK) return st;
+    if (!Wn_dev || !Ws_dev) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL weight pointer");
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_sage_layer_forward: plan is not on the device (call groot_plan_upload)");
+    if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F exceeds the max_F given to groot_plan_upload");
+    const char *a = (const char *)X_dev, *b = (const char *)H_dev;
+    const int64_t bytes = plan->dev.n * (int64_t)F * 4;
+    if (a < b + bytes && b < a + bytes) return fail(GROOT_EINVAL, "groot_sage_layer_forward: X and H overlap");
+    // high-degree rows: their aggregation goes to H first, the layer kernel picks it up from there
+    int err = 0;
+    if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F, hip_stream);
+    if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, H_dev, F, hip_stream);
+    if (!err) err = launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_sage_layer_forward: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" void groot_plan_free(groot_plan *plan)
 {
     if (!plan) return;

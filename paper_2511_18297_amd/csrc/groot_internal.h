@@ -63,6 +63,8 @@ constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
 int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
 int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream);
+int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
+                int relu, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
 int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
 const char *hip_error_text(int err);

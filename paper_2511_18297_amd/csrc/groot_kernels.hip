@@ -6,41 +6,9 @@
 // a "lane group" of L lanes (L = smallest power of two >= F/4, at most 64), so
 // one wavefront works on 64/L rows at a time and every load/store of a group
 // is one contiguous F*4-byte segment.
-#include <hip/hip_runtime.h>
-
-#include "groot_internal.h"
+#include "groot_device.h"
 
 namespace groot {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
-
-constexpr int kWave = 64;
-constexpr int kBlock = 256;                  // threads per workgroup (4 wavefronts)
-constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kLdTileRows = 64;              // consecutive rows per wavefront tile
-constexpr int kLdTileCap = 512;              // non-zeros of a tile that are staged in LDS
-constexpr int kXcds = 8;                     // workgroups are dealt round-robin over 8 XCDs
-
-// Each XCD has its own L2.  Consecutive hardware workgroup ids land on
-// different XCDs, so the logical block index is transposed: XCD x walks the
-// x-th contiguous eighth of the tiles in ascending order.
-__device__ __forceinline__ int64_t logical_block(int64_t blocks_per_xcd, int remap)
-{
-    int64_t b = blockIdx.x;
-    return remap ? (b % kXcds) * blocks_per_xcd + b / kXcds : b;
-}
-
-// Weight of the entries of a row: kExplicit reads val[]; kMean and kOnes are
-// the row-uniform weights of graphs built from an AIG and need no weight array
-// (1/row length is recomputed in registers, correctly rounded, from the row
-// pointer; this saves 4 bytes of HBM traffic per non-zero).
-enum : int { kOnes = (int)WeightMode::Ones, kMean = (int)WeightMode::Mean, kExplicit = (int)WeightMode::Explicit };
-
-template <int W>
-__device__ __forceinline__ float row_weight(int64_t row_nnz)
-{
-    return W == kMean ? (row_nnz > 0 ? 1.0f / (float)row_nnz : 0.0f) : 1.0f;
-}
 
 // ---------------------------------------------------------------------------
 // LD part.  A wavefront owns 64 consecutive rows.  When none of them is
@@ -52,34 +20,6 @@ __device__ __forceinline__ float row_weight(int64_t row_nnz)
 // store G consecutive rows, i.e. one contiguous G*F*4-byte area per store.
 // High-degree rows are skipped (HD pieces write them).
 // ---------------------------------------------------------------------------
-template <int W, bool kStaged>
-__device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *__restrict__ cols,
-                                          const float *__restrict__ vals, const v4f *__restrict__ X,
-                                          int32_t F4, int32_t ff)
-{
-    v4f acc = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = s; p < e; p += 8) {
-        v4f x[8];
-        float w[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            if (p + k < e) {
-                int32_t c = kStaged ? cols[p + k] : __builtin_nontemporal_load(&cols[p + k]);
-                if (W == kExplicit) w[k] = kStaged ? vals[p + k] : __builtin_nontemporal_load(&vals[p + k]);
-                x[k] = X[(int64_t)c * F4 + ff];
-            }
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            if (p + k < e) {
-                if (W == kExplicit) acc += w[k] * x[k];
-                else acc += x[k];
-            }
-    }
-    if (W != kExplicit) acc *= row_weight<W>(e - s);
-    return acc;
-}
-
 constexpr int kLdsBytes = kWavesPerBlock * (2 * kLdTileCap + kLdTileRows + 1) * 4;
 
 template <int L, int W>
@@ -267,31 +207,12 @@ static int lanes_for(int32_t F4)
     return L;
 }
 
-#define GROOT_DISPATCH_L(L, CALL)        \
-    switch (L) {                         \
-    case 1: { constexpr int kL = 1; CALL; } break;   \
-    case 2: { constexpr int kL = 2; CALL; } break;   \
-    case 4: { constexpr int kL = 4; CALL; } break;   \
-    case 8: { constexpr int kL = 8; CALL; } break;   \
-    case 16: { constexpr int kL = 16; CALL; } break; \
-    case 32: { constexpr int kL = 32; CALL; } break; \
-    default: { constexpr int kL = 64; CALL; } break; \
-    }
-
-static bool grid_ok(int64_t blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
-
 #define GROOT_DISPATCH_LW(L, W, CALL)                                  \
     switch (W) {                                                       \
     case kOnes: { constexpr int kW = kOnes; GROOT_DISPATCH_L(L, CALL) } break; \
     case kMean: { constexpr int kW = kMean; GROOT_DISPATCH_L(L, CALL) } break; \
     default: { constexpr int kW = kExplicit; GROOT_DISPATCH_L(L, CALL) } break; \
     }
-
-static bool weights_ok(const DevicePlan &dp)
-{
-    // explicit weights need the weight array on the device; the other modes never touch it
-    return dp.weight_mode == kOnes || dp.weight_mode == kMean || dp.val != nullptr || dp.nnz == 0;
-}
 
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
 {

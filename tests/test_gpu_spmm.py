@@ -160,6 +160,62 @@ def test_transposed_spmm(torch_cuda, case):
     assert_close_to_oracle(dX, want, S, f"transposed {case}")
 
 
+def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what):
+    F = 64
+    rng = np.random.default_rng(seed)
+    X = wl.uniform_features_numpy(seed, 0, n, F)
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
+    b = rng.uniform(-0.125, 0.125, F).astype(np.float32) if with_bias else None
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    guard = 2
+    buf = torch.full((n + 2 * guard, F), float("nan"), dtype=torch.float32, device="cuda")
+    buf[:guard] = 777.0
+    buf[n + guard:] = 777.0
+    H = buf[guard:n + guard]
+    G.groot_sage_layer_forward(plan, dev(X), dev(Wn), dev(Ws), None if b is None else dev(b), relu, H, F)
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert (out[:guard] == 777.0).all() and (out[n + guard:] == 777.0).all(), "wrote outside H"
+    want, A, S = oracle.sage_layer_f64(rowptr, col, val, X, Wn, Ws, b, relu)
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale = np.abs(A) @ a64(Wn) + a64(X) @ a64(Ws) + (a64(b) if b is not None else 0.0)
+    # SpMM tolerance pushed through |Wn|, plus fp32 dot products of length 128 on the matrix cores
+    tol = (1e-5 * S + 1e-6) @ a64(Wn) + 2e-5 * scale + 1e-6
+    err = np.abs(out[guard:n + guard].astype(np.float64) - want)
+    assert np.isfinite(err).all(), f"{what}: non-finite output"
+    assert (err <= tol).all(), f"{what}: max err/tol {np.max(err / tol)}"
+
+
+@pytest.mark.parametrize("n_bits,batch,T,relu,with_bias", [(48, 2, 32, True, True), (48, 1, 32, False, False),
+                                                            (3, 1, 32, True, True), (17, 3, 5, True, False),
+                                                            (40, 1, 1, False, True)])
+def test_fused_sage_layer_on_multipliers(torch_cuda, n_bits, batch, T, relu, with_bias):
+    """H = act((A_hat X) Wn + X Ws + b) with the aggregation kept on chip; rows counts that are not
+    multiples of the 64-row tile, high-degree rows (picked up from the HD kernel), every row high-degree."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    _sage_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 100 + n_bits, relu, with_bias,
+                f"sage {n_bits}x{batch} T={T}")
+
+
+def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda):
+    torch = torch_cuda
+    s = wl.stress_graph(11, 1 << 14, window=512, dmin=64, dmax=2048)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    _sage_check(torch, g, s.rowptr, s.col, s.val, 32, s.n, 5, True, True, "sage stress")
+    plan = G.groot_spmm_plan(g, 32)
+    z = lambda *shape: torch.zeros(*shape, device="cuda")
+    with pytest.raises(G.GrootError):                       # not uploaded
+        G.groot_sage_layer_forward(plan, z(s.n, 64), z(64, 64), z(64, 64), None, True, z(s.n, 64), 64)
+    G.groot_plan_upload(plan, 64)
+    with pytest.raises(G.GrootError):                       # only F = 64
+        G.groot_sage_layer_forward(plan, z(s.n, 32), z(32, 32), z(32, 32), None, True, z(s.n, 32), 32)
+    x = z(s.n, 64)
+    with pytest.raises(G.GrootError):                       # in place
+        G.groot_sage_layer_forward(plan, x, z(64, 64), z(64, 64), None, True, x, 64)
+
+
 def test_tuning_knobs_do_not_change_results(torch_cuda):
     aig, g, (rowptr, col, val, pol) = _aig_case(64, 2)
     X = wl.uniform_features_numpy(8, 0, 2 * aig.num_nodes, 64)
