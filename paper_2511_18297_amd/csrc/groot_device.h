@@ -37,20 +37,20 @@ __device__ __forceinline__ float row_weight(int64_t row_nnz)
     return W == kMean ? (row_nnz > 0 ? 1.0f / (float)row_nnz : 0.0f) : 1.0f;
 }
 
-// Sum of one row for one float4 slice: the feature slices of up to 8 neighbours are gathered
+// Sum of one row for one float4 slice: the feature slices of up to D neighbours are gathered
 // before the first add (kStaged: indices/weights come from the tile's copy in LDS, else from
 // global memory), accumulated in registers in CSR order, and scaled by the row weight.
-template <int W, bool kStaged>
+template <int W, bool kStaged, int D = 8>
 __device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *__restrict__ cols,
                                           const float *__restrict__ vals, const v4f *__restrict__ X,
                                           int32_t F4, int32_t ff)
 {
     v4f acc = {0.f, 0.f, 0.f, 0.f};
-    for (int64_t p = s; p < e; p += 8) {
-        v4f x[8];
-        float w[8];
+    for (int64_t p = s; p < e; p += D) {
+        v4f x[D];
+        float w[D];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < D; ++k) {
             if (p + k < e) {
                 int32_t c = kStaged ? cols[p + k] : __builtin_nontemporal_load(&cols[p + k]);
                 if (W == kExplicit) w[k] = kStaged ? vals[p + k] : __builtin_nontemporal_load(&vals[p + k]);
@@ -58,7 +58,7 @@ __device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *_
             }
         }
 #pragma unroll
-        for (int k = 0; k < 8; ++k)
+        for (int k = 0; k < D; ++k)
             if (p + k < e) {
                 if (W == kExplicit) acc += w[k] * x[k];
                 else acc += x[k];

@@ -22,8 +22,10 @@ constexpr int kSgAStride = 132;             // floats per LDS row of [agg | self
 constexpr int kSgOStride = 68;              // floats per LDS row of the output tile
 constexpr int kSgCap = 128;                 // staged non-zeros per wavefront (16 rows)
 
+// Held to 128 registers (4 wavefronts per SIMD, i.e. 4 resident workgroups per CU): the aggregation phase of
+// one workgroup overlaps the matrix phase of the others.
 template <int W>
-__global__ __launch_bounds__(kBlock) void sage_kernel(const int64_t *__restrict__ rowptr,
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void sage_kernel(const int64_t *__restrict__ rowptr,
                                                       const int32_t *__restrict__ col,
                                                       const float *__restrict__ val,
                                                       const v4f *__restrict__ X, v4f *H,
@@ -55,25 +57,44 @@ __global__ __launch_bounds__(kBlock) void sage_kernel(const int64_t *__restrict_
     const int64_t tile_begin = lw * tiles_per_wg;
     const int64_t tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
 
+    // The row pointers and column indices of a tile are fetched one tile ahead and wait in registers
+    // while the previous tile is aggregated and multiplied: two dependent memory latencies leave the
+    // critical path of every tile.
+    int64_t rp = 0, t_begin = 0;
+    int32_t m = 0, c0 = 0, c1 = 0;
+    float v0 = 0.f, v1 = 0.f;
+    bool staged = false;
+    auto fetch_csr = [&](int64_t tile) {
+        const int64_t ri = tile * kSgRows + 16 * w + (l < 16 ? l : 16);
+        rp = rowptr[ri < n ? ri : n];
+        t_begin = __shfl(rp, 0);
+        const int64_t t_end = __shfl(rp, 16), rp_next = __shfl_down(rp, 1);
+        const bool any_hd = __ballot(l < 16 && rp_next - rp >= T) != 0;
+        staged = !any_hd && (t_end - t_begin) <= kSgCap;
+        m = staged ? (int32_t)(t_end - t_begin) : 0;
+        if (l < m) {
+            c0 = __builtin_nontemporal_load(&col[t_begin + l]);
+            if (W == kExplicit) v0 = __builtin_nontemporal_load(&val[t_begin + l]);
+        }
+        if (l + kWave < m) {
+            c1 = __builtin_nontemporal_load(&col[t_begin + kWave + l]);
+            if (W == kExplicit) v1 = __builtin_nontemporal_load(&val[t_begin + kWave + l]);
+        }
+    };
+    if (tile_begin < tile_end) fetch_csr(tile_begin);
+
     for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
         const int64_t base = tile * kSgRows;
         const int64_t wbase = base + 16 * w;              // first of this wavefront's 16 rows
         // ---- aggregation: 16 rows per wavefront, 4 at a time
-        const int64_t ri = wbase + (l < 16 ? l : 16);
-        const int64_t rp = rowptr[ri < n ? ri : n];
-        const int64_t t_begin = __shfl(rp, 0), t_end = __shfl(rp, 16);
-        const int64_t rp_next = __shfl_down(rp, 1);
-        const bool any_hd = __ballot(l < 16 && rp_next - rp >= T) != 0;
-        const bool staged = !any_hd && (t_end - t_begin) <= kSgCap;
-        if (staged) {
+        const bool staged_now = staged;
+        if (staged_now) {
             if (l < 17) s_rel[w][l] = (int32_t)(rp - t_begin);
-            const int m = (int)(t_end - t_begin);
-            for (int p = l; p < m; p += kWave) {
-                s_col[w][p] = __builtin_nontemporal_load(&col[t_begin + p]);
-                if (W == kExplicit) s_val[w][p] = __builtin_nontemporal_load(&val[t_begin + p]);
-            }
+            if (l < m) { s_col[w][l] = c0; if (W == kExplicit) s_val[w][l] = v0; }
+            if (l + kWave < m) { s_col[w][l + kWave] = c1; if (W == kExplicit) s_val[w][l + kWave] = v1; }
         }
         __syncthreads();
+        if (tile + 1 < tile_end) fetch_csr(tile + 1);     // lands while this tile is being worked on
 #pragma unroll 1
         for (int it = 0; it < 4; ++it) {
             const int lr = it * 4 + g;
@@ -81,12 +102,12 @@ __global__ __launch_bounds__(kBlock) void sage_kernel(const int64_t *__restrict_
             v4f agg = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
             if (row < n) {
                 self = X[row * kSgF4 + f];
-                if (staged) {
-                    agg = ld_row_sum<W, true>(s_rel[w][lr], s_rel[w][lr + 1], s_col[w], s_val[w], X, kSgF4, f);
+                if (staged_now) {
+                    agg = ld_row_sum<W, true, 6>(s_rel[w][lr], s_rel[w][lr + 1], s_col[w], s_val[w], X, kSgF4, f);
                 } else {
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
                     if (e - s >= T) agg = H[row * kSgF4 + f];       // aggregated by the HD kernel
-                    else agg = ld_row_sum<W, false>(s, e, col, val, X, kSgF4, f);
+                    else agg = ld_row_sum<W, false, 6>(s, e, col, val, X, kSgF4, f);
                 }
             }
             float *dst = &s_A[(16 * w + lr) * kSgAStride + 4 * f];
