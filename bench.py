@@ -42,6 +42,67 @@ def algorithmic_bytes(n, nnz, F):
     return 8 * (n + 1) + 4 * nnz + 4 * nnz + 4 * n * F + 4 * n * F
 
 
+def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props):
+    """Partitioned mode (Algorithm 1 of the paper): per part, gather the rows of S_p+ , aggregate on the
+    sub-graph, scatter the owned rows back.  Reports the time of one pass over all parts with every
+    sub-plan resident, and the device footprint one part needs when parts are processed one at a time."""
+    P = args.partitioned
+    t0 = time.time()
+    parts = G.groot_partition_regrow(g, P)
+    t_partition = time.time() - t0
+    items, foot, cross = [], [], 0
+    for p in range(P):
+        pv = G.groot_parts_view(parts, p)
+        sub = G.groot_graph_view(pv["sub"])
+        ids = torch.from_numpy(pv["global_id"].copy()).cuda()
+        plan = G.groot_spmm_plan(pv["sub"], T)
+        G.groot_plan_upload(plan, F)
+        n_loc = ids.shape[0]
+        items.append((plan, ids, pv["n_owned"], n_loc))
+        cross += pv["n_crossing"]
+        # rowptr + col (mean weights are not stored on the device) + ids + X_p + Y_p
+        foot.append(8 * (n_loc + 1) + 4 * sub["nnz"] + 8 * n_loc + 2 * 4 * n_loc * F)
+    max_loc = max(it[3] for it in items)
+    Xp = torch.empty((max_loc, F), dtype=torch.float32, device="cuda")
+    Yp = torch.empty_like(Xp)
+    Yout = torch.full_like(Y, float("nan"))
+
+    def one_pass():
+        for plan, ids, n_owned, n_loc in items:
+            G.groot_rows_gather(ids, X, Xp[:n_loc], F)
+            G.groot_spmm_execute(plan, Xp[:n_loc], Yp[:n_loc], F)
+            G.groot_rows_scatter(ids[:n_owned], Yp[:n_loc], Yout, F)
+
+    for _ in range(max(1, args.warmup)):
+        one_pass()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_pass()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    full_plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(full_plan, F)
+    G.groot_spmm_execute(full_plan, X, Y, F)
+    torch.cuda.synchronize()
+    worst = 0.0
+    for lo in range(0, n, 1 << 24):
+        worst = max(worst, float((Yout[lo:lo + (1 << 24)] - Y[lo:lo + (1 << 24)]).abs().max()))
+    full_foot = 8 * (n + 1) + 4 * nnz + 2 * 4 * n * F
+    undirected = (nnz - n) // 2
+    print(json.dumps({
+        "metric": "partitioned-mode SpMM (gather, per-part SpMM, scatter), 1024-bit CSA AIG, F=64",
+        "value": round(2.0 * nnz * F / (ms * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name + f"_partitioned{P}", "N": n, "nnz": nnz, "F": F, "parts": P},
+        "boundary_edge_fraction": round(cross / 2 / undirected, 4),
+        "rows_with_boundary": sum(it[3] for it in items), "largest_part_rows": max_loc,
+        "device_bytes_full_graph": full_foot, "device_bytes_largest_part": max(foot),
+        "memory_reduction_pct": round(100.0 * (1.0 - max(foot) / full_foot), 2),
+        "max_abs_diff_vs_full_graph": worst, "partition_seconds": round(t_partition, 2), "device": props.name}))
+
+
 def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props):
     """Fused layer against the unfused form (library SpMM, then torch for the dense part)."""
     assert F == 64, "the fused layer is built for F = 64"
@@ -100,6 +161,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
+    ap.add_argument("--partitioned", type=int, default=0, metavar="P",
+                    help="time the partitioned mode instead: P parts with re-grown boundary, gather -> SpMM -> scatter")
     ap.add_argument("--sage-layer", action="store_true",
                     help="time the fused GraphSAGE-mean layer H = relu((A_hat X) Wn + X Ws + b) instead (F = 64)")
     ap.add_argument("--xcd-remap", type=int, default=None)
@@ -155,6 +218,9 @@ def main():
         for _ in range(count):
             G.groot_spmm_execute_phases(plan, X, Y, F, phases)
 
+    if args.partitioned:
+        partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props)
+        return
     if args.sage_layer:
         sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props)
         return
