@@ -55,11 +55,18 @@ def test_two_bit_example_matches_paper():
         want = wl.PI if lab == 4 else wl.PO if lab == 0 else wl.AND
         assert aig.type[nid - 1] == want, nid
         assert aig.label[nid - 1] == lab, nid
+    # the generator-side encoding reproduces every printed feature vector (PI 1, AND 5 and 10, PO 15)
+    enc = wl.paper_node_features(aig)
+    for nid, bits in features.items():
+        assert "".join(str(int(b)) for b in enc[nid - 1]) == bits, nid
+    assert enc.shape == (nodes, 4) and set(np.unique(enc)) <= {0.0, 1.0}
     # feature bits: type bits 00 PI / 11 AND; polarity bits = (left inverted, right inverted)
     for nid, bits in features.items():
         v = nid - 1
         if aig.type[v] == wl.PI:
             assert bits == "0000"
+        elif aig.type[v] == wl.PO:
+            assert bits[0] == "0"
         else:
             assert bits[:2] == "11"
             assert bits[2:] == f"{aig.fanin0[v] & 1}{aig.fanin1[v] & 1}"

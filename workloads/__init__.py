@@ -173,6 +173,26 @@ def uniform_features_numpy(seed: int, row_begin: int, row_end: int, F: int) -> n
     return (top * 2.0 ** -23 - 1.0).astype(np.float32)
 
 
+def paper_node_features(aig: Aig) -> np.ndarray:
+    """The paper's 4-bit node feature vector (Section "Node Features and Node Label creation") as
+    float32 [N1, 4]: PI 0000; internal AND node 1 1 L R with L / R = left / right input inverted;
+    PO 0 X 1 1 with X = the edge from its driver is inverted.  (The text gives the PO encoding as
+    "0X" plus inherited polarity and prints 0011 for a PO with a non-inverted input; this is the
+    reading under which all four printed examples -- nodes 1, 5, 10, 15 of the two-bit multiplier --
+    come out as printed.)"""
+    n1 = aig.num_nodes
+    x = np.zeros((n1, 4), dtype=np.float32)
+    is_and, is_po = aig.type == AND, aig.type == PO
+    x[is_and, 0] = 1.0
+    x[is_and, 1] = 1.0
+    x[is_and, 2] = (aig.fanin0[is_and] & 1).astype(np.float32)
+    x[is_and, 3] = (aig.fanin1[is_and] & 1).astype(np.float32)
+    x[is_po, 1] = (aig.fanin0[is_po] & 1).astype(np.float32)
+    x[is_po, 2] = 1.0
+    x[is_po, 3] = 1.0
+    return x
+
+
 def aig_node_features(aig: Aig, seed: int, F: int) -> np.ndarray:
     """Feature matrix of the smallest workload: columns 0-2 one-hot node type
     (PI / AND / PO); 3 = inverted fanin records; 4 = non-inverted fanin
