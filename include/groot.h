@@ -169,6 +169,32 @@ groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------
+ * groot_plan_lists_device -- the lists of groot_spmm_plan computed on the GPU.
+ * Paper: Section "Kernel Design - GROOT-GPU", LD kernel: every row's degree is
+ * taken from the row pointer and the rows are sorted by degree with a stable
+ * count sort, which is linear in the number of rows.  Here that runs on the
+ * device from the plan's uploaded row pointer (per-block degree histograms, a
+ * prefix over blocks, ballot ranks inside a wavefront), for graphs whose CSR
+ * lives on the device and changes between runs.
+ * All outputs are device pointers owned by the caller:
+ *   row_class_dev          uint8  [N]     1 = HD, 0 = LD
+ *   hd_rows_dev            int32  [N]     first n_hd entries written
+ *   ld_rows_dev            int32  [N]     first n_ld entries written
+ *   ld_rows_by_degree_dev  int32  [N]     first n_ld entries written
+ *   ld_deg_offsets_dev     int64  [T+1]   T = the plan's degree threshold
+ *   counts_dev             int64  [2]     {n_hd, n_ld}
+ * The written entries are bit-identical to groot_plan_view's arrays.
+ * Allocates and frees its own scratch (4 (T+2) bytes per 4096 rows) and
+ * synchronises hip_stream before it returns.
+ * Errors: EINVAL (NULL, plan not uploaded), ERANGE (threshold > 1024), ENOMEM,
+ * EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t *row_class_dev,
+                                     int32_t *hd_rows_dev, int32_t *ld_rows_dev,
+                                     int32_t *ld_rows_by_degree_dev, int64_t *ld_deg_offsets_dev,
+                                     int64_t *counts_dev, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * groot_partition_regrow -- partition into sub-graphs with re-grown boundary.
  * Paper: Section "GNN and Edge Re-growth After Partition", Eq. (1), Eq. (2)
  * and Algorithm 1.  For every part p with node set S_p:

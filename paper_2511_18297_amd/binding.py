@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_sage_layer_forward", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
 ]
@@ -58,6 +58,7 @@ _lib.groot_plan_upload.argtypes = [_vp, _i32]
 _lib.groot_spmm_execute.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.groot_spmm_execute_phases.argtypes = [_vp, _vp, _vp, _i32, _u32, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
+_lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_free.argtypes = [_vp]
 _lib.groot_plan_free.restype = None
 _lib.groot_partition_regrow.argtypes = [_vp, _i32, _vp, _u32, _pp]
@@ -115,7 +116,7 @@ class Graph:
         self._owner = owner          # keeps the parent alive for borrowed handles
 
     def __del__(self):
-        if getattr(self, "handle", None) and self._owner is None:
+        if getattr(self, "handle", None) and self._owner is None and _lib is not None:
             _lib.groot_graph_free(self.handle)
             self.handle = None
 
@@ -126,7 +127,7 @@ class Plan:
         self.graph = graph           # the plan borrows its graph
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and _lib is not None:   # module globals are cleared at interpreter exit
             _lib.groot_plan_free(self.handle)
             self.handle = None
 
@@ -137,7 +138,7 @@ class Parts:
         self.graph = graph
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and _lib is not None:
             _lib.groot_parts_free(self.handle)
             self.handle = None
 
@@ -238,6 +239,24 @@ def groot_sage_layer_forward(pl: Plan, X, Wn, Ws, bias, relu: bool, H, F: int = 
     _check(_lib.groot_sage_layer_forward(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Wn, "Wn"), _dev_ptr(Ws, "Ws"),
                                          None if bias is None else _dev_ptr(bias, "bias"), 1 if relu else 0,
                                          _dev_ptr(H, "H"), F, _stream_handle(stream)))
+
+
+def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_degree, ld_deg_offsets, counts,
+                            stream=None) -> None:
+    """Caller-allocated CUDA tensors: uint8[N], int32[N] x3, int64[T+1], int64[2]."""
+    import torch
+
+    n = groot_graph_view(pl.graph)["n"]
+    for t, dt, size, what in ((row_class, torch.uint8, n, "row_class"), (hd_rows, torch.int32, n, "hd_rows"),
+                              (ld_rows, torch.int32, n, "ld_rows"), (ld_rows_by_degree, torch.int32, n, "ld_rows_by_degree"),
+                              (ld_deg_offsets, torch.int64, pl.degree_threshold + 1, "ld_deg_offsets"),
+                              (counts, torch.int64, 2, "counts")):
+        if t.dtype != dt or t.numel() < max(size, 1):
+            raise TypeError(f"{what} must be {dt} with at least {max(size, 1)} elements")
+    _check(_lib.groot_plan_lists_device(pl.handle, _dev_ptr(row_class, "row_class"), _dev_ptr(hd_rows, "hd_rows"),
+                                        _dev_ptr(ld_rows, "ld_rows"), _dev_ptr(ld_rows_by_degree, "ld_rows_by_degree"),
+                                        _dev_ptr(ld_deg_offsets, "ld_deg_offsets"), _dev_ptr(counts, "counts"),
+                                        _stream_handle(stream)))
 
 
 def groot_partition_regrow(g: Graph, num_parts: int, part_of=None, flags: int = GROOT_REGROW) -> Parts:

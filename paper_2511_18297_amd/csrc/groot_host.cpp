@@ -538,6 +538,23 @@ extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const f
     return GROOT_OK;
 }
 
+extern "C" groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t *row_class_dev, int32_t *hd_rows_dev,
+                                                int32_t *ld_rows_dev, int32_t *ld_rows_by_degree_dev,
+                                                int64_t *ld_deg_offsets_dev, int64_t *counts_dev, void *hip_stream)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_plan_lists_device: NULL plan");
+    if (!row_class_dev || !hd_rows_dev || !ld_rows_dev || !ld_rows_by_degree_dev || !ld_deg_offsets_dev || !counts_dev)
+        return fail(GROOT_EINVAL, "groot_plan_lists_device: NULL output pointer");
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_plan_lists_device: plan is not on the device (call groot_plan_upload)");
+    if (plan->threshold > kPlanDeviceMaxThreshold)
+        return fail(GROOT_ERANGE, "groot_plan_lists_device: degree threshold above " + std::to_string(kPlanDeviceMaxThreshold));
+    int err = launch_plan_device(plan->dev.rowptr, plan->dev.n, plan->threshold, row_class_dev, hd_rows_dev, ld_rows_dev,
+                                 ld_rows_by_degree_dev, ld_deg_offsets_dev, counts_dev, hip_stream);
+    if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, "groot_plan_lists_device: scratch allocation failed");
+    if (err) return fail(GROOT_EHIP, std::string("groot_plan_lists_device: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" void groot_plan_free(groot_plan *plan)
 {
     if (!plan) return;

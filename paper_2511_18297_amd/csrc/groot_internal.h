@@ -67,6 +67,12 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
                 int relu, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
 int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
+// Device-side plan lists (groot_plan_device.hip).  Synchronises the stream; kErrOutOfDeviceMemory when its
+// scratch cannot be allocated.
+constexpr int kPlanDeviceMaxThreshold = 1024;
+constexpr int kErrOutOfDeviceMemory = 2;   // hipErrorOutOfMemory
+int launch_plan_device(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
+                       int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts, void *stream);
 const char *hip_error_text(int err);
 
 // Device memory helpers (groot_kernels.hip, so that the host file needs no HIP headers).

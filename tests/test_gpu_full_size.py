@@ -125,6 +125,23 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
     assert np.array_equal(pv["hd_rows"].reshape(batch, -1), np.arange(2 * BITS)[None, :] + (np.arange(batch) * n1)[:, None])
     G.groot_plan_upload(plan, F)
 
+    # the device-side plan lists at full size, bit for bit against the oracle's count sort
+    want = oracle.plan(view["rowptr"], T)
+    d_class = torch.empty(n, dtype=torch.uint8, device="cuda")
+    d_hd, d_ld, d_by = (torch.full((n,), -7, dtype=torch.int32, device="cuda") for _ in range(3))
+    d_off = torch.empty(T + 1, dtype=torch.int64, device="cuda")
+    d_cnt = torch.empty(2, dtype=torch.int64, device="cuda")
+    G.groot_plan_lists_device(plan, d_class, d_hd, d_ld, d_by, d_off, d_cnt)
+    n_hd, n_ld = (int(v) for v in d_cnt.cpu())
+    assert (n_hd, n_ld) == (want["hd_rows"].shape[0], want["ld_rows"].shape[0])
+    assert np.array_equal(d_class.cpu().numpy(), want["row_class"])
+    assert np.array_equal(d_off.cpu().numpy(), want["ld_deg_offsets"])
+    assert np.array_equal(d_hd.cpu().numpy()[:n_hd], want["hd_rows"])
+    assert np.array_equal(d_ld.cpu().numpy()[:n_ld], want["ld_rows"])
+    assert np.array_equal(d_by.cpu().numpy()[:n_ld], want["ld_rows_by_degree"])
+    assert bool((d_by[n_ld:] == -7).all())
+    del want, d_class, d_hd, d_ld, d_by, d_off, d_cnt
+
     # (a) X = 1: every row of the mean-normalised graph sums to deg * fl(1/deg), within 2^-23 of 1
     X = torch.ones((n, F), dtype=torch.float32, device="cuda")
     Y = torch.full((n, F), float("nan"), dtype=torch.float32, device="cuda")

@@ -230,3 +230,30 @@ def test_partition_and_misc_error_paths():
     G.binding._lib.groot_graph_free(None)
     G.binding._lib.groot_plan_free(None)
     G.binding._lib.groot_parts_free(None)
+
+
+def test_device_plan_lists_host_checks():
+    """Argument checks of the device-side plan that need no GPU: a plan that was never uploaded and
+    NULL outputs are refused before any device work."""
+    aig = wl.csa_multiplier_aig(4)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    plan = G.groot_spmm_plan(g, 4)
+    lib = G.binding._lib
+    dummy = ctypes.c_void_p(256)
+    assert lib.groot_plan_lists_device(plan.handle, dummy, dummy, dummy, dummy, dummy, dummy, None) == G.GROOT_EINVAL
+    assert "not on the device" in G.groot_last_error()
+    assert lib.groot_plan_lists_device(plan.handle, None, dummy, dummy, dummy, dummy, dummy, None) == G.GROOT_EINVAL
+    assert lib.groot_plan_lists_device(None, dummy, dummy, dummy, dummy, dummy, dummy, None) == G.GROOT_EINVAL
+
+
+def test_build_module_is_importable_without_loading_the_library():
+    """A tree without libgroot.so must still be able to import the build step (which makes the library);
+    only the use of the binding needs it."""
+    import subprocess
+    import sys
+
+    code = ("import sys; import paper_2511_18297_amd.build as b; from paper_2511_18297_amd import build as b2; "
+            "assert b is b2 and callable(b.build); "
+            "assert 'paper_2511_18297_amd.binding' not in sys.modules; print('ok')")
+    out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
