@@ -167,6 +167,7 @@ def main():
                     help="time the fused GraphSAGE-mean layer H = relu((A_hat X) Wn + X Ws + b) instead (F = 64)")
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--hd-chunk", type=int, default=None)
+    ap.add_argument("--sage-gap", type=int, default=None, help="pacing of the fused layer's matrix wavefronts (0..4)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU by design); "
@@ -190,6 +191,8 @@ def main():
         G.groot_set_tuning("xcd_remap", args.xcd_remap)
     if args.hd_chunk is not None:
         G.groot_set_tuning("hd_chunk", args.hd_chunk)
+    if args.sage_gap is not None:
+        G.groot_set_tuning("sage_gap", args.sage_gap)
 
     name = args.workload
     if name is None:

@@ -235,9 +235,10 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
                                 float *Y_dev, int32_t F, void *hip_stream);
 
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
- * groot_plan_upload) and "hd_chunk" (largest piece of a high-degree row,
- * 64..4096 non-zeros, read by groot_spmm_plan).  Unknown names give EINVAL.
- * Not needed for normal use. */
+ * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
+ * 64..4096 non-zeros, read by groot_spmm_plan) and "sage_gap" (0..4, the pause
+ * between matrix instructions in groot_sage_layer_forward, read at each call).
+ * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 
 /* Thread-local description of the last failure on this thread; never NULL. */

@@ -421,7 +421,7 @@ void release_device(groot_plan *pl)
 {
     DevicePlan &d = pl->dev;
     dev_free(d.rowptr); dev_free(d.col); dev_free(d.val);
-    dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials);
+    dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials); dev_free(d.zero_row);
     d = DevicePlan{};
     pl->resident = false;
 }
@@ -459,7 +459,9 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
     d.weight_mode = (int)g->weight_mode;
     const bool need_val = g->weight_mode == WeightMode::Explicit;   // row-uniform weights are recomputed on the device
     groot_status st;
-    if ((st = to_device(&d.rowptr, g->rowptr.data(), g->rowptr.size(), "rowptr")) != GROOT_OK ||
+    const std::vector<float> zeros(kZeroRowFloats, 0.0f);
+    if ((st = to_device(&d.zero_row, zeros.data(), zeros.size(), "zero row")) != GROOT_OK ||
+        (st = to_device(&d.rowptr, g->rowptr.data(), g->rowptr.size(), "rowptr")) != GROOT_OK ||
         (st = to_device(&d.col, g->col.data(), g->col.size(), "col")) != GROOT_OK ||
         (st = to_device(&d.val, g->val.data(), need_val ? g->val.size() : 0, "val")) != GROOT_OK ||
         (st = to_device(&d.chunks, plan->chunks.data(), plan->chunks.size(), "HD schedule")) != GROOT_OK ||
@@ -771,6 +773,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (!name) return fail(GROOT_EINVAL, "groot_set_tuning: NULL name");
     std::string k(name);
     if (k == "xcd_remap") { tuning().xcd_remap = value ? 1 : 0; return GROOT_OK; }
+    if (k == "sage_gap") {
+        if (value < 0 || value > 4) return fail(GROOT_EINVAL, "groot_set_tuning: sage_gap must be in [0,4]");
+        tuning().sage_gap = (int)value;
+        return GROOT_OK;
+    }
     if (k == "hd_chunk") {
         if (value < 64 || value > 4096) return fail(GROOT_EINVAL, "groot_set_tuning: hd_chunk must be in [64,4096]");
         tuning().hd_chunk = (int)value;

@@ -36,6 +36,7 @@ struct HdSplitRow {
 struct Tuning {
     int xcd_remap = 1;
     int hd_chunk = 512;
+    int sage_gap = 2;               // pacing of the fused layer's matrix wavefronts, see launch_sage
 };
 Tuning &tuning();
 
@@ -55,8 +56,10 @@ struct DevicePlan {
     float *partials = nullptr;      // [n_partials, partial_stride]
     int64_t n_partials = 0;
     int xcd_remap = 1;
+    float *zero_row = nullptr;      // kZeroRowFloats zeros: the gather target of unused slots in the fused layer
 };
 
+constexpr int kZeroRowFloats = 64;
 constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64 rows)
 
 // Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).

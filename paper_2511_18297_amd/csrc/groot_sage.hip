@@ -1,152 +1,300 @@
 // Fused GraphSAGE-mean layer for gfx950:  H = act((A_hat X) Wn + X Ws + b),  F_in = F_out = 64.
 //
-// The aggregation of a tile of rows never goes to HBM: a workgroup computes the
-// 64 aggregated rows of its tile exactly like the LD kernel (lane groups of 16
-// lanes, float4 gathers, register sums), parks them with the rows' own features
-// in LDS as a 64 x 128 fp32 tile [A_hat X | X], and multiplies that tile with
-// the stacked weights [Wn; Ws] (128 x 64) on the matrix cores
-// (v_mfma_f32_16x16x4_f32).  Wavefront w owns output columns 16w..16w+15: its
-// 128 x 16 slice of the weights lives in 32 registers for the whole launch
-// (workgroups are persistent and walk a contiguous range of tiles), so the only
-// matrix operand read per tile is the LDS tile.  The 64 x 64 result goes back
-// through LDS to be stored as full 256-byte rows.
-// High-degree rows are aggregated beforehand by the HD kernel into H itself;
-// the layer kernel picks those sums up from H instead of recomputing them.
+// The aggregation of a tile of 64 rows never goes to HBM: it is formed like in the LD kernel (lane
+// groups of 16 lanes, float4 gathers, register sums), parked with the rows' own features in LDS as a
+// 64 x 128 fp32 tile [A_hat X | X], and multiplied with the stacked weights [Wn; Ws] (128 x 64) on the
+// matrix cores (v_mfma_f32_16x16x4_f32).
+//
+// The two halves are bound by different units (the gathers by memory, the products by the matrix
+// cores), and a wavefront that issues vector memory instructions into a saturated memory pipeline is
+// held at the issue, where it cannot feed the matrix cores either.  So the wavefronts are specialised.
+// One persistent workgroup of 12 wavefronts per CU walks a contiguous range of tiles:
+//   * 4 consumer wavefronts (one per SIMD) never touch global memory after loading their weights.
+//     Consumer w owns output columns 16w..16w+15; its 128 x 16 slice of [Wn; Ws] lives in 32 registers.
+//     Per tile it runs 128 matrix instructions on the LDS tile and writes its 64 x 16 result to an LDS
+//     output tile.
+//   * 8 producer wavefronts (two per SIMD) each aggregate 8 rows of the next tile into the other LDS
+//     tile and store 8 rows of the previous result from the LDS output tile as full 256-byte rows.
+//     Their gathers run one tile ahead in two register sets, across the barrier, so the memory
+//     pipeline never drains; row pointers are fetched three tiles ahead and column indices two.
+// Both roles meet at one barrier per tile.  The barrier orders LDS traffic only (no global fence):
+// nothing is exchanged through global memory, and the producers' loads stay in flight across it.
+// High-degree rows are aggregated beforehand by the HD kernel into H itself; the producers pick those
+// sums up from H instead of recomputing them.
 #include "groot_device.h"
 
 namespace groot {
 
-constexpr int kSgRows = 64;                 // rows per workgroup tile (16 per wavefront)
+constexpr int kSgRows = 64;                 // rows per tile
 constexpr int kSgF4 = 16;                   // 64 features = 16 float4
-constexpr int kSgAStride = 132;             // floats per LDS row of [agg | self] (128 + 4: conflict-free MFMA operand reads)
-constexpr int kSgOStride = 68;              // floats per LDS row of the output tile
-constexpr int kSgCap = 128;                 // staged non-zeros per wavefront (16 rows)
+constexpr int kSgAStride = 132;             // floats per LDS row of [agg | self] (128 + 4: conflict-free operand reads)
+constexpr int kSgOStride = 68;              // floats per LDS row of the output tile (conflict-free result writes)
+constexpr int kSgConsumers = 4, kSgProducers = 8;
+constexpr int kSgThreads = (kSgConsumers + kSgProducers) * kWave;   // 768
+constexpr int kSgProdRows = kSgRows / kSgProducers;                 // 8 rows of a tile per producer
+constexpr int kSgD = 6;                     // entries of a row on the pipelined path (AIG rows with a self-loop: 2 to 6)
+constexpr int kSgCap = 64;                  // staged column indices per producer (>= kSgProdRows * kSgD)
+static_assert(kSgProdRows * kSgD <= kSgCap, "a producer's simple rows fit its staging area");
 
-// Held to 128 registers (4 wavefronts per SIMD, i.e. 4 resident workgroups per CU): the aggregation phase of
-// one workgroup overlaps the matrix phase of the others.
-template <int W>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) void sage_kernel(const int64_t *__restrict__ rowptr,
-                                                      const int32_t *__restrict__ col,
-                                                      const float *__restrict__ val,
-                                                      const v4f *__restrict__ X, v4f *H,
-                                                      const float *__restrict__ Wn,
-                                                      const float *__restrict__ Ws,
-                                                      const float *__restrict__ bias, int relu,
-                                                      int64_t n, int32_t T, int64_t n_tiles,
-                                                      int64_t tiles_per_wg, int64_t wgs_per_xcd, int remap)
+__device__ __forceinline__ void sage_wave_sync()
 {
-    __shared__ __align__(16) float s_A[kSgRows * kSgAStride];
-    __shared__ int32_t s_col[kWavesPerBlock][kSgCap];
-    __shared__ float s_val[kWavesPerBlock][kSgCap];
-    __shared__ int32_t s_rel[kWavesPerBlock][17];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
-    const int tid = threadIdx.x, w = tid / kWave, l = tid % kWave;
-    const int g = l / 16, f = l % 16;            // lane group / float4 slice in the aggregation phase
-    const int kq = l / 16, jcol = 16 * w + l % 16;   // k offset / output column in the matrix phase
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also fences global memory, which
+// makes every wavefront wait for all of its loads and stores in flight.
+__device__ __forceinline__ void sage_lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
-    // this wavefront's slice of [Wn; Ws]: bfrag[kk] = Wcat[4 kk + kq][jcol]
-    float bfrag[32];
-#pragma unroll
-    for (int kk = 0; kk < 32; ++kk) {
-        const int k = 4 * kk + kq;
-        bfrag[kk] = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
-    }
-    const float bias_v = bias ? bias[jcol] : 0.0f;
+// A wavefront that issues matrix instructions back to back keeps the SIMD's vector issue to itself: the
+// other wavefronts of that SIMD (here two producers) do not get a single instruction in, whatever their
+// priority.  The consumers therefore pause for a few cycles after every four matrix instructions (kGap
+// selects the pause), which is when the producers' address arithmetic, loads and sums are issued.
+template <int kGap>
+__device__ __forceinline__ void sage_consumer_pause()
+{
+    if (kGap == 1) asm volatile("s_nop 7");
+    if (kGap == 2) asm volatile("s_nop 15");
+    if (kGap == 3) asm volatile("s_nop 15\n\ts_nop 7");
+    if (kGap == 4) asm volatile("s_nop 15\n\ts_nop 15");
+}
 
+template <int W, int kGap>
+__global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void sage_kernel(
+    const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
+    const v4f *__restrict__ X, v4f *H, const float *__restrict__ zero_row, const float *__restrict__ Wn,
+    const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n, int32_t T, int64_t n_tiles, int64_t tiles_per_wg,
+    int64_t wgs_per_xcd, int remap)
+{
+    __shared__ __align__(16) float s_A[2][kSgRows * kSgAStride];       // 67,584 B
+    __shared__ __align__(16) float s_O[2][kSgRows * kSgOStride];       // 34,816 B
+    __shared__ __align__(8) int64_t s_slot[kSgProducers][kSgCap];    // byte offset (from X) of slot k of row r at [6 r + k]
+    __shared__ __align__(8) float s_slotw[kSgProducers][kSgCap];     // its weight (explicit weights only)
+    __shared__ float s_inv[kSgProducers][kSgProdRows];
+
+    const int wv = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int64_t lw = logical_block(wgs_per_xcd, remap);
     const int64_t tile_begin = lw * tiles_per_wg;
     const int64_t tile_end = tile_begin + tiles_per_wg < n_tiles ? tile_begin + tiles_per_wg : n_tiles;
+    if (tile_begin >= tile_end) return;                          // the whole workgroup leaves
 
-    // The row pointers and column indices of a tile are fetched one tile ahead and wait in registers
-    // while the previous tile is aggregated and multiplied: two dependent memory latencies leave the
-    // critical path of every tile.
-    int64_t rp = 0, t_begin = 0;
-    int32_t m = 0, c0 = 0, c1 = 0;
-    float v0 = 0.f, v1 = 0.f;
-    bool staged = false;
-    auto fetch_csr = [&](int64_t tile) {
-        const int64_t ri = tile * kSgRows + 16 * w + (l < 16 ? l : 16);
-        rp = rowptr[ri < n ? ri : n];
-        t_begin = __shfl(rp, 0);
-        const int64_t t_end = __shfl(rp, 16), rp_next = __shfl_down(rp, 1);
-        const bool any_hd = __ballot(l < 16 && rp_next - rp >= T) != 0;
-        staged = !any_hd && (t_end - t_begin) <= kSgCap;
-        m = staged ? (int32_t)(t_end - t_begin) : 0;
-        if (l < m) {
-            c0 = __builtin_nontemporal_load(&col[t_begin + l]);
-            if (W == kExplicit) v0 = __builtin_nontemporal_load(&val[t_begin + l]);
-        }
-        if (l + kWave < m) {
-            c1 = __builtin_nontemporal_load(&col[t_begin + kWave + l]);
-            if (W == kExplicit) v1 = __builtin_nontemporal_load(&val[t_begin + kWave + l]);
-        }
-    };
-    if (tile_begin < tile_end) fetch_csr(tile_begin);
-
-    for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
-        const int64_t base = tile * kSgRows;
-        const int64_t wbase = base + 16 * w;              // first of this wavefront's 16 rows
-        // ---- aggregation: 16 rows per wavefront, 4 at a time
-        const bool staged_now = staged;
-        if (staged_now) {
-            if (l < 17) s_rel[w][l] = (int32_t)(rp - t_begin);
-            if (l < m) { s_col[w][l] = c0; if (W == kExplicit) s_val[w][l] = v0; }
-            if (l + kWave < m) { s_col[w][l + kWave] = c1; if (W == kExplicit) s_val[w][l + kWave] = v1; }
-        }
-        __syncthreads();
-        if (tile + 1 < tile_end) fetch_csr(tile + 1);     // lands while this tile is being worked on
-#pragma unroll 1
-        for (int it = 0; it < 4; ++it) {
-            const int lr = it * 4 + g;
-            const int64_t row = wbase + lr;
-            v4f agg = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
-            if (row < n) {
-                self = X[row * kSgF4 + f];
-                if (staged_now) {
-                    agg = ld_row_sum<W, true, 6>(s_rel[w][lr], s_rel[w][lr + 1], s_col[w], s_val[w], X, kSgF4, f);
-                } else {
-                    const int64_t s = rowptr[row], e = rowptr[row + 1];
-                    if (e - s >= T) agg = H[row * kSgF4 + f];       // aggregated by the HD kernel
-                    else agg = ld_row_sum<W, false, 6>(s, e, col, val, X, kSgF4, f);
+    if (wv < kSgConsumers) {
+        // =================================== consumer ===================================
+        const int w = wv;
+        const int kq = l / 16, jcol = 16 * w + l % 16;           // k slot / output column
+        // A lane reads four consecutive k of a tile row at once (k = 16 j + 4 kq + i, i = 0..3); matrix
+        // instruction (j, i) contracts the four k slots kq = 0..3, so its B operand is
+        // bfrag[4 j + i] = Wcat[16 j + 4 kq + i][jcol].
+        float bfrag[32];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = 16 * j + 4 * kq + i;
+                bfrag[4 * j + i] = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
+            }
+        const float bias_v = bias ? bias[jcol] : 0.0f;
+        sage_lds_barrier();                                      // the first tile is in s_A[0]
+        int cur = 0;
+        for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
+            const float *a_tile = s_A[cur];
+            float *o_tile = s_O[cur];
+            v4f acc[4];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb) acc[rb] = (v4f){bias_v, bias_v, bias_v, bias_v};
+            // operands of step j+1 are read while the 16 matrix instructions of step j run
+            v4f a[2][4];
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+                a[0][rb] = *(const v4f *)&a_tile[(rb * 16 + l % 16) * kSgAStride + 4 * kq];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (j + 1 < 8) {
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        a[(j + 1) & 1][rb] = *(const v4f *)&a_tile[(rb * 16 + l % 16) * kSgAStride + 16 * (j + 1) + 4 * kq];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                    for (int rb = 0; rb < 4; ++rb)
+                        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j & 1][rb][i], bfrag[4 * j + i], acc[rb], 0, 0, 0);
+                    sage_consumer_pause<kGap>();
                 }
             }
-            float *dst = &s_A[(16 * w + lr) * kSgAStride + 4 * f];
-            *(v4f *)dst = agg;
-            *(v4f *)(dst + 64) = self;
+            // result (lane holds rows 4 kq + r of its column) to the output tile
+#pragma unroll
+            for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    float v = acc[rb][r];
+                    if (relu) v = v > 0.0f ? v : 0.0f;
+                    o_tile[(rb * 16 + 4 * kq + r) * kSgOStride + jcol] = v;
+                }
+            sage_lds_barrier();
+            cur ^= 1;
         }
-        __syncthreads();
-        // ---- [agg | self] (64 x 128) times this wavefront's 128 x 16 weight slice
-        v4f acc[4];
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb) acc[rb] = (v4f){bias_v, bias_v, bias_v, bias_v};
-#pragma unroll
-        for (int kk = 0; kk < 32; ++kk) {
-#pragma unroll
-            for (int rb = 0; rb < 4; ++rb) {
-                const float a = s_A[(rb * 16 + l % 16) * kSgAStride + 4 * kk + kq];
-                acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bfrag[kk], acc[rb], 0, 0, 0);
-            }
-        }
-        __syncthreads();                                  // every wavefront is done reading the tile
-        // ---- result tile to LDS (lane holds rows 4 kq + r of its column), then full-row stores
-#pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float v = acc[rb][r];
-                if (relu) v = v > 0.0f ? v : 0.0f;
-                s_A[(rb * 16 + 4 * kq + r) * kSgOStride + jcol] = v;
-            }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int idx = tid + kBlock * q;
-            const int orow = idx / kSgF4, c4 = idx % kSgF4;
-            const int64_t row = base + orow;
-            if (row < n) __builtin_nontemporal_store(*(const v4f *)&s_A[orow * kSgOStride + 4 * c4], &H[row * kSgF4 + c4]);
-        }
-        __syncthreads();                                  // the tile buffer is free for the next tile
+        return;
     }
+
+    // =================================== producer ===================================
+    const int p = wv - kSgConsumers;             // rows 8p .. 8p+7 of every tile
+    const int g = l / 16, f = l % 16;            // lane group / float4 slice
+    const int64_t zero_off = (const char *)zero_row - (const char *)X;   // where unused slots point
+
+    // ---- CSR pipeline for the producer's 8 rows of a tile
+    // rp_a: row pointers of the tile whose column indices are in c0 (the next tile to be staged);
+    // rp_b: row pointers of the tile after that.
+    int64_t rp_a = 0, rp_b = 0;
+    int32_t c0 = 0;
+    float v0 = 0.f;
+    bool simple_a = false;
+    auto load_rp = [&](int64_t tile) -> int64_t {
+        const int64_t ri = tile * kSgRows + kSgProdRows * p + (l < kSgProdRows ? l : kSgProdRows);
+        return rowptr[ri < n ? ri : n];          // lanes 0..8 hold the 9 pointers; rows past the end read rowptr[n]
+    };
+    // The 8 rows are "simple" when every row has at most kSgD entries and none is high-degree: they go
+    // through the pipelined path.  Their (at most 48) entries are one load per lane.
+    auto load_cols = [&]() {                     // from rp_a
+        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kSgProdRows), rp_next = __shfl_down(rp_a, 1);
+        const int64_t len = rp_next - rp_a;
+        simple_a = __ballot(l < kSgProdRows && (len > kSgD || len >= T)) == 0;
+        const int32_t m = simple_a ? (int32_t)(t_end - begin) : 0;
+        // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
+        const int64_t i0 = l < m ? begin + l : 0;
+        c0 = __builtin_nontemporal_load(&col[i0]);
+        if (W == kExplicit) v0 = __builtin_nontemporal_load(&val[i0]);
+    };
+    // rp_a, c0 -> LDS as a slot table: every row gets exactly kSgD slots, lane 6 r + k prepares slot k
+    // of row r as the byte offset of the gathered row from X.  A slot past the row's end points at a row
+    // of zeros outside X, so the sum of a row is the plain sum of its kSgD slots.  Rows of a tile that
+    // is not simple are staged as empty.  All index arithmetic of the gathers is done here, once per
+    // tile and in parallel over the lanes, not per gathered row.
+    bool simple_iss = false;                     // whether the tile now in the slot table is simple
+    auto stage = [&]() {
+        simple_iss = simple_a;
+        const int r = l / kSgD, k = l - r * kSgD;                // l < 48: row r, slot k
+        const int32_t rel = simple_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
+        const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
+        const int32_t c = __shfl(c0, lo + k);
+        const float wv_ = W == kExplicit ? __shfl(v0, lo + k) : 0.f;
+        const bool live = k < hi - lo;
+        if (l < kSgProdRows * kSgD) {
+            s_slot[p][l] = live ? ((int64_t)c << 8) : zero_off;
+            if (W == kExplicit) s_slotw[p][l] = live ? wv_ : 0.f;
+        }
+        const int32_t len = __shfl_down(rel, 1) - rel;           // all lanes take part in the exchange
+        if (l < kSgProdRows) s_inv[p][l] = row_weight<W>(len);   // lane r: weight of row r
+        sage_wave_sync();
+    };
+
+    // ---- aggregation of four simple rows (one per lane group) in two halves, a whole tile apart: the
+    //      loads of a group of tile t+2 are issued right after the same group of tile t+1 has been
+    //      summed.  The issue does not branch and every lane issues all kSgD + 1 loads, so the number
+    //      of loads in flight is known at compile time and the wait before a group's sum lets the
+    //      younger loads fly on.
+    struct RowRegs {
+        v4f xs[kSgD], self;
+        float ws[kSgD];
+        float inv;
+    };
+    RowRegs rr[2];
+    const char *Xf = (const char *)X + 16 * f;                   // this lane's float4 slice of row 0
+    auto issue = [&](RowRegs &q, int64_t tile, int grp) {
+        const int lr = grp * 4 + g;
+        int64_t row = tile * kSgRows + kSgProdRows * p + lr;
+        row = row < n ? row : n - 1;
+        q.inv = s_inv[p][lr];
+        q.self = *(const v4f *)(Xf + (row << 8));
+#pragma unroll
+        for (int k = 0; k < kSgD; ++k) {
+            const int64_t off = s_slot[p][lr * kSgD + k];
+            if (W == kExplicit) q.ws[k] = s_slotw[p][lr * kSgD + k];
+            q.xs[k] = *(const v4f *)(Xf + off);
+        }
+    };
+    auto finish = [&](RowRegs &q, int grp, float *buf) {
+        const int lr = grp * 4 + g;
+        v4f agg = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < kSgD; ++k) {
+            if (W == kExplicit) agg += q.ws[k] * q.xs[k];
+            else agg += q.xs[k];
+        }
+        if (W != kExplicit) agg *= q.inv;
+        float *dst = &buf[(kSgProdRows * p + lr) * kSgAStride + 4 * f];
+        *(v4f *)dst = agg;
+        *(v4f *)(dst + 64) = q.self;                             // rows past the end are never stored
+    };
+    // Any other row (long, high-degree, or next to one): straight from global memory, not overlapped.
+    auto slow_rows = [&](int64_t tile, int grp, float *buf) {
+        const int lr = grp * 4 + g;
+        const int64_t row = tile * kSgRows + kSgProdRows * p + lr;
+        v4f agg = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
+        if (row < n) {
+            self = X[row * kSgF4 + f];
+            const int64_t s = rowptr[row], e = rowptr[row + 1];
+            if (e - s >= T) agg = H[row * kSgF4 + f];            // aggregated by the HD kernel
+            else agg = ld_row_sum<W, false, kSgD>(s, e, col, val, X, kSgF4, f);
+        }
+        float *dst = &buf[(kSgProdRows * p + lr) * kSgAStride + 4 * f];
+        *(v4f *)dst = agg;
+        *(v4f *)(dst + 64) = self;
+    };
+    // The producer's 8 rows of a finished tile: LDS output tile -> H, full rows.
+    auto store_rows = [&](int64_t tile, const float *o_tile) {
+#pragma unroll
+        for (int grp = 0; grp < 2; ++grp) {
+            const int lr = grp * 4 + g;
+            const int64_t row = tile * kSgRows + kSgProdRows * p + lr;
+            if (row < n)
+                __builtin_nontemporal_store(*(const v4f *)&o_tile[(kSgProdRows * p + lr) * kSgOStride + 4 * f],
+                                            &H[row * kSgF4 + f]);
+        }
+    };
+
+    // ---- prologue: the first tile is aggregated on its own, the second one is put in flight
+    slow_rows(tile_begin, 0, s_A[0]);
+    slow_rows(tile_begin, 1, s_A[0]);
+    rp_a = load_rp(tile_begin + 1);
+    load_cols();
+    stage();
+    bool simple_fin = simple_iss;                                // tile_begin + 1: summed during the first phase
+    rp_a = load_rp(tile_begin + 2);                              // same order of loads as in the loop: CSR, then rows
+    load_cols();
+    rp_b = load_rp(tile_begin + 3);
+    issue(rr[0], tile_begin + 1, 0);
+    issue(rr[1], tile_begin + 1, 1);
+    sage_lds_barrier();
+
+    int cur = 0;
+    for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
+        // While the consumers multiply `tile` (s_A[cur] -> s_O[cur]): store the result of tile-1, finish
+        // tile+1 into s_A[cur^1], put tile+2 in flight.  Past the workgroup's last tile the pipeline runs
+        // on empty: the loads still go to valid addresses, the sums land in the LDS tile nobody reads.
+        float *a_next = s_A[cur ^ 1];
+        stage();                                                 // CSR of tile+2 -> slot table
+        rp_a = rp_b;
+        load_cols();                                             // column indices of tile+3
+        rp_b = load_rp(tile + 4);
+        if (tile > tile_begin) store_rows(tile - 1, s_O[cur ^ 1]);
+        finish(rr[0], 0, a_next);
+        issue(rr[0], tile + 2, 0);
+        finish(rr[1], 1, a_next);
+        issue(rr[1], tile + 2, 1);
+        if (!simple_fin) {                                       // rare: redo the producer's rows of tile+1
+            slow_rows(tile + 1, 0, a_next);
+            slow_rows(tile + 1, 1, a_next);
+        }
+        simple_fin = simple_iss;
+        sage_lds_barrier();
+        cur ^= 1;
+    }
+    store_rows(tile_end - 1, s_O[cur ^ 1]);
 }
 
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
@@ -158,22 +306,30 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
     const int64_t n_tiles = (dp.n + kSgRows - 1) / kSgRows;
-    // persistent workgroups: exactly as many as the device keeps resident, so that all of them run at once
-    int per_cu = 0;
-    GROOT_DISPATCH_W(dp.weight_mode, (e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sage_kernel<kW>, kBlock, 0)));
-    if (e != hipSuccess) return (int)e;
-    if (per_cu < 1) per_cu = 1;
-    int64_t n_wg = (int64_t)cus * per_cu;
-    n_wg = (n_wg + kXcds - 1) / kXcds * kXcds;
+    // persistent workgroups: one per CU (its 12 wavefronts fill three of a SIMD's wavefront slots each)
+    int64_t n_wg = (cus + kXcds - 1) / kXcds * kXcds;
     if (n_wg > n_tiles) n_wg = n_tiles;
     const int remap = dp.xcd_remap && n_wg % kXcds == 0 && n_wg >= 4 * kXcds;
     const int64_t tiles_per_wg = (n_tiles + n_wg - 1) / n_wg;
     if (!grid_ok(n_wg)) return (int)hipErrorInvalidConfiguration;
-    if (!weights_ok(dp)) return (int)hipErrorInvalidValue;
+    if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
-    GROOT_DISPATCH_W(dp.weight_mode, (sage_kernel<kW><<<dim3((unsigned)n_wg), dim3(kBlock), 0, st>>>(
-                                         dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)H, Wn, Ws, bias, relu, dp.n,
-                                         dp.threshold, n_tiles, tiles_per_wg, n_wg / kXcds, remap)));
+    // the kernel reads entry 0 of the index (and weight) array from idle lanes: give it something to read
+    // when the matrix has no entries, or no weight array
+    const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
+    const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
+#define GROOT_SAGE_LAUNCH(GAP)                                                                                       \
+    GROOT_DISPATCH_W(dp.weight_mode, (sage_kernel<kW, GAP><<<dim3((unsigned)n_wg), dim3(kSgThreads), 0, st>>>(           \
+                                         dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)H, dp.zero_row, Wn, Ws, bias, \
+                                         relu, dp.n, dp.threshold, n_tiles, tiles_per_wg, n_wg / kXcds, remap)))
+    switch (tuning().sage_gap) {
+    case 0: GROOT_SAGE_LAUNCH(0); break;
+    case 1: GROOT_SAGE_LAUNCH(1); break;
+    case 3: GROOT_SAGE_LAUNCH(3); break;
+    case 4: GROOT_SAGE_LAUNCH(4); break;
+    default: GROOT_SAGE_LAUNCH(2); break;
+    }
+#undef GROOT_SAGE_LAUNCH
     return (int)hipGetLastError();
 }
 
