@@ -32,9 +32,10 @@ WORKLOADS = {
 }
 
 
-# HBM-side traffic of one ld_kernel launch in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
-# (see profiles/); filled in per workload once measured, None otherwise.
-TRAFFIC = {"csa1024_b16_F64": 80.52e9}   # 46.20 GB read + 34.32 GB written
+# HBM-side traffic of one launch of the LD kernel in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
+# (see profiles/); filled in per workload and kernel once measured, None otherwise.
+TRAFFIC = {("csa1024_b16_F64", "ld_pipe_kernel"): 83.91e9,   # 49.59 GB read + 34.32 GB written
+           ("csa1024_b16_F64", "ld_kernel"): 80.52e9}        # 46.20 GB read + 34.32 GB written
 
 
 def algorithmic_bytes(n, nnz, F):
@@ -167,6 +168,7 @@ def main():
                     help="time the fused GraphSAGE-mean layer H = relu((A_hat X) Wn + X Ws + b) instead (F = 64)")
     ap.add_argument("--xcd-remap", type=int, default=None)
     ap.add_argument("--hd-chunk", type=int, default=None)
+    ap.add_argument("--ld-pipeline", type=int, default=None, help="LD kernel choice: 1 pipelined, 0 plain, -1 auto")
     ap.add_argument("--sage-gap", type=int, default=None, help="pacing of the fused layer's matrix wavefronts (0..4)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -191,6 +193,8 @@ def main():
         G.groot_set_tuning("xcd_remap", args.xcd_remap)
     if args.hd_chunk is not None:
         G.groot_set_tuning("hd_chunk", args.hd_chunk)
+    if args.ld_pipeline is not None:
+        G.groot_set_tuning("ld_pipeline", args.ld_pipeline)
     if args.sage_gap is not None:
         G.groot_set_tuning("sage_gap", args.sage_gap)
 
@@ -301,6 +305,10 @@ def main():
                "sample": f"copies 0..{copies - 1} of {batch}: {n1 * copies} rows, {int(rp[-1]) * copies} nnz, F={F} "
                          f"(fp64, row-parallel OpenMP, one copy at a time)"}
 
+    # which LD kernel the library picked: the software-pipelined one serves F = 32, 64, 128 on graphs with
+    # short rows and row-uniform weights (every AIG graph; not the transposed one, whose weights are explicit)
+    knob = -1 if args.ld_pipeline is None else args.ld_pipeline
+    ld_name = "ld_pipe_kernel" if F in (32, 64, 128) and (knob == 1 or (knob < 0 and not args.transposed)) else "ld_kernel"
     out = {
         "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak), 1024-bit CSA AIG, F=64",
         "value": round(gflops, 2),
@@ -320,8 +328,9 @@ def main():
         "hbm_gbps": round(gbps, 1),
         "hbm_pct_of_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "algorithmic_bytes_per_step": bytes_all,
-        "roofline": {"bound": "hbm", "kernel": "ld_kernel", "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4), "traffic": None if args.transposed else TRAFFIC.get(name),
+        "roofline": {"bound": "hbm", "kernel": ld_name, "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None if args.transposed else TRAFFIC.get((name, ld_name)),
                      "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld},
         "hd_ms": round(ms_hd, 4),
         "finish_ms": round(ms_fin, 4),

@@ -236,8 +236,12 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
 
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
  * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
- * 64..4096 non-zeros, read by groot_spmm_plan) and "sage_gap" (0..4, the pause
- * between matrix instructions in groot_sage_layer_forward, read at each call).
+ * 64..4096 non-zeros, read by groot_spmm_plan), "sage_gap" (0..4, the pause
+ * between matrix instructions in groot_sage_layer_forward, read at each call)
+ * and "ld_pipeline" (which LD kernel serves F = 32, 64, 128: 1 the software-
+ * pipelined one, 0 the plain one, -1 (default) the pipelined one when at least
+ * 90 % of the low-degree rows have at most 6 entries and the weights are
+ * row-uniform; read by groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

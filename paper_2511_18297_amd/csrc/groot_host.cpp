@@ -459,7 +459,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
     d.weight_mode = (int)g->weight_mode;
     const bool need_val = g->weight_mode == WeightMode::Explicit;   // row-uniform weights are recomputed on the device
     groot_status st;
-    const std::vector<float> zeros(kZeroRowFloats, 0.0f);
+    const std::vector<float> zeros(kZeroRowFloats + kTrashFloats, 0.0f);
     if ((st = to_device(&d.zero_row, zeros.data(), zeros.size(), "zero row")) != GROOT_OK ||
         (st = to_device(&d.rowptr, g->rowptr.data(), g->rowptr.size(), "rowptr")) != GROOT_OK ||
         (st = to_device(&d.col, g->col.data(), g->col.size(), "col")) != GROOT_OK ||
@@ -471,6 +471,15 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         release_device(plan);
         set_error(keep);
         return st;
+    }
+    // The pipelined LD kernel serves rows of at most 6 entries; longer ones take an unoverlapped path there.
+    {
+        const int64_t n_ld = (int64_t)plan->ld_rows.size();
+        const int32_t short_deg = std::min<int32_t>(7, plan->threshold);
+        const int64_t n_short = plan->ld_deg_offsets.empty() ? 0 : plan->ld_deg_offsets[short_deg];
+        const int knob = tuning().ld_pipeline;
+        // with explicit weights the plain kernel measured faster (16.0 against 17.0 ms on the transposed headline graph)
+        d.ld_pipelined = knob > 0 || (knob < 0 && n_ld > 0 && n_short * 10 >= n_ld * 9 && !need_val);
     }
     d.n_chunks = (int64_t)plan->chunks.size();
     d.n_tiles = (g->n + kRowsPerLdTile - 1) / kRowsPerLdTile;
@@ -773,6 +782,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (!name) return fail(GROOT_EINVAL, "groot_set_tuning: NULL name");
     std::string k(name);
     if (k == "xcd_remap") { tuning().xcd_remap = value ? 1 : 0; return GROOT_OK; }
+    if (k == "ld_pipeline") {
+        if (value < -1 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: ld_pipeline must be -1, 0 or 1");
+        tuning().ld_pipeline = (int)value;
+        return GROOT_OK;
+    }
     if (k == "sage_gap") {
         if (value < 0 || value > 4) return fail(GROOT_EINVAL, "groot_set_tuning: sage_gap must be in [0,4]");
         tuning().sage_gap = (int)value;

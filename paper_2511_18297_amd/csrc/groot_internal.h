@@ -37,6 +37,7 @@ struct Tuning {
     int xcd_remap = 1;
     int hd_chunk = 512;
     int sage_gap = 2;               // pacing of the fused layer's matrix wavefronts, see launch_sage
+    int ld_pipeline = -1;           // pipelined LD kernel: 1 always (where it applies), 0 never, -1 when the rows are short
 };
 Tuning &tuning();
 
@@ -56,14 +57,18 @@ struct DevicePlan {
     float *partials = nullptr;      // [n_partials, partial_stride]
     int64_t n_partials = 0;
     int xcd_remap = 1;
-    float *zero_row = nullptr;      // kZeroRowFloats zeros: the gather target of unused slots in the fused layer
+    float *zero_row = nullptr;      // kZeroRowFloats zeros (the gather target of unused slots in the pipelined
+                                    // kernels), followed by kTrashFloats that those kernels may overwrite
+    int ld_pipelined = 0;           // low-degree rows go through the pipelined LD kernel when F allows
 };
 
-constexpr int kZeroRowFloats = 64;
+constexpr int kZeroRowFloats = 128;
+constexpr int kTrashFloats = 2048;
 constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64 rows)
 
 // Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
+int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);   // F = 32, 64, 128
 int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
 int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream);
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,

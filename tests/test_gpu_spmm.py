@@ -15,6 +15,15 @@ ensure_built()
 import paper_2511_18297_amd as G  # noqa: E402
 
 
+@pytest.fixture(autouse=True, params=[0, 1], ids=["ld_plain", "ld_pipelined"])
+def ld_kernel_choice(request):
+    """Every case runs with each of the two LD kernels (the pipelined one applies to F = 32, 64, 128;
+    other widths take the plain kernel either way)."""
+    G.groot_set_tuning("ld_pipeline", request.param)
+    yield request.param
+    G.groot_set_tuning("ld_pipeline", -1)
+
+
 @pytest.fixture(scope="module")
 def torch_cuda():
     import torch
