@@ -29,12 +29,17 @@ constexpr int kSgRows = 64;                 // rows per tile
 constexpr int kSgF4 = 16;                   // 64 features = 16 float4
 constexpr int kSgAStride = 132;             // floats per LDS row of [agg | self] (128 + 4: conflict-free operand reads)
 constexpr int kSgOStride = 68;              // floats per LDS row of the output tile (conflict-free result writes)
-constexpr int kSgConsumers = 4, kSgProducers = 8;
+#ifndef GROOT_SAGE_PRODUCERS
+#define GROOT_SAGE_PRODUCERS 8      // 4 (one per SIMD, 16 rows each, four register sets) measured 30.3 ms against 29.2
+#endif
+constexpr int kSgConsumers = 4, kSgProducers = GROOT_SAGE_PRODUCERS;
 constexpr int kSgThreads = (kSgConsumers + kSgProducers) * kWave;   // 768
-constexpr int kSgProdRows = kSgRows / kSgProducers;                 // 8 rows of a tile per producer
+constexpr int kSgProdRows = kSgRows / kSgProducers;                 // rows of a tile per producer
+constexpr int kSgGroups = kSgProdRows / 4;                          // lane-group sweeps (4 rows each) per producer and tile
 constexpr int kSgD = 6;                     // entries of a row on the pipelined path (AIG rows with a self-loop: 2 to 6)
-constexpr int kSgCap = 64;                  // staged column indices per producer (>= kSgProdRows * kSgD)
-static_assert(kSgProdRows * kSgD <= kSgCap, "a producer's simple rows fit its staging area");
+constexpr int kSgSlots = kSgProdRows * kSgD;                        // slots of a producer's rows
+constexpr int kSgH = (kSgSlots + kWave - 1) / kWave;                // column indices per lane
+static_assert(kSgProdRows + 1 <= kWave, "row pointers of a producer fit one wavefront");
 
 __device__ __forceinline__ void sage_wave_sync()
 {
@@ -64,7 +69,7 @@ __device__ __forceinline__ void sage_consumer_pause()
 }
 
 template <int W, int kGap>
-__global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) void sage_kernel(
+__global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgThreads / 256, kSgThreads / 256))) void sage_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const v4f *__restrict__ X, v4f *H, const float *__restrict__ zero_row, const float *__restrict__ Wn,
     const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n, int32_t T, int64_t n_tiles, int64_t tiles_per_wg,
@@ -72,8 +77,8 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
 {
     __shared__ __align__(16) float s_A[2][kSgRows * kSgAStride];       // 67,584 B
     __shared__ __align__(16) float s_O[2][kSgRows * kSgOStride];       // 34,816 B
-    __shared__ __align__(8) int64_t s_slot[kSgProducers][kSgCap];    // byte offset (from X) of slot k of row r at [6 r + k]
-    __shared__ __align__(8) float s_slotw[kSgProducers][kSgCap];     // its weight (explicit weights only)
+    __shared__ __align__(8) int64_t s_slot[kSgProducers][kSgSlots];  // byte offset (from X) of slot k of row r at [6 r + k]
+    __shared__ __align__(8) float s_slotw[kSgProducers][kSgSlots];   // its weight (explicit weights only)
     __shared__ float s_inv[kSgProducers][kSgProdRows];
 
     const int wv = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -147,45 +152,64 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
     const int64_t zero_off = (const char *)zero_row - (const char *)X;   // where unused slots point
 
     // ---- CSR pipeline for the producer's 8 rows of a tile
-    // rp_a: row pointers of the tile whose column indices are in c0 (the next tile to be staged);
+    // rp_a: row pointers of the tile whose column indices are in cc (the next tile to be staged);
     // rp_b: row pointers of the tile after that.
     int64_t rp_a = 0, rp_b = 0;
-    int32_t c0 = 0;
-    float v0 = 0.f;
+    int32_t cc[kSgH];
+    float vv[kSgH];
+#pragma unroll
+    for (int h = 0; h < kSgH; ++h) { cc[h] = 0; vv[h] = 0.f; }
     bool simple_a = false;
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kSgRows + kSgProdRows * p + (l < kSgProdRows ? l : kSgProdRows);
-        return rowptr[ri < n ? ri : n];          // lanes 0..8 hold the 9 pointers; rows past the end read rowptr[n]
+        return rowptr[ri < n ? ri : n];          // lanes 0..kSgProdRows hold the pointers; rows past the end read rowptr[n]
     };
-    // The 8 rows are "simple" when every row has at most kSgD entries and none is high-degree: they go
-    // through the pipelined path.  Their (at most 48) entries are one load per lane.
+    // The producer's rows are "simple" when every row has at most kSgD entries and none is high-degree:
+    // they go through the pipelined path.
     auto load_cols = [&]() {                     // from rp_a
         const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kSgProdRows), rp_next = __shfl_down(rp_a, 1);
         const int64_t len = rp_next - rp_a;
         simple_a = __ballot(l < kSgProdRows && (len > kSgD || len >= T)) == 0;
         const int32_t m = simple_a ? (int32_t)(t_end - begin) : 0;
         // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
-        const int64_t i0 = l < m ? begin + l : 0;
-        c0 = __builtin_nontemporal_load(&col[i0]);
-        if (W == kExplicit) v0 = __builtin_nontemporal_load(&val[i0]);
+#pragma unroll
+        for (int h = 0; h < kSgH; ++h) {
+            const int64_t i = l + kWave * h < m ? begin + l + kWave * h : 0;
+            cc[h] = __builtin_nontemporal_load(&col[i]);
+            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
+        }
     };
-    // rp_a, c0 -> LDS as a slot table: every row gets exactly kSgD slots, lane 6 r + k prepares slot k
-    // of row r as the byte offset of the gathered row from X.  A slot past the row's end points at a row
-    // of zeros outside X, so the sum of a row is the plain sum of its kSgD slots.  Rows of a tile that
-    // is not simple are staged as empty.  All index arithmetic of the gathers is done here, once per
-    // tile and in parallel over the lanes, not per gathered row.
+    // rp_a, cc -> LDS as a slot table: every row gets exactly kSgD slots, lane s (and s + 64) prepares slot
+    // k of row r, s = 6 r + k, as the byte offset of the gathered row from X.  A slot past the row's end
+    // points at a row of zeros outside X, so the sum of a row is the plain sum of its kSgD slots.  Rows of
+    // a tile that is not simple are staged as empty.  All index arithmetic of the gathers is done here,
+    // once per tile and in parallel over the lanes, not per gathered row.
     bool simple_iss = false;                     // whether the tile now in the slot table is simple
     auto stage = [&]() {
         simple_iss = simple_a;
-        const int r = l / kSgD, k = l - r * kSgD;                // l < 48: row r, slot k
         const int32_t rel = simple_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
-        const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
-        const int32_t c = __shfl(c0, lo + k);
-        const float wv_ = W == kExplicit ? __shfl(v0, lo + k) : 0.f;
-        const bool live = k < hi - lo;
-        if (l < kSgProdRows * kSgD) {
-            s_slot[p][l] = live ? ((int64_t)c << 8) : zero_off;
-            if (W == kExplicit) s_slotw[p][l] = live ? wv_ : 0.f;
+#pragma unroll
+        for (int h = 0; h < kSgH; ++h) {
+            const int s_ = l + kWave * h;
+            const int r = s_ / kSgD, k = s_ - r * kSgD;
+            const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
+            const int src = lo + k;
+            int32_t c = 0;
+            float wv_ = 0.f;
+#pragma unroll
+            for (int q = 0; q < kSgH; ++q) {
+                const int32_t cq = __shfl(cc[q], src - kWave * q);
+                c = (src >> 6) == q ? cq : c;
+                if (W == kExplicit) {
+                    const float wq = __shfl(vv[q], src - kWave * q);
+                    wv_ = (src >> 6) == q ? wq : wv_;
+                }
+            }
+            const bool live = k < hi - lo;
+            if (s_ < kSgSlots) {
+                s_slot[p][s_] = live ? ((int64_t)c << 8) : zero_off;
+                if (W == kExplicit) s_slotw[p][s_] = live ? wv_ : 0.f;
+            }
         }
         const int32_t len = __shfl_down(rel, 1) - rel;           // all lanes take part in the exchange
         if (l < kSgProdRows) s_inv[p][l] = row_weight<W>(len);   // lane r: weight of row r
@@ -202,7 +226,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
         float ws[kSgD];
         float inv;
     };
-    RowRegs rr[2];
+    RowRegs rr[kSgGroups];
     const char *Xf = (const char *)X + 16 * f;                   // this lane's float4 slice of row 0
     auto issue = [&](RowRegs &q, int64_t tile, int grp) {
         const int lr = grp * 4 + g;
@@ -248,7 +272,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
     // The producer's 8 rows of a finished tile: LDS output tile -> H, full rows.
     auto store_rows = [&](int64_t tile, const float *o_tile) {
 #pragma unroll
-        for (int grp = 0; grp < 2; ++grp) {
+        for (int grp = 0; grp < kSgGroups; ++grp) {
             const int lr = grp * 4 + g;
             const int64_t row = tile * kSgRows + kSgProdRows * p + lr;
             if (row < n)
@@ -258,8 +282,8 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
     };
 
     // ---- prologue: the first tile is aggregated on its own, the second one is put in flight
-    slow_rows(tile_begin, 0, s_A[0]);
-    slow_rows(tile_begin, 1, s_A[0]);
+#pragma unroll 1
+    for (int grp = 0; grp < kSgGroups; ++grp) slow_rows(tile_begin, grp, s_A[0]);
     rp_a = load_rp(tile_begin + 1);
     load_cols();
     stage();
@@ -267,8 +291,8 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
     rp_a = load_rp(tile_begin + 2);                              // same order of loads as in the loop: CSR, then rows
     load_cols();
     rp_b = load_rp(tile_begin + 3);
-    issue(rr[0], tile_begin + 1, 0);
-    issue(rr[1], tile_begin + 1, 1);
+#pragma unroll
+    for (int grp = 0; grp < kSgGroups; ++grp) issue(rr[grp], tile_begin + 1, grp);
     sage_lds_barrier();
 
     int cur = 0;
@@ -282,13 +306,14 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(3, 3
         load_cols();                                             // column indices of tile+3
         rp_b = load_rp(tile + 4);
         if (tile > tile_begin) store_rows(tile - 1, s_O[cur ^ 1]);
-        finish(rr[0], 0, a_next);
-        issue(rr[0], tile + 2, 0);
-        finish(rr[1], 1, a_next);
-        issue(rr[1], tile + 2, 1);
+#pragma unroll
+        for (int grp = 0; grp < kSgGroups; ++grp) {
+            finish(rr[grp], grp, a_next);
+            issue(rr[grp], tile + 2, grp);
+        }
         if (!simple_fin) {                                       // rare: redo the producer's rows of tile+1
-            slow_rows(tile + 1, 0, a_next);
-            slow_rows(tile + 1, 1, a_next);
+#pragma unroll 1
+            for (int grp = 0; grp < kSgGroups; ++grp) slow_rows(tile + 1, grp, a_next);
         }
         simple_fin = simple_iss;
         sage_lds_barrier();
