@@ -151,6 +151,19 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
     for lo in range(0, n, 1 << 24):
         dev_max = max(dev_max, float((Y[lo:lo + (1 << 24)] - 1.0).abs().max()))
     assert dev_max <= 2.0 ** -22, dev_max          # NaN (an unwritten row) fails this too
+    # the same property through the plain LD kernel (the default above is the pipelined one)
+    G.groot_set_tuning("ld_pipeline", 0)
+    try:
+        plain = G.groot_spmm_plan(g, T)
+        G.groot_plan_upload(plain, F)
+        Y.fill_(float("nan"))
+        G.groot_spmm_execute(plain, X, Y, F)
+        torch.cuda.synchronize()
+        for lo in range(0, n, 1 << 24):
+            assert float((Y[lo:lo + (1 << 24)] - 1.0).abs().max()) <= 2.0 ** -22
+        del plain
+    finally:
+        G.groot_set_tuning("ld_pipeline", -1)
 
     # (b) the benchmark's inputs, sampled rows against the oracle
     wl.uniform_features(3, 0, n, F, out=X)

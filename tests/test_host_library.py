@@ -216,6 +216,10 @@ def test_partition_and_misc_error_paths():
     with pytest.raises(G.GrootError):
         G.groot_set_tuning("hd_chunk", 7)
     G.groot_set_tuning("hd_chunk", 512)
+    for knob, bad, good in (("ld_pipeline", 2, -1), ("ld_pipeline", -2, -1), ("sage_gap", 5, 2), ("sage_gap", -1, 2)):
+        with pytest.raises(G.GrootError):
+            G.groot_set_tuning(knob, bad)
+        G.groot_set_tuning(knob, good)
     plan = G.groot_spmm_plan(g, 32)
     # executing without device residency is refused on the host, before any HIP call
     lib = G.binding._lib
