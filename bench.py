@@ -29,6 +29,12 @@ WORKLOADS = {
     "csa1024_b1_F64": (1024, 1, 64, 2, 32),
     "csa256_b1_F64": (256, 1, 64, 1, 32),
     "csa32_b1_F32": (32, 1, 32, 0, 32),
+    # degree profile of the paper's Booth dataset at its kernel-evaluation sizes (64-512 bit, embedding 32):
+    # radix-4 Booth multipliers, batched so that the graph is large enough to time
+    "booth512_b16_F32": (512, 16, 32, 4, 32),
+    "booth256_b16_F32": (256, 16, 32, 4, 32),
+    "booth64_b16_F32": (64, 16, 32, 4, 32),
+    "booth512_b16_F64": (512, 16, 64, 4, 32),
 }
 
 
@@ -205,7 +211,7 @@ def main():
     bits, batch, F, seed, T = WORKLOADS[name]
 
     t0 = time.time()
-    aig = wl.csa_multiplier_aig(bits)
+    aig = wl.booth_multiplier_aig(bits) if name.startswith("booth") else wl.csa_multiplier_aig(bits)
     g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
     if args.transposed:
         g = G.groot_graph_transpose(g)
@@ -305,10 +311,9 @@ def main():
                "sample": f"copies 0..{copies - 1} of {batch}: {n1 * copies} rows, {int(rp[-1]) * copies} nnz, F={F} "
                          f"(fp64, row-parallel OpenMP, one copy at a time)"}
 
-    # which LD kernel the library picked: the software-pipelined one serves F = 32, 64, 128 on graphs with
-    # short rows and row-uniform weights (every AIG graph; not the transposed one, whose weights are explicit)
-    knob = -1 if args.ld_pipeline is None else args.ld_pipeline
-    ld_name = "ld_pipe_kernel" if F in (32, 64, 128) and (knob == 1 or (knob < 0 and not args.transposed)) else "ld_kernel"
+    # which LD kernel the library picked for this plan and F
+    mode = G.groot_plan_query(plan, "ld_pipelined")
+    ld_name = "ld_pipe_kernel" if (mode == 2 and F in (32, 64, 128)) or (mode == 1 and F in (64, 128)) else "ld_kernel"
     out = {
         "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak), 1024-bit CSA AIG, F=64",
         "value": round(gflops, 2),

@@ -234,14 +234,21 @@ groot_status groot_rows_gather(const int64_t *ids_dev, int64_t n, const float *X
 groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *in_dev,
                                 float *Y_dev, int32_t F, void *hip_stream);
 
+/* What the library decided for an uploaded plan, for diagnostics and benchmarks:
+ * "ld_pipelined" (0 the plain LD kernel always, 1 the pipelined one for F = 64
+ * and 128, 2 also for F = 32), "hd_pieces" (launch size of the HD kernel),
+ * "hd_partials" (partial-sum slots of split high-degree rows).
+ * Errors: EINVAL (NULL, unknown name, plan not uploaded). */
+groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t *value);
+
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
  * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
  * 64..4096 non-zeros, read by groot_spmm_plan), "sage_gap" (0..4, the pause
  * between matrix instructions in groot_sage_layer_forward, read at each call)
- * and "ld_pipeline" (which LD kernel serves F = 32, 64, 128: 1 the software-
- * pipelined one, 0 the plain one, -1 (default) the pipelined one when at least
- * 90 % of the low-degree rows have at most 6 entries and the weights are
- * row-uniform; read by groot_plan_upload).
+ * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
+ * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one for F = 64
+ * and 128 when at least 99.9 % of the low-degree rows have at most 6 entries
+ * and the weights are row-uniform; read by groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

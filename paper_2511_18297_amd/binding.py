@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
 ]
@@ -59,6 +59,7 @@ _lib.groot_spmm_execute.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.groot_spmm_execute_phases.argtypes = [_vp, _vp, _vp, _i32, _u32, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
 _lib.groot_plan_free.argtypes = [_vp]
 _lib.groot_plan_free.restype = None
 _lib.groot_partition_regrow.argtypes = [_vp, _i32, _vp, _u32, _pp]
@@ -257,6 +258,12 @@ def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_de
                                         _dev_ptr(ld_rows, "ld_rows"), _dev_ptr(ld_rows_by_degree, "ld_rows_by_degree"),
                                         _dev_ptr(ld_deg_offsets, "ld_deg_offsets"), _dev_ptr(counts, "counts"),
                                         _stream_handle(stream)))
+
+
+def groot_plan_query(pl: Plan, what: str) -> int:
+    out = _i64(0)
+    _check(_lib.groot_plan_query(pl.handle, what.encode(), ctypes.byref(out)))
+    return out.value
 
 
 def groot_partition_regrow(g: Graph, num_parts: int, part_of=None, flags: int = GROOT_REGROW) -> Parts:

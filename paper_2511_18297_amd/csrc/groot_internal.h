@@ -59,7 +59,7 @@ struct DevicePlan {
     int xcd_remap = 1;
     float *zero_row = nullptr;      // kZeroRowFloats zeros (the gather target of unused slots in the pipelined
                                     // kernels), followed by kTrashFloats that those kernels may overwrite
-    int ld_pipelined = 0;           // low-degree rows go through the pipelined LD kernel when F allows
+    int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
 };
 
 constexpr int kZeroRowFloats = 128;

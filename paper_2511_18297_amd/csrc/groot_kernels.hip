@@ -217,7 +217,9 @@ static int lanes_for(int32_t F4)
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
 {
     const int32_t F4 = F / 4;
-    if (dp.ld_pipelined && dp.zero_row && (F4 == 8 || F4 == 16 || F4 == 32)) return launch_ld_pipelined(dp, X, Y, F, stream);
+    // the pipelined kernel pays off from F = 64 on (F = 32: equal on the large graphs, slower on small ones)
+    if (dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
+        return launch_ld_pipelined(dp, X, Y, F, stream);
     const int64_t per_xcd = (dp.n_tiles + kXcds - 1) / kXcds;
     const int remap = dp.xcd_remap && dp.n_tiles >= 4 * kXcds;
     const int64_t grid = remap ? per_xcd * kXcds : dp.n_tiles;

@@ -58,6 +58,20 @@ def _aig_case(n, batch, flags=G.GROOT_DEFAULT_FLAGS):
     return aig, g, o
 
 
+@pytest.mark.parametrize("n_bits,batch,F,T", [(64, 2, 32, 32), (32, 3, 64, 16), (96, 1, 128, 64)])
+def test_booth_multiplier_degree_profile(torch_cuda, n_bits, batch, F, T):
+    """Radix-4 Booth multipliers: about 3.5 n high-degree rows of n to 4n entries (recoding signals and
+    primary inputs), many of them split into several pieces, next to the short rows."""
+    aig = wl.booth_multiplier_aig(n_bits)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    X = wl.uniform_features_numpy(40 + n_bits, 0, aig.num_nodes * batch, F)
+    Y, plan, _, _ = _run(torch_cuda, g, T, X)
+    assert G.groot_plan_view(plan)["n_hd"] >= 2 * n_bits * batch
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, f"booth {n_bits}x{batch} F={F} T={T}")
+
+
 def test_config1_32bit_structural_features(torch_cuda):
     """32-bit multiplier, F = 32, node-type / polarity columns + U(-1,1), T = 32."""
     aig, g, (rowptr, col, val, pol) = _aig_case(32, 1)

@@ -43,6 +43,21 @@ def test_graph_build_bit_exact(n, batch, flags):
     assert np.array_equal(v["pol"], pol)
 
 
+@pytest.mark.parametrize("n,batch", [(8, 1), (16, 3), (48, 2)])
+def test_graph_build_bit_exact_on_booth_multipliers(n, batch):
+    aig = wl.booth_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    v = G.groot_graph_view(g)
+    rowptr, col, val, pol = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    assert np.array_equal(v["rowptr"], rowptr) and np.array_equal(v["col"], col)
+    assert np.array_equal(v["val"].view(np.uint32), val.view(np.uint32)) and np.array_equal(v["pol"], pol)
+    for T in (8, 32):
+        pv = G.groot_plan_view(G.groot_spmm_plan(g, T))
+        want = oracle.plan(rowptr, T)
+        for key in ("row_class", "hd_rows", "ld_rows", "ld_rows_by_degree", "ld_deg_offsets"):
+            assert np.array_equal(pv[key], want[key]), key
+
+
 def test_graph_build_hand_made_aig_with_repeated_fanin():
     # node 3 = AND(x, !x) on the same driver, node 4 = AND(!2, 3), PO on !4
     typ = np.array([0, 0, 1, 1, 1, 2], dtype=np.uint8)
@@ -248,6 +263,8 @@ def test_device_plan_lists_host_checks():
     assert "not on the device" in G.groot_last_error()
     assert lib.groot_plan_lists_device(plan.handle, None, dummy, dummy, dummy, dummy, dummy, None) == G.GROOT_EINVAL
     assert lib.groot_plan_lists_device(None, dummy, dummy, dummy, dummy, dummy, dummy, None) == G.GROOT_EINVAL
+    with pytest.raises(G.GrootError):
+        G.groot_plan_query(plan, "ld_pipelined")          # not uploaded
 
 
 def test_build_module_is_importable_without_loading_the_library():

@@ -135,6 +135,50 @@ def test_multiplier_function_equals_integer_product(n):
         assert got == a * b, (n, a, b)
 
 
+@pytest.mark.parametrize("n", [2, 4, 6, 8, 16, 32, 64, 96])
+def test_booth_multiplier_function_and_degree_profile(n):
+    """The radix-4 Booth generator multiplies (every pattern through the oracle's bit-parallel AIG
+    evaluation), is a well-formed AIG, and has the degree profile it is there for: the recoding
+    signals of the n/2 + 1 digit rows are high-degree nodes next to the primary inputs."""
+    aig = wl.booth_multiplier_aig(n)
+    n1 = aig.num_nodes
+    assert (aig.type[:2 * n] == 0).all() and (aig.type[-2 * n:] == 2).all() and (aig.type[2 * n:-2 * n] == 1).all()
+    ids = np.arange(n1)
+    inner = aig.type == 1
+    assert ((aig.fanin0[inner] >> 1) < ids[inner]).all() and ((aig.fanin1[inner] >> 1) < ids[inner]).all()   # topological
+    assert (aig.fanin0[inner] >= 0).all() and (aig.fanin1[inner] >= 0).all()                                 # no constants left
+    assert (aig.fanin0[-2 * n:] == aig.fanin1[-2 * n:]).all() and (aig.fanin0[-2 * n:] == aig.po_driver).all()
+    rng = random.Random(2000 + n)
+    ops = [(rng.getrandbits(n), rng.getrandbits(n)) for _ in range(58)]
+    ops += [(0, 0), ((1 << n) - 1, (1 << n) - 1), (1, (1 << n) - 1), ((1 << n) - 1, 1),
+            (1 << (n - 1), 1 << (n - 1)), ((1 << n) - 1, (1 << n) - 2)]
+    pi = np.zeros(2 * n, dtype=np.uint64)
+    for pat, (a, b) in enumerate(ops):
+        for i in range(n):
+            if (a >> i) & 1:
+                pi[i] |= np.uint64(1) << np.uint64(pat)
+            if (b >> i) & 1:
+                pi[n + i] |= np.uint64(1) << np.uint64(pat)
+    words = oracle.aig_simulate(aig.type, aig.fanin0, aig.fanin1, pi)
+    po = words[-2 * n:]
+    for pat, (a, b) in enumerate(ops):
+        got = sum(((int(po[k]) >> pat) & 1) << k for k in range(2 * n))
+        assert got == a * b, (n, a, b)
+    if n >= 32:
+        rowptr, _, _, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+        deg = np.diff(rowptr)
+        hot = int((deg >= n).sum())
+        assert 2 * n <= hot <= 4 * n            # about 3.5 n rows of n .. 4n+8 entries (CSA: exactly 2n rows of n+1)
+        assert deg.max() >= 2 * n
+        assert (deg <= 6).mean() > 0.98
+
+
+def test_booth_generator_rejects_odd_widths():
+    for n in (0, 1, 3, 7, 4096):
+        with pytest.raises(ValueError):
+            wl.booth_multiplier_aig(n)
+
+
 @pytest.mark.parametrize("n", [2, 3, 6, 8, 32, 256])
 def test_gate_counts_closed_form(n):
     """n^2 partial products + n half adders (3 ANDs) + n(n-2) full adders (7 ANDs)."""

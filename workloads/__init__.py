@@ -29,7 +29,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libworkloads.so")
-_SOURCES = [os.path.join(_HERE, "csa_aig.c"), os.path.join(_HERE, "stress.c")]
+_SOURCES = [os.path.join(_HERE, "csa_aig.c"), os.path.join(_HERE, "stress.c"), os.path.join(_HERE, "booth_aig.c")]
 _lib = None
 
 PI, AND, PO = 0, 1, 2
@@ -59,6 +59,8 @@ def _load():
         lib.wl_csa_generate.argtypes = [ctypes.c_int32, u8p, i32p, i32p, i32p]
         lib.wl_csa_generate_labeled.restype = ctypes.c_int64
         lib.wl_csa_generate_labeled.argtypes = [ctypes.c_int32, u8p, i32p, i32p, i32p, u8p]
+        lib.wl_booth_generate.restype = ctypes.c_int64
+        lib.wl_booth_generate.argtypes = [ctypes.c_int32, u8p, i32p, i32p, i32p]
         lib.wl_stress_rowptr.restype = ctypes.c_int64
         lib.wl_stress_rowptr.argtypes = [ctypes.c_uint64] + [ctypes.c_int64] * 4 + [i64p]
         lib.wl_stress_fill.restype = ctypes.c_int32
@@ -101,6 +103,25 @@ def csa_multiplier_aig(n_bits: int) -> Aig:
                                       _ptr(label, ctypes.c_uint8))
     if got != n1:
         raise RuntimeError(f"CSA generator wrote {got} nodes, expected {n1}")
+    return Aig(n_bits, typ, f0, f1, po, label)
+
+
+def booth_multiplier_aig(n_bits: int) -> Aig:
+    """Radix-4 Booth multiplier (unsigned, n_bits even): the degree profile of the paper's Booth dataset.
+    Labels: 4 = PI, 3 = AND, 0 = PO (no XOR / MAJ roots are marked)."""
+    lib = _load()
+    n1 = int(lib.wl_booth_generate(n_bits, None, None, None, None))
+    if n1 < 0:
+        raise ValueError("n_bits must be even, 2..2048")
+    typ = np.empty(n1, dtype=np.uint8)
+    f0 = np.empty(n1, dtype=np.int32)
+    f1 = np.empty(n1, dtype=np.int32)
+    po = np.empty(2 * n_bits, dtype=np.int32)
+    got = lib.wl_booth_generate(n_bits, _ptr(typ, ctypes.c_uint8), _ptr(f0, ctypes.c_int32),
+                                _ptr(f1, ctypes.c_int32), _ptr(po, ctypes.c_int32))
+    if got != n1:
+        raise RuntimeError(f"Booth generator wrote {got} nodes, expected {n1}")
+    label = np.where(typ == 0, 4, np.where(typ == 1, 3, 0)).astype(np.uint8)
     return Aig(n_bits, typ, f0, f1, po, label)
 
 
