@@ -139,7 +139,8 @@ groot_status groot_plan_upload(groot_plan *plan, int32_t max_F);
  *   overlapping.  F: multiple of 4, 4 <= F <= 512.  Y is overwritten entirely;
  *   empty rows give 0.  Accumulation is fp32.
  * hip_stream: a hipStream_t (NULL = default stream).  The call only enqueues
- *   work and never synchronises.  At most one execute per plan may be in
+ *   kernels: it never synchronises, allocates or clears memory, so it may be
+ *   recorded into a HIP graph by stream capture and replayed.  At most one execute per plan may be in
  *   flight at a time (the plan owns the scratch for split rows).
  * Errors: EINVAL (NULL, alignment, F, plan not uploaded), EHIP (launch failed).
  * groot_spmm_execute_phases runs a subset of the kernels (bit-or of

@@ -296,6 +296,49 @@ def test_execute_on_side_stream(torch_cuda):
     assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "side stream")
 
 
+def test_execute_and_fused_layer_replay_from_a_hip_graph(torch_cuda):
+    """The execute calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+    two-layer forward pass can be captured into a HIP graph once and replayed: every replay, with new
+    inputs written into the captured buffers and eager work in between, must equal the eager result."""
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(40, 2)
+    n, F = 2 * aig.num_nodes, 64
+    plan = G.groot_spmm_plan(g, 16)
+    G.groot_plan_upload(plan, F)
+    rng = np.random.default_rng(9)
+    Wn, Ws = (torch.from_numpy(rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32)).cuda() for _ in range(2))
+    X = torch.zeros((n, F), device="cuda")
+    A, H, Y = torch.empty_like(X), torch.empty_like(X), torch.empty_like(X)
+
+    def forward():
+        G.groot_spmm_execute(plan, X, A, F)                              # plain aggregation
+        G.groot_sage_layer_forward(plan, A, Wn, Ws, None, True, H, F)    # fused layer on top of it
+        G.groot_spmm_execute(plan, H, Y, F)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        X.copy_(wl.uniform_features(70, 0, n, F, device="cuda"))
+        forward()                                                        # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        forward()
+    for seed in (71, 72, 73):
+        X.copy_(wl.uniform_features(seed, 0, n, F, device="cuda"))
+        Y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = Y.clone()
+        Y.fill_(float("nan"))
+        forward()                                                        # eager, same buffers
+        torch.cuda.synchronize()
+        assert torch.equal(replayed, Y), f"replay with seed {seed} differs from the eager run"
+        Y64, S = oracle.spmm_f64(rowptr, col, val, H.cpu().numpy())
+        assert_close_to_oracle(replayed.cpu().numpy(), Y64, S, f"graph replay, seed {seed}")
+
+
 @pytest.mark.parametrize("n,batch,P,regrow", [(32, 2, 4, 1), (64, 1, 16, 1), (32, 1, 3, 0)])
 def test_partitioned_mode_scatters_back_to_full_result(torch_cuda, n, batch, P, regrow):
     """rows_gather -> per-part SpMM -> rows_scatter reproduces the full-graph
