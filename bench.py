@@ -35,6 +35,9 @@ WORKLOADS = {
     "booth256_b16_F32": (256, 16, 32, 4, 32),
     "booth64_b16_F32": (64, 16, 32, 4, 32),
     "booth512_b16_F64": (512, 16, 64, 4, 32),
+    # shape of the 4-LUT-mapped carry-save multiplier (rows of 7 entries; adjacency only, via groot_graph_from_csr)
+    "lut4csa512_b16_F32": (512, 16, 32, 5, 32),
+    "lut4csa256_b16_F32": (256, 16, 32, 5, 32),
 }
 
 
@@ -211,8 +214,15 @@ def main():
     bits, batch, F, seed, T = WORKLOADS[name]
 
     t0 = time.time()
-    aig = wl.booth_multiplier_aig(bits) if name.startswith("booth") else wl.csa_multiplier_aig(bits)
-    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    lut = wl.lut4_csa_graph(bits, 1) if name.startswith("lut4") else None
+    if lut is not None:
+        if args.transposed or args.partitioned or args.sage_layer:
+            sys.exit("the LUT-shape workloads run the plain SpMM only")
+        aig = None
+        g = G.groot_graph_from_csr(*(lambda b: (b.rowptr, b.col, b.val))(wl.lut4_csa_graph(bits, batch)))
+    else:
+        aig = wl.booth_multiplier_aig(bits) if name.startswith("booth") else wl.csa_multiplier_aig(bits)
+        g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
     if args.transposed:
         g = G.groot_graph_transpose(g)
     view = G.groot_graph_view(g)
@@ -288,8 +298,11 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
 
-        n1 = aig.num_nodes
-        rp, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
+        n1 = lut.n if lut is not None else aig.num_nodes
+        if lut is not None:
+            rp, col, val = lut.rowptr, lut.col, lut.val
+        else:
+            rp, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 1)
         if args.transposed:
             rp, col, val = oracle.csr_transpose(rp, col, val)
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))

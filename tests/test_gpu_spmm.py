@@ -72,6 +72,18 @@ def test_booth_multiplier_degree_profile(torch_cuda, n_bits, batch, F, T):
     assert_close_to_oracle(Y, Y64, S, f"booth {n_bits}x{batch} F={F} T={T}")
 
 
+@pytest.mark.parametrize("n_bits,batch,F,T", [(48, 2, 32, 32), (32, 1, 64, 8), (24, 3, 128, 7)])
+def test_lut4_mapped_multiplier_shape(torch_cuda, n_bits, batch, F, T):
+    """4-LUT-mapped carry-save array: interior rows of 7 entries (longer than the pipelined kernel's 6
+    slots: there they go through its plain loop), 2n rows of 2n+1; T = 7 makes almost every row high-degree."""
+    s = wl.lut4_csa_graph(n_bits, batch)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    X = wl.uniform_features_numpy(60 + n_bits, 0, s.n, F)
+    Y, plan, _, _ = _run(torch_cuda, g, T, X)
+    Y64, S = oracle.spmm_f64(s.rowptr, s.col, s.val, X)
+    assert_close_to_oracle(Y, Y64, S, f"lut4 {n_bits}x{batch} F={F} T={T}")
+
+
 def test_config1_32bit_structural_features(torch_cuda):
     """32-bit multiplier, F = 32, node-type / polarity columns + U(-1,1), T = 32."""
     aig, g, (rowptr, col, val, pol) = _aig_case(32, 1)

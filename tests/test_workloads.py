@@ -250,3 +250,27 @@ def test_stress_graph_distribution():
     # regenerating gives the same graph
     g2 = wl.stress_graph(4, n, window=window, dmin=dmin, dmax=dmax)
     assert np.array_equal(g.col, g2.col) and np.array_equal(g.rowptr, g2.rowptr)
+
+
+@pytest.mark.parametrize("n,batch", [(2, 1), (5, 3), (32, 2)])
+def test_lut4_graph_shape(n, batch):
+    """Symmetric, self-loops, sorted rows, mean weights bit-exact, block-diagonal copies, and the degree
+    profile the generator documents (2n input rows of 2n+1 entries, interior LUT rows of 7)."""
+    g = wl.lut4_csa_graph(n, batch)
+    n1 = g.n // batch
+    assert n1 == 2 * n + 2 * n * n + 2 * n + 2 * n
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    pairs = set(zip(rows.tolist(), g.col.tolist()))
+    assert all((c, r) in pairs for r, c in pairs)                       # symmetric
+    assert all((v, v) in pairs for v in range(g.n))                     # self-loops
+    assert all(r // n1 == c // n1 for r, c in pairs)                    # copies do not touch
+    for v in range(g.n):
+        seg = g.col[g.rowptr[v]:g.rowptr[v + 1]]
+        assert (np.diff(seg) > 0).all()
+    deg = np.diff(g.rowptr)
+    want = (np.float32(1.0) / deg.astype(np.float32)).astype(np.float32)
+    assert np.array_equal(g.val.view(np.uint32), np.repeat(want, deg).view(np.uint32))
+    assert (deg[:2 * n] == 2 * n + 1).all()                             # every input feeds 2n LUTs
+    if n >= 5:
+        assert np.bincount(deg).argmax() == 7
+    assert np.array_equal(deg[:n1], deg[n1 * (batch - 1):])             # same profile in every copy

@@ -274,3 +274,69 @@ def stress_graph(seed: int, n: int, window: int = 4096, dmin: int = 64, dmax: in
 
 def stress_is_heavy(seed: int, row: int) -> bool:
     return bool(_load().wl_stress_is_heavy(seed, row))
+
+
+# ----------------------------------------------------------------------------
+# 4-LUT-mapped carry-save multiplier (graph shape only)
+# ----------------------------------------------------------------------------
+def lut4_csa_graph(n_bits: int, batch: int = 1) -> Csr:
+    """Shape of a carry-save array multiplier after mapping to 4-input LUTs (stand-in for the paper's
+    FPGA-mapped dataset, which needs ABC): every array cell (i, j) becomes two LUT nodes, sum and carry,
+    with the same four fanins a_j, b_i, sum(i-1, j+1), carry(i-1, j) (those that exist); a last row of
+    n sum/carry LUT pairs forms the ripple adder; 2n primary outputs have one fanin each.  No logic
+    functions are modelled: only the adjacency.  Node order: a_0.., b_0.., cells row by row (sum, carry
+    interleaved), adder row, outputs.  Returns the symmetric adjacency with self-loops, mean-normalised
+    (weights fl(1/row length)), replicated block-diagonally `batch` times.
+    Degree profile: 2n primary-input rows of 2n+1 entries (the high-degree class), interior LUT rows of
+    7 entries (4 fanins, 2 fanouts, itself): longer than an AIG's 4-5."""
+    import scipy.sparse as sp
+
+    n = n_bits
+    if n < 2 or n > 2048 or batch < 1:
+        raise ValueError("bad LUT graph parameters")
+    a = np.arange(n)
+    b = n + np.arange(n)
+    cell0 = 2 * n
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    s_id = cell0 + 2 * (i * n + j)
+    c_id = s_id + 1
+    src, dst = [], []
+
+    def edges(frm, to, mask=None):
+        frm, to = np.broadcast_arrays(frm, to)
+        if mask is not None:
+            frm, to = frm[mask], to[mask]
+        src.append(np.asarray(frm).ravel())
+        dst.append(np.asarray(to).ravel())
+
+    for out in (s_id, c_id):
+        edges(a[j], out)
+        edges(b[i], out)
+        up = (i > 0) & (j + 1 < n)
+        edges(np.where(up, s_id - 2 * n + 2, 0), out, up)            # sum(i-1, j+1)
+        edges(np.where(i > 0, c_id - 2 * n, 0), out, i > 0)          # carry(i-1, j)
+    add0 = cell0 + 2 * n * n
+    k = np.arange(n)
+    for out in (add0 + 2 * k, add0 + 2 * k + 1):                      # adder bit k: sum and carry LUTs
+        edges(np.where(k + 1 < n, s_id[n - 1, np.minimum(k + 1, n - 1)], 0), out, k + 1 < n)
+        edges(c_id[n - 1, k], out)
+        edges(np.where(k > 0, add0 + 2 * (k - 1) + 1, 0), out, k > 0)
+    po0 = add0 + 2 * n
+    edges(s_id[:, 0], po0 + np.arange(n))                             # low product bits leave the array's first column
+    edges(add0 + 2 * k, po0 + n + k)
+    n1 = po0 + 2 * n
+    src = np.concatenate(src).astype(np.int64)
+    dst = np.concatenate(dst).astype(np.int64)
+    ones = np.ones(src.shape[0], dtype=np.int8)
+    adj = sp.coo_matrix((ones, (src, dst)), shape=(n1, n1)).tocsr()
+    adj = ((adj + adj.T + sp.identity(n1, dtype=np.int8, format="csr")) > 0).astype(np.int8).tocsr()
+    adj.sort_indices()
+    rp1 = adj.indptr.astype(np.int64)
+    col1 = adj.indices.astype(np.int64)
+    deg = np.diff(rp1)
+    val1 = np.repeat(np.float32(1.0) / deg.astype(np.float32), deg).astype(np.float32)
+    nnz1 = int(rp1[-1])
+    rowptr = np.concatenate([[0]] + [rp1[1:] + c * nnz1 for c in range(batch)]).astype(np.int64)
+    col = np.concatenate([col1 + c * n1 for c in range(batch)]).astype(np.int32)
+    val = np.tile(val1, batch)
+    return Csr(int(n1) * batch, rowptr, col, val)
