@@ -151,6 +151,25 @@ groot_status groot_spmm_execute(const groot_plan *plan, const float *X_dev, floa
 groot_status groot_spmm_execute_phases(const groot_plan *plan, const float *X_dev, float *Y_dev,
                                        int32_t F, uint32_t phases, void *hip_stream);
 /* ---------------------------------------------------------------------------
+ * groot_spmm_execute_rows -- the same product restricted to the first n_rows
+ * rows, each written where the caller wants it:
+ *     Y[out_ids[r], :] = (A_hat X)[r, :]      r < n_rows      (out_ids NULL: Y[r, :])
+ * Paper: Section "GNN and Edge Re-growth After Partition", Algorithm 1: on a
+ * re-grown sub-graph only the rows of S_p are results (local ids 0..n_owned-1,
+ * the boundary rows behind them are computed only to be dropped), and they
+ * belong at their global positions.  With n_rows = n_owned and out_ids = the
+ * first n_owned entries of the part's global_id this writes the part's result
+ * straight into the full Y: no boundary rows are computed, no copy of Y_p, no
+ * scatter pass.
+ * out_ids_dev (device, int64[n_rows], may be NULL): distinct row numbers of Y;
+ * the caller guarantees that Y has those rows and does not overlap X (neither
+ * can be checked here).  Other rows of Y are not touched.  Stream, scratch
+ * and error behaviour as groot_spmm_execute; n_rows outside [0, N] is EINVAL.
+ * ------------------------------------------------------------------------- */
+groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev, float *Y_dev,
+                                     int32_t F, int64_t n_rows, const int64_t *out_ids_dev,
+                                     void *hip_stream);
+/* ---------------------------------------------------------------------------
  * groot_sage_layer_forward -- one GraphSAGE-mean layer with the aggregation fused in:
  *     H = act( (A_hat X) Wn + X Ws + b ),   act = ReLU if relu != 0, identity otherwise.
  * Paper: Section "GNN and Edge Re-growth After Partition" (the GraphSAGE layer takes

@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
 ]
@@ -57,6 +57,7 @@ _lib.groot_plan_view.argtypes = [_vp, _pi64, _pi64, _pp, _pp, _pp, _pp, _pp]
 _lib.groot_plan_upload.argtypes = [_vp, _i32]
 _lib.groot_spmm_execute.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.groot_spmm_execute_phases.argtypes = [_vp, _vp, _vp, _i32, _u32, _vp]
+_lib.groot_spmm_execute_rows.argtypes = [_vp, _vp, _vp, _i32, _i64, _vp, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
@@ -233,6 +234,16 @@ def groot_spmm_execute(pl: Plan, X, Y, F: int = None, stream=None) -> None:
 def groot_spmm_execute_phases(pl: Plan, X, Y, F: int, phases: int, stream=None) -> None:
     _check(_lib.groot_spmm_execute_phases(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, phases,
                                           _stream_handle(stream)))
+
+
+def groot_spmm_execute_rows(pl: Plan, X, Y, F: int, n_rows: int, out_ids=None, stream=None) -> None:
+    import torch
+
+    if out_ids is not None and (out_ids.dtype != torch.int64 or out_ids.numel() < n_rows):
+        raise TypeError("out_ids must be int64 with at least n_rows entries")
+    _check(_lib.groot_spmm_execute_rows(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, n_rows,
+                                        None if out_ids is None else _dev_ptr(out_ids, "out_ids"),
+                                        _stream_handle(stream)))
 
 
 def groot_sage_layer_forward(pl: Plan, X, Wn, Ws, bias, relu: bool, H, F: int = None, stream=None) -> None:

@@ -522,6 +522,24 @@ extern "C" groot_status groot_spmm_execute_phases(const groot_plan *plan, const 
     return GROOT_OK;
 }
 
+extern "C" groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev, float *Y_dev, int32_t F,
+                                                int64_t n_rows, const int64_t *out_ids_dev, void *hip_stream)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_spmm_execute_rows: NULL plan");
+    groot_status st = check_features("groot_spmm_execute_rows", X_dev, Y_dev, F);
+    if (st != GROOT_OK) return st;
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_spmm_execute_rows: plan is not on the device (call groot_plan_upload)");
+    if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_spmm_execute_rows: F exceeds the max_F given to groot_plan_upload");
+    if (n_rows < 0 || n_rows > plan->dev.n) return fail(GROOT_EINVAL, "groot_spmm_execute_rows: n_rows outside [0, N]");
+    if (n_rows == 0) return GROOT_OK;
+    const RowOut out{out_ids_dev, n_rows};
+    int err = launch_ld(plan->dev, X_dev, Y_dev, F, hip_stream, &out);
+    if (!err && plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, Y_dev, F, hip_stream, &out);
+    if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, Y_dev, F, hip_stream, &out);
+    if (err) return fail(GROOT_EHIP, std::string("groot_spmm_execute_rows: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" groot_status groot_spmm_execute(const groot_plan *plan, const float *X_dev, float *Y_dev,
                                            int32_t F, void *hip_stream)
 {

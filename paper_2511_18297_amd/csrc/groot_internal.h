@@ -66,11 +66,18 @@ constexpr int kZeroRowFloats = 128;
 constexpr int kTrashFloats = 2048;
 constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64 rows)
 
+// Optional restriction and redirection of the output rows: only rows [0, n_out) are computed, and row r is
+// written to Y[ids[r]] (ids == NULL: to Y[r]).  Device pointer.
+struct RowOut {
+    const int64_t *ids;
+    int64_t n_out;
+};
+
 // Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).
-int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
+int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
 int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);   // F = 32, 64, 128
-int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);
-int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream);
+int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
+int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);

@@ -26,7 +26,7 @@ template <int L, int W>
 __device__ __forceinline__ void ld_tile(char *smem, int64_t tile, const int64_t *__restrict__ rowptr,
                                         const int32_t *__restrict__ col, const float *__restrict__ val,
                                         const v4f *__restrict__ X, v4f *__restrict__ Y, int64_t n,
-                                        int32_t F4, int32_t T)
+                                        int32_t F4, int32_t T, const int64_t *__restrict__ out_ids, int64_t n_out)
 {
     constexpr int G = kWave / L;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
@@ -58,19 +58,20 @@ __device__ __forceinline__ void ld_tile(char *smem, int64_t tile, const int64_t 
     for (int it = 0; it < kLdTileRows / G; ++it) {
         const int lr = it * G + g;
         const int64_t row = base + lr;
-        if (row >= n) break;
+        if (row >= n_out) break;                         // n_out <= n: rows past it are not wanted
+        const int64_t orow = out_ids ? out_ids[row] : row;
         if (staged) {
             const int64_t s = s_rel[lr], e = s_rel[lr + 1];
             for (int32_t ff = f; ff < F4; ff += L) {
                 v4f acc = ld_row_sum<W, true>(s, e, s_col, s_val, X, F4, ff);
-                __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
+                __builtin_nontemporal_store(acc, &Y[orow * F4 + ff]);
             }
         } else {
             const int64_t s = rowptr[row], e = rowptr[row + 1];
             if (e - s >= T) continue;
             for (int32_t ff = f; ff < F4; ff += L) {
                 v4f acc = ld_row_sum<W, false>(s, e, col, val, X, F4, ff);
-                __builtin_nontemporal_store(acc, &Y[row * F4 + ff]);
+                __builtin_nontemporal_store(acc, &Y[orow * F4 + ff]);
             }
         }
     }
@@ -86,7 +87,8 @@ __device__ __forceinline__ void ld_tile(char *smem, int64_t tile, const int64_t 
 template <int L, int W>
 __device__ __forceinline__ void hd_piece(char *smem, const HdChunk ch, const int32_t *__restrict__ col,
                                          const float *__restrict__ val, const v4f *__restrict__ X,
-                                         v4f *__restrict__ Y, v4f *__restrict__ partials, int32_t F4)
+                                         v4f *__restrict__ Y, v4f *__restrict__ partials, int32_t F4,
+                                         const int64_t *__restrict__ out_ids)
 {
     constexpr int G = kBlock / L;
     v4f(*s_red)[L] = (v4f(*)[L])smem;                    // [G][L]
@@ -129,7 +131,7 @@ __device__ __forceinline__ void hd_piece(char *smem, const HdChunk ch, const int
         }
         if (g == 0 && live) {
             v4f sum = s_red[0][f];
-            if (ch.slot < 0) Y[(int64_t)ch.row * F4 + ff] = sum;
+            if (ch.slot < 0) Y[(out_ids ? out_ids[ch.row] : (int64_t)ch.row) * F4 + ff] = sum;
             else partials[(int64_t)ch.slot * F4 + ff] = sum;
         }
         __syncthreads();
@@ -143,12 +145,13 @@ __global__ __launch_bounds__(kBlock) void ld_kernel(const int64_t *__restrict__ 
                                                     const float *__restrict__ val,
                                                     const v4f *__restrict__ X, v4f *__restrict__ Y,
                                                     int64_t n, int32_t F4, int32_t T, int64_t n_tiles,
-                                                    int64_t blocks_per_xcd, int remap)
+                                                    int64_t blocks_per_xcd, int remap,
+                                                    const int64_t *__restrict__ out_ids, int64_t n_out)
 {
     __shared__ __align__(16) char smem[kLdsBytes];
     const int64_t tile = logical_block(blocks_per_xcd, remap);
     if (tile >= n_tiles) return;
-    ld_tile<L, W>(smem, tile, rowptr, col, val, X, Y, n, F4, T);
+    ld_tile<L, W>(smem, tile, rowptr, col, val, X, Y, n, F4, T, out_ids, n_out);
 }
 
 // Block k of the HD launch computes piece k.
@@ -157,10 +160,13 @@ __global__ __launch_bounds__(kBlock) void hd_kernel(const HdChunk *__restrict__ 
                                                     const int32_t *__restrict__ col,
                                                     const float *__restrict__ val,
                                                     const v4f *__restrict__ X, v4f *__restrict__ Y,
-                                                    v4f *__restrict__ partials, int32_t F4)
+                                                    v4f *__restrict__ partials, int32_t F4,
+                                                    const int64_t *__restrict__ out_ids, int64_t n_out)
 {
     __shared__ __align__(16) char smem[kBlock * sizeof(v4f)];
-    hd_piece<L, W>(smem, chunks[blockIdx.x], col, val, X, Y, partials, F4);
+    const HdChunk ch = chunks[blockIdx.x];
+    if (ch.row >= n_out) return;                         // the whole workgroup: a row that is not wanted
+    hd_piece<L, W>(smem, ch, col, val, X, Y, partials, F4, out_ids);
 }
 
 // Y[row] = partials[first] + ... + partials[first+count-1], in that order.
@@ -168,16 +174,19 @@ template <int L>
 __global__ __launch_bounds__(kBlock) void hd_finish_kernel(const HdSplitRow *__restrict__ rows,
                                                            int64_t n_rows,
                                                            const v4f *__restrict__ partials,
-                                                           v4f *__restrict__ Y, int32_t F4)
+                                                           v4f *__restrict__ Y, int32_t F4,
+                                                           const int64_t *__restrict__ out_ids, int64_t n_out)
 {
     constexpr int G = kBlock / L;
     const int64_t k = (int64_t)blockIdx.x * G + threadIdx.x / L;
     if (k >= n_rows) return;
     const HdSplitRow sr = rows[k];
+    if (sr.row >= n_out) return;
+    const int64_t orow = out_ids ? out_ids[sr.row] : (int64_t)sr.row;
     for (int32_t ff = threadIdx.x % L; ff < F4; ff += L) {
         v4f acc = {0.f, 0.f, 0.f, 0.f};
         for (int32_t c = 0; c < sr.count; ++c) acc += partials[(int64_t)(sr.first + c) * F4 + ff];
-        Y[(int64_t)sr.row * F4 + ff] = acc;
+        Y[orow * F4 + ff] = acc;
     }
 }
 
@@ -214,46 +223,54 @@ static int lanes_for(int32_t F4)
     default: { constexpr int kW = kExplicit; GROOT_DISPATCH_L(L, CALL) } break; \
     }
 
-int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
+int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out)
 {
     const int32_t F4 = F / 4;
+    const int64_t *out_ids = out ? out->ids : nullptr;
+    const int64_t n_out = out ? out->n_out : dp.n;
     // the pipelined kernel pays off from F = 64 on (F = 32: equal on the large graphs, slower on small ones)
-    if (dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
+    if (!out && dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
         return launch_ld_pipelined(dp, X, Y, F, stream);
-    const int64_t per_xcd = (dp.n_tiles + kXcds - 1) / kXcds;
-    const int remap = dp.xcd_remap && dp.n_tiles >= 4 * kXcds;
-    const int64_t grid = remap ? per_xcd * kXcds : dp.n_tiles;
+    const int64_t n_tiles = (n_out + kRowsPerLdTile - 1) / kRowsPerLdTile;
+    if (n_tiles == 0) return 0;
+    const int64_t per_xcd = (n_tiles + kXcds - 1) / kXcds;
+    const int remap = dp.xcd_remap && n_tiles >= 4 * kXcds;
+    const int64_t grid = remap ? per_xcd * kXcds : n_tiles;
     if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
     if (!weights_ok(dp)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     GROOT_DISPATCH_LW(lanes_for(F4), dp.weight_mode,
                       (ld_kernel<kL, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                          dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)Y, dp.n, F4, dp.threshold, dp.n_tiles,
-                          per_xcd, remap)));
+                          dp.rowptr, dp.col, dp.val, (const v4f *)X, (v4f *)Y, dp.n, F4, dp.threshold, n_tiles,
+                          per_xcd, remap, out_ids, n_out)));
     return (int)hipGetLastError();
 }
 
-int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
+int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out)
 {
     const int32_t F4 = F / 4;
+    const int64_t *out_ids = out ? out->ids : nullptr;
+    const int64_t n_out = out ? out->n_out : dp.n;
     if (!grid_ok(dp.n_chunks)) return (int)hipErrorInvalidConfiguration;
     if (!weights_ok(dp)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     GROOT_DISPATCH_LW(lanes_for(F4), dp.weight_mode,
                       (hd_kernel<kL, kW><<<dim3((unsigned)dp.n_chunks), dim3(kBlock), 0, st>>>(
-                          dp.chunks, dp.col, dp.val, (const v4f *)X, (v4f *)Y, (v4f *)dp.partials, F4)));
+                          dp.chunks, dp.col, dp.val, (const v4f *)X, (v4f *)Y, (v4f *)dp.partials, F4, out_ids, n_out)));
     return (int)hipGetLastError();
 }
 
-int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream)
+int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, const RowOut *out)
 {
     const int32_t F4 = F / 4;
+    const int64_t *out_ids = out ? out->ids : nullptr;
+    const int64_t n_out = out ? out->n_out : dp.n;
     const int L = lanes_for(F4);
     const int64_t grid = (dp.n_split_rows + kBlock / L - 1) / (kBlock / L);
     if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
     hipStream_t st = (hipStream_t)stream;
     GROOT_DISPATCH_L(L, (hd_finish_kernel<kL><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                            dp.split_rows, dp.n_split_rows, (const v4f *)dp.partials, (v4f *)Y, F4)));
+                            dp.split_rows, dp.n_split_rows, (const v4f *)dp.partials, (v4f *)Y, F4, out_ids, n_out)));
     return (int)hipGetLastError();
 }
 

@@ -308,6 +308,60 @@ def test_execute_on_side_stream(torch_cuda):
     assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "side stream")
 
 
+@pytest.mark.parametrize("n,batch,P,T,F", [(32, 2, 4, 32, 64), (48, 1, 5, 8, 32), (24, 3, 2, 200, 20)])
+def test_partitioned_mode_owned_rows_written_in_place(torch_cuda, n, batch, P, T, F):
+    """groot_spmm_execute_rows on every re-grown part (first n_owned local rows, written at their global
+    ids) fills the full result without computing boundary rows or copying: every element against the
+    oracle on the full graph (every row is owned by exactly one part), and nothing else is written."""
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(n, batch)
+    N = batch * aig.num_nodes
+    X_np = wl.uniform_features_numpy(16, 0, N, F)
+    X = torch.from_numpy(X_np).cuda()
+    guard = 2
+    buf = torch.full((N + 2 * guard, F), float("nan"), device="cuda")
+    buf[:guard] = 555.0
+    buf[N + guard:] = 555.0
+    Y = buf[guard:N + guard]
+    parts = G.groot_partition_regrow(g, P)
+    for p in range(P):
+        pv = G.groot_parts_view(parts, p)
+        ids = torch.from_numpy(pv["global_id"].copy()).cuda()
+        Xp = torch.empty((ids.shape[0], F), device="cuda")
+        G.groot_rows_gather(ids, X, Xp, F)
+        plan = G.groot_spmm_plan(pv["sub"], T)
+        G.groot_plan_upload(plan, F)
+        G.groot_spmm_execute_rows(plan, Xp, Y, F, pv["n_owned"], ids)
+        torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert (out[:guard] == 555.0).all() and (out[N + guard:] == 555.0).all(), "wrote outside Y"
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
+    assert_close_to_oracle(out[guard:N + guard], Y64, S, f"owned rows in place, P={P} T={T} F={F}")
+
+
+def test_execute_rows_prefix_without_map_and_errors(torch_cuda):
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(40, 1)
+    N, F = aig.num_nodes, 64
+    X_np = wl.uniform_features_numpy(17, 0, N, F)
+    X = torch.from_numpy(X_np).cuda()
+    plan = G.groot_spmm_plan(g, 16)
+    G.groot_plan_upload(plan, F)
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
+    for n_rows in (0, 1, 37, 300, N - 1, N):            # 37 < 2n: cuts through the high-degree input rows
+        Y = torch.full((N, F), -3.0, device="cuda")
+        G.groot_spmm_execute_rows(plan, X, Y, F, n_rows)
+        torch.cuda.synchronize()
+        out = Y.cpu().numpy()
+        assert (out[n_rows:] == -3.0).all(), f"n_rows={n_rows}: wrote past the requested rows"
+        if n_rows:
+            assert_close_to_oracle(out[:n_rows], Y64[:n_rows], S[:n_rows], f"prefix of {n_rows} rows")
+    with pytest.raises(G.GrootError):
+        G.groot_spmm_execute_rows(plan, X, torch.empty_like(X), F, N + 1)
+    with pytest.raises(G.GrootError):
+        G.groot_spmm_execute_rows(plan, X, torch.empty_like(X), F, -1)
+
+
 def test_execute_and_fused_layer_replay_from_a_hip_graph(torch_cuda):
     """The execute calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
     two-layer forward pass can be captured into a HIP graph once and replayed: every replay, with new
