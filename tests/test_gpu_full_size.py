@@ -206,6 +206,23 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
         worst = max(worst, float((a - b).abs().max()))
     assert worst <= 1e-5, worst
 
+    # the owned rows of two parts computed straight into place (no boundary rows, no scatter pass)
+    Yp_full.fill_(float("nan"))
+    for p in (3, 12):
+        pw = G.groot_parts_view(parts, p)
+        ids = torch.from_numpy(pw["global_id"].copy()).cuda()
+        Xp = torch.empty((ids.shape[0], F), dtype=torch.float32, device="cuda")
+        G.groot_rows_gather(ids, X, Xp, F)
+        sub_plan = G.groot_spmm_plan(pw["sub"], T)
+        G.groot_plan_upload(sub_plan, F)
+        G.groot_spmm_execute_rows(sub_plan, Xp, Yp_full, F, pw["n_owned"], ids)
+        torch.cuda.synchronize()
+        owned = ids[:pw["n_owned"]]
+        assert float((Yp_full[owned] - Y[owned]).abs().max()) <= 1e-5
+        del sub_plan, Xp, ids, owned
+    written = int((~torch.isnan(Yp_full[:, 0])).sum())
+    assert written == sum(G.groot_parts_view(parts, p)["n_owned"] for p in (3, 12))
+
     # two parts, bit for bit against the oracle's Eq. (1)-(2)
     full_rowptr, full_col, full_val = view["rowptr"], view["col"], view["val"]
     part_of = oracle.part_of_default(n, n1, 16)
