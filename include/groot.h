@@ -267,8 +267,8 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
  * between matrix instructions in groot_sage_layer_forward, read at each call)
  * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
  * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one for F = 64
- * and 128 when at least 99.9 % of the low-degree rows have at most 6 entries
- * and the weights are row-uniform; read by groot_plan_upload).
+ * and 128 when at least 99.9 % of the low-degree rows have at most 6 entries;
+ * read by groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

@@ -478,10 +478,9 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         const int32_t short_deg = std::min<int32_t>(7, plan->threshold);
         const int64_t n_short = plan->ld_deg_offsets.empty() ? 0 : plan->ld_deg_offsets[short_deg];
         const int knob = tuning().ld_pipeline;
-        // with explicit weights the plain kernel measured faster (16.0 against 17.0 ms on the transposed headline graph)
         // (a tile with one longer row is redone by the plain loop after a drain of the pipeline: with 0.55 % of
         // such rows, the Booth multipliers, the pipelined kernel measured 11 % slower than the plain one)
-        d.ld_pipelined = knob > 0 ? 2 : (knob < 0 && n_ld > 0 && n_short * 1000 >= n_ld * 999 && !need_val) ? 1 : 0;
+        d.ld_pipelined = knob > 0 ? 2 : (knob < 0 && n_ld > 0 && n_short * 1000 >= n_ld * 999) ? 1 : 0;
     }
     d.n_chunks = (int64_t)plan->chunks.size();
     d.n_tiles = (g->n + kRowsPerLdTile - 1) / kRowsPerLdTile;

@@ -20,6 +20,8 @@
 //    that is not "simple" (a row with more than kPipeD entries, a high-degree row, the ragged last tile)
 //    are stored to a trash area instead of Y, and the tile is then redone by a plain, unoverlapped path.
 //  * No workgroup barrier anywhere: wavefronts share nothing.
+#include <type_traits>
+
 #include "groot_device.h"
 
 namespace groot {
@@ -46,8 +48,11 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     constexpr int kRowShift = L == 8 ? 7 : L == 16 ? 8 : 9;   // log2 of a feature row's bytes
     static_assert(L == 8 || L == 16 || L == 32, "one float4 per lane");
     static_assert(kTileRows + 1 <= kWave, "row pointers of a tile fit one wavefront");
-    __shared__ __align__(8) int64_t s_slot[kPipeWaves][kSlots];
-    __shared__ float s_w[W == kExplicit ? kPipeWaves : 1][W == kExplicit ? kSlots : 1];
+    // a slot: byte offset of the gathered row from X; with explicit weights the entry's weight rides in the
+    // same 16-byte slot, so that one LDS read per slot serves both
+    struct SlotW { int64_t off; float w; float pad; };
+    using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
+    __shared__ __align__(16) Slot s_slot[kPipeWaves][kSlots];
     __shared__ float s_inv[kPipeWaves][kTileRows];
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -108,8 +113,9 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             }
             const bool live = k < hi - lo;
             if (s < kSlots) {
-                s_slot[w][s] = live ? ((int64_t)c << kRowShift) : zero_off;
-                if (W == kExplicit) s_w[w][s] = live ? wt : 0.f;
+                const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
+                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
+                else s_slot[w][s] = off;
             }
         }
         const int32_t len = __shfl_down(rel, 1) - rel;   // all lanes take part in the exchange
@@ -130,8 +136,13 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
         if (W == kMean) q.inv = s_inv[w][lr];
 #pragma unroll
         for (int k = 0; k < kPipeD; ++k) {
-            q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * kPipeD + k]);
-            if (W == kExplicit) q.ws[k] = s_w[w][lr * kPipeD + k];
+            if constexpr (W == kExplicit) {
+                const SlotW sl = s_slot[w][lr * kPipeD + k];
+                q.xs[k] = *(const v4f *)(Xf + sl.off);
+                q.ws[k] = sl.w;
+            } else {
+                q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * kPipeD + k]);
+            }
         }
     };
     auto sum = [&](const Regs &q) -> v4f {
