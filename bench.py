@@ -63,6 +63,7 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
     parts = G.groot_partition_regrow(g, P)
     t_partition = time.time() - t0
     items, foot, cross = [], [], 0
+    t0 = time.time()
     for p in range(P):
         pv = G.groot_parts_view(parts, p)
         sub = G.groot_graph_view(pv["sub"])
@@ -75,6 +76,8 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
         # rowptr + col (mean weights are not stored on the device) + ids + X_p + the owned rows of Y
         # (boundary rows are not computed: groot_spmm_execute_rows)
         foot.append(8 * (n_loc + 1) + 4 * sub["nnz"] + 8 * n_loc + 4 * n_loc * F + 4 * pv["n_owned"] * F)
+    torch.cuda.synchronize()
+    t_plans = time.time() - t0
     max_loc = max(it[3] for it in items)
     Xp = torch.empty((max_loc, F), dtype=torch.float32, device="cuda")
     Yp = torch.empty_like(Xp)
@@ -113,6 +116,26 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
     worst = 0.0
     for lo in range(0, n, 1 << 24):
         worst = max(worst, float((Yout[lo:lo + (1 << 24)] - Y[lo:lo + (1 << 24)]).abs().max()))
+    # the same partition built on the device: re-growth of every part from the full graph's resident CSR, and a
+    # plan from the part's device arrays; one pass with those plans must give the same result
+    items.clear()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    dev_items = []
+    for p in range(P):
+        part = G.groot_partition_regrow_device(full_plan, P, p)
+        pv = G.groot_dev_part_view(part)
+        plan = G.groot_dev_part_plan(part, T, F)
+        dev_items.append((plan, pv["global_id"], pv["n_owned"], pv["n_owned"] + pv["n_halo"], part))
+    torch.cuda.synchronize()
+    t_partition_dev = time.perf_counter() - t0
+    assert max(it[3] for it in dev_items) == max_loc
+    items.extend(it[:4] for it in dev_items)
+    Yout.fill_(float("nan"))
+    ms_dev = timed(one_pass)
+    worst_dev = 0.0
+    for lo in range(0, n, 1 << 24):
+        worst_dev = max(worst_dev, float((Yout[lo:lo + (1 << 24)] - Y[lo:lo + (1 << 24)]).abs().max()))
     full_foot = 8 * (n + 1) + 4 * nnz + 2 * 4 * n * F
     undirected = (nnz - n) // 2
     print(json.dumps({
@@ -126,7 +149,11 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
         "rows_with_boundary": sum(it[3] for it in items), "largest_part_rows": max_loc,
         "device_bytes_full_graph": full_foot, "device_bytes_largest_part": max(foot),
         "memory_reduction_pct": round(100.0 * (1.0 - max(foot) / full_foot), 2),
-        "max_abs_diff_vs_full_graph": worst, "partition_seconds": round(t_partition, 2), "device": props.name}))
+        "max_abs_diff_vs_full_graph": worst, "partition_seconds": round(t_partition, 2),
+        "host_plans_and_upload_seconds": round(t_plans, 2),
+        "device_built": {"partition_and_plans_seconds": round(t_partition_dev, 3), "ms_per_step": round(ms_dev, 4),
+                         "max_abs_diff_vs_full_graph": worst_dev},
+        "device": props.name}))
 
 
 def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props):

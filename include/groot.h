@@ -41,6 +41,7 @@ typedef enum {
 typedef struct groot_graph groot_graph;
 typedef struct groot_plan  groot_plan;
 typedef struct groot_parts groot_parts;
+typedef struct groot_dev_part groot_dev_part;
 
 /* flags of groot_graph_build */
 #define GROOT_SYMMETRIC  1u   /* store both directions of every AIG edge */
@@ -244,6 +245,58 @@ groot_status groot_parts_view(const groot_parts *parts, int32_t p, int64_t *n_ow
                               const groot_graph **sub);
 int32_t groot_parts_count(const groot_parts *parts);
 void groot_parts_free(groot_parts *parts);
+
+/* ---------------------------------------------------------------------------
+ * groot_partition_regrow_device -- one part of the same partition, built on
+ * the device from the CSR that an uploaded plan keeps there.
+ * Paper: Section "GNN and Edge Re-growth After Partition", Eq. (1), Eq. (2)
+ * and Algorithm 1; definitions, local numbering, kept edges, weights and
+ * n_crossing exactly as in groot_partition_regrow, and the arrays are
+ * bit-identical to that call's part p.
+ * plan: resident (groot_plan_upload, or a plan made by groot_dev_part_plan).
+ * part_of_dev (device, int32 [N], may be NULL): part of every node; NULL
+ *   selects the built-in rule of groot_partition_regrow (nodes per copy are
+ *   those of the plan's graph; a plan made by groot_dev_part_plan counts as
+ *   one copy).
+ * p: the part to build, in [0, num_parts).
+ * The result owns its device arrays (groot_dev_part_view; layout of the
+ * sub-graph: rowptr int64 [n_owned + n_halo + 1], col int32 [nnz] local ids,
+ * val float [nnz] or NULL when the graph's weights are row-uniform,
+ * global_id int64 [n_owned + n_halo]).  Allocates device memory (4 bytes per
+ * node of the whole graph as scratch, freed before it returns) and
+ * synchronises hip_stream.
+ * Errors: EINVAL (NULL, plan not resident, P < 1, P > N, p or a part_of entry
+ *   outside [0,P), unknown flags); ENOMEM (host or device); EHIP.
+ *
+ * groot_dev_part_plan -- an executable plan for the part's sub-graph, built
+ * from the device arrays (degree classes and counting sort as in
+ * groot_plan_lists_device; the schedule of the high-degree rows is made on
+ * the host from those rows' extents only).  The sub-graph's arrays MOVE into
+ * the plan: afterwards groot_dev_part_view gives NULL for rowptr/col/val, the
+ * part keeps its counts and global_id, and a second call gives EINVAL.  The
+ * plan is resident (groot_plan_upload on it is a no-op for max_F' <= max_F and
+ * EINVAL above), has no host lists (groot_plan_view gives EINVAL; use
+ * groot_plan_lists_device), and is freed with groot_plan_free.
+ * Errors: EINVAL, ERANGE (degree_threshold > 1024), ENOMEM, EHIP.
+ *
+ * groot_dev_part_download -- copies of the part's arrays in host buffers of
+ * the caller (sizes as above; any pointer may be NULL = not wanted);
+ * synchronises hip_stream.  EINVAL for rowptr/col/val once they have moved
+ * into a plan, and for val when the sub-graph has no weight array.
+ * ------------------------------------------------------------------------- */
+groot_status groot_partition_regrow_device(const groot_plan *plan, int32_t num_parts,
+                                           const int32_t *part_of_dev, uint32_t flags, int32_t p,
+                                           void *hip_stream, groot_dev_part **out);
+groot_status groot_dev_part_view(const groot_dev_part *part, int64_t *n_owned, int64_t *n_halo,
+                                 int64_t *n_crossing, int64_t *nnz, const int64_t **global_id_dev,
+                                 const int64_t **rowptr_dev, const int32_t **col_dev,
+                                 const float **val_dev);
+groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree_threshold, int32_t max_F,
+                                 void *hip_stream, groot_plan **out);
+groot_status groot_dev_part_download(const groot_dev_part *part, int64_t *global_id_host,
+                                     int64_t *rowptr_host, int32_t *col_host, float *val_host,
+                                     void *hip_stream);
+void groot_dev_part_free(groot_dev_part *part);
 
 /* Row gather / scatter for the partitioned mode (device pointers; ids int64):
  *   gather : out[i,:]     = X[ids[i],:]      i < n

@@ -25,7 +25,8 @@ EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
     "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
-    "groot_parts_count", "groot_parts_free", "groot_rows_gather", "groot_rows_scatter",
+    "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
+    "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
 ]
 
@@ -69,6 +70,12 @@ _lib.groot_parts_count.argtypes = [_vp]
 _lib.groot_parts_count.restype = _i32
 _lib.groot_parts_free.argtypes = [_vp]
 _lib.groot_parts_free.restype = None
+_lib.groot_partition_regrow_device.argtypes = [_vp, _i32, _vp, _u32, _i32, _vp, _pp]
+_lib.groot_dev_part_view.argtypes = [_vp, _pi64, _pi64, _pi64, _pi64, _pp, _pp, _pp, _pp]
+_lib.groot_dev_part_plan.argtypes = [_vp, _i32, _i32, _vp, _pp]
+_lib.groot_dev_part_download.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp]
+_lib.groot_dev_part_free.argtypes = [_vp]
+_lib.groot_dev_part_free.restype = None
 _lib.groot_rows_gather.argtypes = [_vp, _i64, _vp, _vp, _i32, _vp]
 _lib.groot_rows_scatter.argtypes = [_vp, _i64, _vp, _vp, _i32, _vp]
 _lib.groot_set_tuning.argtypes = [ctypes.c_char_p, _i64]
@@ -132,6 +139,29 @@ class Plan:
         if getattr(self, "handle", None) and _lib is not None:   # module globals are cleared at interpreter exit
             _lib.groot_plan_free(self.handle)
             self.handle = None
+
+
+class DevPart:
+    """Owner of a groot_dev_part handle (one part of a partition, in device memory)."""
+
+    def __init__(self, handle, plan):
+        self.handle = handle
+        self.plan = plan             # the plan whose graph was partitioned
+
+    def __del__(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.groot_dev_part_free(self.handle)
+            self.handle = None
+
+
+class RawDeviceArray:
+    """A library-owned device array: pointer, element count and dtype; accepted wherever a CUDA tensor of ids is."""
+
+    def __init__(self, ptr, count, dtype, owner):
+        self.device_pointer = ptr
+        self.shape = (count,)
+        self.dtype = np.dtype(dtype)
+        self._owner = owner
 
 
 class Parts:
@@ -209,6 +239,8 @@ def groot_plan_upload(pl: Plan, max_F: int) -> None:
 def _dev_ptr(t, what):
     import torch
 
+    if isinstance(t, RawDeviceArray):
+        return t.device_pointer
     if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
         raise TypeError(f"{what} must be a contiguous CUDA tensor")
     return t.data_ptr()
@@ -239,7 +271,10 @@ def groot_spmm_execute_phases(pl: Plan, X, Y, F: int, phases: int, stream=None) 
 def groot_spmm_execute_rows(pl: Plan, X, Y, F: int, n_rows: int, out_ids=None, stream=None) -> None:
     import torch
 
-    if out_ids is not None and (out_ids.dtype != torch.int64 or out_ids.numel() < n_rows):
+    if isinstance(out_ids, RawDeviceArray):
+        if out_ids.dtype != np.int64 or out_ids.shape[0] < n_rows:
+            raise TypeError("out_ids must be int64 with at least n_rows entries")
+    elif out_ids is not None and (out_ids.dtype != torch.int64 or out_ids.numel() < n_rows):
         raise TypeError("out_ids must be int64 with at least n_rows entries")
     _check(_lib.groot_spmm_execute_rows(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, n_rows,
                                         None if out_ids is None else _dev_ptr(out_ids, "out_ids"),
@@ -258,7 +293,7 @@ def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_de
     """Caller-allocated CUDA tensors: uint8[N], int32[N] x3, int64[T+1], int64[2]."""
     import torch
 
-    n = groot_graph_view(pl.graph)["n"]
+    n = pl.n_rows if pl.graph is None else groot_graph_view(pl.graph)["n"]
     for t, dt, size, what in ((row_class, torch.uint8, n, "row_class"), (hd_rows, torch.int32, n, "hd_rows"),
                               (ld_rows, torch.int32, n, "ld_rows"), (ld_rows_by_degree, torch.int32, n, "ld_rows_by_degree"),
                               (ld_deg_offsets, torch.int64, pl.degree_threshold + 1, "ld_deg_offsets"),
@@ -297,6 +332,67 @@ def groot_parts_view(parts: Parts, p: int) -> dict:
                                  ctypes.byref(gid), ctypes.byref(sub)))
     return dict(n_owned=a.value, n_halo=b.value, n_crossing=c.value,
                 global_id=_view(gid.value, a.value + b.value, np.int64, parts), sub=Graph(sub.value, owner=parts))
+
+
+def groot_partition_regrow_device(pl: Plan, num_parts: int, p: int, part_of=None, flags: int = GROOT_REGROW,
+                                  stream=None) -> DevPart:
+    """part_of: None (built-in rule) or a CUDA int32 tensor with one entry per node."""
+    import torch
+
+    pp = None
+    if part_of is not None:
+        if not isinstance(part_of, torch.Tensor) or part_of.dtype != torch.int32:
+            raise TypeError("part_of must be a CUDA int32 tensor")
+        n = pl.n_rows if pl.graph is None else groot_graph_view(pl.graph)["n"]
+        if part_of.numel() != n:
+            raise ValueError("part_of must have one entry per node")
+        pp = _dev_ptr(part_of, "part_of")
+    out = ctypes.c_void_p()
+    _check(_lib.groot_partition_regrow_device(pl.handle, num_parts, pp, flags, p, _stream_handle(stream),
+                                              ctypes.byref(out)))
+    return DevPart(out.value, pl)
+
+
+def groot_dev_part_view(part: DevPart) -> dict:
+    a, b, c, z = _i64(0), _i64(0), _i64(0), _i64(0)
+    gid, rp, col, val = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    _check(_lib.groot_dev_part_view(part.handle, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(z),
+                                    ctypes.byref(gid), ctypes.byref(rp), ctypes.byref(col), ctypes.byref(val)))
+    n = a.value + b.value
+
+    def arr(ptr, count, dtype):
+        return RawDeviceArray(ptr.value, count, dtype, part) if ptr.value else None
+    return dict(n_owned=a.value, n_halo=b.value, n_crossing=c.value, nnz=z.value,
+                global_id=arr(gid, n, np.int64), rowptr=arr(rp, n + 1, np.int64), col=arr(col, z.value, np.int32),
+                val=arr(val, z.value, np.float32))
+
+
+def groot_dev_part_download(part: DevPart, stream=None) -> dict:
+    """Host copies (numpy) of whatever the part still holds."""
+    v = groot_dev_part_view(part)
+    n = v["n_owned"] + v["n_halo"]
+    out = dict(global_id=np.empty(n, np.int64))
+    if v["rowptr"] is not None:
+        out["rowptr"] = np.empty(n + 1, np.int64)
+        out["col"] = np.empty(v["nnz"], np.int32)
+    if v["val"] is not None:
+        out["val"] = np.empty(v["nnz"], np.float32)
+
+    def ptr(name):
+        return out[name].ctypes.data if name in out else None
+    _check(_lib.groot_dev_part_download(part.handle, ptr("global_id"), ptr("rowptr"), ptr("col"), ptr("val"),
+                                        _stream_handle(stream)))
+    return out
+
+
+def groot_dev_part_plan(part: DevPart, degree_threshold: int, max_F: int, stream=None) -> Plan:
+    out = ctypes.c_void_p()
+    _check(_lib.groot_dev_part_plan(part.handle, degree_threshold, max_F, _stream_handle(stream), ctypes.byref(out)))
+    pl = Plan(out.value, None)
+    pl.degree_threshold = degree_threshold
+    v = groot_dev_part_view(part)
+    pl.n_rows = v["n_owned"] + v["n_halo"]
+    return pl
 
 
 def groot_rows_gather(ids, X, out, F: int = None, stream=None) -> None:

@@ -91,6 +91,12 @@ struct groot_parts {
     std::vector<Part> parts;
 };
 
+struct groot_dev_part {
+    DevicePart d;
+    WeightMode weight_mode = WeightMode::Explicit;
+    bool csr_moved = false;         // the CSR arrays now belong to a plan
+};
+
 // ---------------------------------------------------------------------------
 // graph construction
 // ---------------------------------------------------------------------------
@@ -329,6 +335,55 @@ extern "C" void groot_graph_free(groot_graph *g) { delete g; }
 // ---------------------------------------------------------------------------
 // plan
 // ---------------------------------------------------------------------------
+namespace {
+
+// HD schedule: every high-degree row is cut into balanced pieces of at most hd_chunk non-zeros.
+// begin_of(k) / degree_of(k): first non-zero and stored length of the k-th high-degree row.
+template <class Begin, class Degree>
+groot_status hd_schedule(int64_t n_hd, const int32_t *hd_rows, Begin begin_of, Degree degree_of,
+                         std::vector<HdChunk> &chunks, std::vector<HdSplitRow> &split_rows, int64_t &n_partials)
+{
+    const int64_t chunk = std::max(64, tuning().hd_chunk);
+    int64_t slots = 0;
+    for (int64_t k = 0; k < n_hd; ++k) {
+        const int32_t row = hd_rows[k];
+        const int64_t b = begin_of(k), d = degree_of(k);
+        const int64_t pieces = std::max<int64_t>(1, (d + chunk - 1) / chunk);
+        if (slots + pieces > std::numeric_limits<int32_t>::max() / 2)
+            return fail(GROOT_ERANGE, "groot_spmm_plan: too many high-degree pieces");
+        const int64_t per = (d + pieces - 1) / pieces;
+        if (pieces > 1) split_rows.push_back(HdSplitRow{row, (int32_t)slots, (int32_t)pieces, 0});
+        for (int64_t c = 0; c < pieces; ++c) {
+            const int64_t lo = c * per, hi = std::min(d, lo + per);
+            HdChunk ch;
+            ch.begin = b + lo;
+            ch.len = (int32_t)std::max<int64_t>(0, hi - lo);
+            ch.row = row;
+            ch.slot = pieces > 1 ? (int32_t)(slots + c) : -1;
+            ch.row_nnz = (int32_t)std::min<int64_t>(d, std::numeric_limits<int32_t>::max());
+            chunks.push_back(ch);
+        }
+        if (pieces > 1) slots += pieces;
+    }
+    n_partials = slots;
+    return GROOT_OK;
+}
+
+// Pieces run in the order of their first column (key[c] of piece c): pieces of different rows that read the
+// same stretch of feature rows (in an array multiplier: the a_j and b_i rows over the same partial products)
+// then run close together, and the second reader finds the rows in the last-level cache.
+void sort_hd_schedule(std::vector<HdChunk> &chunks, const std::vector<int32_t> &key)
+{
+    std::vector<int64_t> order(chunks.size());
+    for (size_t c = 0; c < order.size(); ++c) order[c] = (int64_t)c;
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return key[a] < key[b]; });
+    std::vector<HdChunk> sorted(chunks.size());
+    for (size_t c = 0; c < order.size(); ++c) sorted[c] = chunks[order[c]];
+    chunks.swap(sorted);
+}
+
+}  // namespace
+
 extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_threshold, groot_plan **out)
 {
     if (!g || !out) return fail(GROOT_EINVAL, "groot_spmm_plan: NULL argument");
@@ -363,36 +418,14 @@ extern "C" groot_status groot_spmm_plan(const groot_graph *g, int32_t degree_thr
             pl->ld_rows[il++] = (int32_t)i;
             pl->ld_rows_by_degree[cursor[g->rowptr[i + 1] - g->rowptr[i]]++] = (int32_t)i;
         }
-        // HD schedule: balanced pieces of at most hd_chunk non-zeros
-        const int64_t chunk = std::max(64, tuning().hd_chunk);
-        int64_t slots = 0;
-        for (int64_t k = 0; k < n_hd; ++k) {
-            int32_t row = pl->hd_rows[k];
-            int64_t b = g->rowptr[row], d = g->rowptr[row + 1] - b;
-            int64_t pieces = (d + chunk - 1) / chunk;
-            if (slots + pieces > std::numeric_limits<int32_t>::max() / 2)
-                return fail(GROOT_ERANGE, "groot_spmm_plan: too many high-degree pieces");
-            int64_t per = (d + pieces - 1) / pieces;
-            if (pieces > 1) pl->split_rows.push_back(HdSplitRow{row, (int32_t)slots, (int32_t)pieces, 0});
-            for (int64_t c = 0; c < pieces; ++c) {
-                int64_t lo = c * per, hi = std::min(d, lo + per);
-                HdChunk ch;
-                ch.begin = b + lo;
-                ch.len = (int32_t)std::max<int64_t>(0, hi - lo);
-                ch.row = row;
-                ch.slot = pieces > 1 ? (int32_t)(slots + c) : -1;
-                ch.row_nnz = (int32_t)std::min<int64_t>(d, std::numeric_limits<int32_t>::max());
-                pl->chunks.push_back(ch);
-            }
-            if (pieces > 1) slots += pieces;
-        }
-        // Pieces run in the order of their first column: pieces of different rows that read the same
-        // stretch of feature rows (in an array multiplier: the a_j and b_i rows over the same partial
-        // products) then run close together, and the second reader finds the rows in the last-level cache.
-        std::stable_sort(pl->chunks.begin(), pl->chunks.end(), [&](const HdChunk &a, const HdChunk &b) {
-            return g->col[a.begin] < g->col[b.begin];
-        });
-        pl->n_partials = slots;
+        groot_status hs = hd_schedule(n_hd, pl->hd_rows.data(), [&](int64_t k) { return g->rowptr[pl->hd_rows[k]]; },
+                                      [&](int64_t k) { return g->rowptr[pl->hd_rows[k] + 1] - g->rowptr[pl->hd_rows[k]]; },
+                                      pl->chunks, pl->split_rows, pl->n_partials);
+        if (hs != GROOT_OK) return hs;
+        std::vector<int32_t> key(pl->chunks.size());
+        for (size_t c = 0; c < key.size(); ++c)
+            key[c] = pl->chunks[c].len > 0 ? g->col[pl->chunks[c].begin] : std::numeric_limits<int32_t>::max();
+        sort_hd_schedule(pl->chunks, key);
         *out = pl.release();
         return GROOT_OK;
     } catch (const std::bad_alloc &) {
@@ -406,6 +439,7 @@ extern "C" groot_status groot_plan_view(const groot_plan *plan, int64_t *n_hd, i
                                         const int64_t **ld_deg_offsets)
 {
     if (!plan) return fail(GROOT_EINVAL, "groot_plan_view: NULL plan");
+    if (!plan->g) return fail(GROOT_EINVAL, "groot_plan_view: the plan was built on the device (use groot_plan_lists_device)");
     if (n_hd) *n_hd = (int64_t)plan->hd_rows.size();
     if (n_ld) *n_ld = (int64_t)plan->ld_rows.size();
     if (row_class) *row_class = plan->row_class.data();
@@ -449,6 +483,10 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
 {
     if (!plan) return fail(GROOT_EINVAL, "groot_plan_upload: NULL plan");
     if (max_F < 4 || max_F > 512 || max_F % 4) return fail(GROOT_EINVAL, "groot_plan_upload: max_F must be a multiple of 4 in [4,512]");
+    if (!plan->g) {
+        if (max_F <= plan->max_F) return GROOT_OK;
+        return fail(GROOT_EINVAL, "groot_plan_upload: the plan was built on the device with a smaller max_F");
+    }
     if (plan->resident) release_device(plan);
     const groot_graph *g = plan->g;
     DevicePlan &d = plan->dev;
@@ -766,6 +804,187 @@ extern "C" groot_status groot_parts_view(const groot_parts *parts, int32_t p, in
 }
 
 extern "C" void groot_parts_free(groot_parts *parts) { delete parts; }
+
+// ---------------------------------------------------------------------------
+// partition + boundary edge re-growth on the device
+// ---------------------------------------------------------------------------
+extern "C" groot_status groot_partition_regrow_device(const groot_plan *plan, int32_t num_parts,
+                                                      const int32_t *part_of_dev, uint32_t flags, int32_t p,
+                                                      void *hip_stream, groot_dev_part **out)
+{
+    if (!plan || !out) return fail(GROOT_EINVAL, "groot_partition_regrow_device: NULL argument");
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_partition_regrow_device: plan is not on the device (call groot_plan_upload)");
+    const int64_t n = plan->dev.n;
+    if (num_parts < 1 || num_parts > n) return fail(GROOT_EINVAL, "groot_partition_regrow_device: num_parts must be in [1,N]");
+    if (p < 0 || p >= num_parts) return fail(GROOT_EINVAL, "groot_partition_regrow_device: part index outside [0,P)");
+    if (flags & ~GROOT_REGROW) return fail(GROOT_EINVAL, "groot_partition_regrow_device: unknown flag bits");
+    std::unique_ptr<groot_dev_part> part(new (std::nothrow) groot_dev_part);
+    if (!part) return fail(GROOT_ENOMEM, "groot_partition_regrow_device: out of host memory");
+    part->weight_mode = (WeightMode)plan->dev.weight_mode;
+    const int64_t n1 = plan->g ? plan->g->n1 : n;
+    int err = launch_regrow_device(plan->dev, n1, num_parts, part_of_dev, p, (flags & GROOT_REGROW) ? 1 : 0, hip_stream,
+                                   &part->d);
+    if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, "groot_partition_regrow_device: device allocation failed");
+    if (err == kErrBadPartId) return fail(GROOT_EINVAL, "groot_partition_regrow_device: a part_of entry lies outside [0,P)");
+    if (err) return fail(GROOT_EHIP, std::string("groot_partition_regrow_device: ") + hip_error_text(err));
+    *out = part.release();
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_dev_part_view(const groot_dev_part *part, int64_t *n_owned, int64_t *n_halo,
+                                            int64_t *n_crossing, int64_t *nnz, const int64_t **global_id_dev,
+                                            const int64_t **rowptr_dev, const int32_t **col_dev, const float **val_dev)
+{
+    if (!part) return fail(GROOT_EINVAL, "groot_dev_part_view: NULL part");
+    if (n_owned) *n_owned = part->d.n_owned;
+    if (n_halo) *n_halo = part->d.n_halo;
+    if (n_crossing) *n_crossing = part->d.n_crossing;
+    if (nnz) *nnz = part->d.nnz;
+    if (global_id_dev) *global_id_dev = part->d.global_id;
+    if (rowptr_dev) *rowptr_dev = part->d.rowptr;
+    if (col_dev) *col_dev = part->d.col;
+    if (val_dev) *val_dev = part->d.val;
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_dev_part_download(const groot_dev_part *part, int64_t *global_id_host,
+                                                int64_t *rowptr_host, int32_t *col_host, float *val_host,
+                                                void *hip_stream)
+{
+    if (!part) return fail(GROOT_EINVAL, "groot_dev_part_download: NULL part");
+    const DevicePart &d = part->d;
+    const int64_t n = d.n_owned + d.n_halo;
+    if ((rowptr_host || col_host || val_host) && part->csr_moved)
+        return fail(GROOT_EINVAL, "groot_dev_part_download: the part's sub-graph has moved into a plan");
+    if (val_host && !d.val) return fail(GROOT_EINVAL, "groot_dev_part_download: the sub-graph has no weight array (row-uniform weights)");
+    int err = 0;
+    if (!err && global_id_host) err = device_download(global_id_host, d.global_id, (size_t)n * 8, hip_stream);
+    if (!err && rowptr_host) err = device_download(rowptr_host, d.rowptr, (size_t)(n + 1) * 8, hip_stream);
+    if (!err && col_host) err = device_download(col_host, d.col, (size_t)d.nnz * 4, hip_stream);
+    if (!err && val_host) err = device_download(val_host, d.val, (size_t)d.nnz * 4, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_dev_part_download: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" void groot_dev_part_free(groot_dev_part *part)
+{
+    if (!part) return;
+    free_device_part(part->d);
+    delete part;
+}
+
+namespace {
+// frees device memory on scope exit unless released
+struct DevBuf {
+    void *p = nullptr;
+    ~DevBuf() { dev_free(p); }
+    int alloc(size_t bytes) { return dev_alloc(&p, bytes ? bytes : 1); }
+    template <class T> T *as() const { return (T *)p; }
+    void *release() { void *q = p; p = nullptr; return q; }
+};
+}  // namespace
+
+extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree_threshold, int32_t max_F,
+                                            void *hip_stream, groot_plan **out)
+{
+    const char *who = "groot_dev_part_plan: ";
+    if (!part || !out) return fail(GROOT_EINVAL, std::string(who) + "NULL argument");
+    if (part->csr_moved) return fail(GROOT_EINVAL, std::string(who) + "the part's sub-graph already belongs to a plan");
+    if (degree_threshold < 1) return fail(GROOT_EINVAL, std::string(who) + "degree_threshold must be >= 1");
+    if (degree_threshold > kPlanDeviceMaxThreshold)
+        return fail(GROOT_ERANGE, std::string(who) + "degree threshold above " + std::to_string(kPlanDeviceMaxThreshold));
+    if (max_F < 4 || max_F > 512 || max_F % 4) return fail(GROOT_EINVAL, std::string(who) + "max_F must be a multiple of 4 in [4,512]");
+    const int32_t T = degree_threshold;
+    const int64_t n = part->d.n_owned + part->d.n_halo;
+    if (n < 1) return fail(GROOT_EINVAL, std::string(who) + "the part has no rows");
+    try {
+        std::unique_ptr<groot_plan> pl(new groot_plan);
+        // lists on the device; only the high-degree rows and the degree offsets are needed here
+        DevBuf row_class, hd_rows, ld_rows, by_degree, deg_offsets, counts;
+        if (row_class.alloc((size_t)n) || hd_rows.alloc((size_t)n * 4) || ld_rows.alloc((size_t)n * 4) ||
+            by_degree.alloc((size_t)n * 4) || deg_offsets.alloc((size_t)(T + 1) * 8) || counts.alloc(16))
+            return fail(GROOT_ENOMEM, std::string(who) + "device allocation of the plan lists failed");
+        int err = launch_plan_device(part->d.rowptr, n, T, row_class.as<uint8_t>(), hd_rows.as<int32_t>(),
+                                     ld_rows.as<int32_t>(), by_degree.as<int32_t>(), deg_offsets.as<int64_t>(),
+                                     counts.as<int64_t>(), hip_stream);
+        if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "scratch allocation failed");
+        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        int64_t h_counts[2] = {0, 0};
+        std::vector<int64_t> offs(T + 1, 0);
+        if ((err = device_download(h_counts, counts.p, sizeof h_counts, hip_stream)) ||
+            (err = device_download(offs.data(), deg_offsets.p, offs.size() * 8, hip_stream)))
+            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        const int64_t n_hd = h_counts[0], n_ld = h_counts[1];
+        if (n_hd < 0 || n_ld < 0 || n_hd + n_ld != n) return fail(GROOT_EHIP, std::string(who) + "inconsistent row counts from the device");
+        std::vector<int32_t> rows(n_hd);
+        std::vector<int64_t> begin(n_hd), end(n_hd);
+        if ((err = device_download(rows.data(), hd_rows.p, (size_t)n_hd * 4, hip_stream)) ||
+            (err = device_row_extents(part->d.rowptr, hd_rows.as<int32_t>(), n_hd, begin.data(), end.data(), hip_stream))) {
+            if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "scratch allocation failed");
+            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        }
+        for (int64_t k = 0; k < n_hd; ++k)
+            if (rows[k] < 0 || rows[k] >= n || begin[k] < 0 || end[k] < begin[k] || end[k] > part->d.nnz)
+                return fail(GROOT_EHIP, std::string(who) + "row extents from the device are out of range");
+        groot_status hs = hd_schedule(n_hd, rows.data(), [&](int64_t k) { return begin[k]; },
+                                      [&](int64_t k) { return end[k] - begin[k]; }, pl->chunks, pl->split_rows,
+                                      pl->n_partials);
+        if (hs != GROOT_OK) return hs;
+        std::vector<int64_t> idx(pl->chunks.size());
+        std::vector<int32_t> key(pl->chunks.size());
+        for (size_t c = 0; c < idx.size(); ++c) idx[c] = pl->chunks[c].len > 0 ? pl->chunks[c].begin : 0;
+        if ((err = device_gather_col(part->d.col, idx.data(), (int64_t)idx.size(), key.data(), hip_stream))) {
+            if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "scratch allocation failed");
+            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        }
+        for (size_t c = 0; c < key.size(); ++c)
+            if (pl->chunks[c].len <= 0) key[c] = std::numeric_limits<int32_t>::max();
+        sort_hd_schedule(pl->chunks, key);
+
+        DevicePlan &d = pl->dev;
+        const std::vector<float> zeros(kZeroRowFloats + kTrashFloats, 0.0f);
+        groot_status st;
+        if ((st = to_device(&d.zero_row, zeros.data(), zeros.size(), "zero row")) != GROOT_OK ||
+            (st = to_device(&d.chunks, pl->chunks.data(), pl->chunks.size(), "HD schedule")) != GROOT_OK ||
+            (st = to_device(&d.split_rows, pl->split_rows.data(), pl->split_rows.size(), "HD split rows")) != GROOT_OK ||
+            (st = to_device<float>(&d.partials, nullptr, (size_t)pl->n_partials * max_F, "HD partial sums")) != GROOT_OK) {
+            std::string keep = groot_last_error();
+            release_device(pl.get());
+            set_error(keep);
+            return st;
+        }
+        d.n = n;
+        d.nnz = part->d.nnz;
+        d.threshold = T;
+        d.xcd_remap = tuning().xcd_remap;
+        d.weight_mode = (int)part->weight_mode;
+        d.n_tiles = (n + kRowsPerLdTile - 1) / kRowsPerLdTile;
+        d.n_chunks = (int64_t)pl->chunks.size();
+        d.n_split_rows = (int64_t)pl->split_rows.size();
+        d.n_partials = pl->n_partials;
+        {
+            const int64_t n_short = offs[std::min<int32_t>(7, T)];
+            const int knob = tuning().ld_pipeline;
+            d.ld_pipelined = knob > 0 ? 2 : (knob < 0 && n_ld > 0 && n_short * 1000 >= n_ld * 999) ? 1 : 0;
+        }
+        // the sub-graph moves into the plan
+        d.rowptr = part->d.rowptr;
+        d.col = part->d.col;
+        d.val = part->d.val;
+        part->d.rowptr = nullptr;
+        part->d.col = nullptr;
+        part->d.val = nullptr;
+        part->csr_moved = true;
+        pl->g = nullptr;
+        pl->threshold = T;
+        pl->max_F = max_F;
+        pl->resident = true;
+        *out = pl.release();
+        return GROOT_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, std::string(who) + "out of host memory");
+    }
+}
 
 // ---------------------------------------------------------------------------
 // row gather / scatter, tuning, errors

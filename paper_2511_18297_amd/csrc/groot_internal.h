@@ -88,6 +88,25 @@ constexpr int kPlanDeviceMaxThreshold = 1024;
 constexpr int kErrOutOfDeviceMemory = 2;   // hipErrorOutOfMemory
 int launch_plan_device(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
                        int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts, void *stream);
+// One part of a partition with re-grown boundary, built on the device (groot_regrow_device.hip).  All pointers
+// are device memory owned by the struct's holder; val is NULL unless the source graph has explicit weights.
+struct DevicePart {
+    int64_t n_owned = 0, n_halo = 0, n_crossing = 0, nnz = 0;
+    int64_t *global_id = nullptr;   // [n_owned + n_halo]
+    int64_t *rowptr = nullptr;      // [n_owned + n_halo + 1]
+    int32_t *col = nullptr;         // [nnz] local ids
+    float *val = nullptr;           // [nnz] or NULL
+};
+constexpr int kErrBadPartId = -2;   // a caller-supplied part id outside [0, P)
+// Synchronises the stream.  part_of_dev may be NULL (built-in rule with n1 nodes per copy).
+int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int32_t *part_of_dev, int32_t p,
+                         int regrow, void *stream, DevicePart *out);
+void free_device_part(DevicePart &part);
+// Small synchronous device reads for the high-degree schedule of a plan built from device arrays.
+int device_row_extents(const int64_t *rowptr_dev, const int32_t *rows_dev, int64_t n_rows, int64_t *begin_host,
+                       int64_t *end_host, void *stream);
+int device_gather_col(const int32_t *col_dev, const int64_t *idx_host, int64_t n_idx, int32_t *out_host, void *stream);
+int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream);
 const char *hip_error_text(int err);
 
 // Device memory helpers (groot_kernels.hip, so that the host file needs no HIP headers).

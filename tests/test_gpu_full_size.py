@@ -9,7 +9,8 @@ involves every row -- with X = 1 every mean-normalised row sums to
 deg * fl(1/deg) -- and (b) on sampled rows the oracle computes one by one from
 its own adjacency of one copy and the block-diagonal batch rule; the
 16-way partitioned mode must scatter back to the same result, and two of its
-parts are compared bit for bit with the oracle's re-growth."""
+parts are compared bit for bit with the oracle's re-growth, from the host and
+from the device-side re-growth."""
 import os
 
 import numpy as np
@@ -234,6 +235,29 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
         assert np.array_equal(pw["global_id"], want["global_id"])
         assert np.array_equal(sub["rowptr"], want["rowptr"]) and np.array_equal(sub["col"], want["col"])
         assert np.array_equal(sub["val"].view(np.uint32), want["val"].view(np.uint32))
+        # the same part re-grown on the device from the resident CSR of the full graph, and its owned rows
+        # through a plan built from the device arrays
+        print(f"device re-growth of part {p} at full size", flush=True)
+        part = G.groot_partition_regrow_device(plan, 16, p)
+        dv = G.groot_dev_part_view(part)
+        assert (dv["n_owned"], dv["n_halo"], dv["n_crossing"], dv["nnz"]) == \
+            (want["n_owned"], want["n_halo"], want["n_crossing"], want["col"].shape[0])
+        got = G.groot_dev_part_download(part)
+        assert np.array_equal(got["global_id"], want["global_id"])
+        assert np.array_equal(got["rowptr"], want["rowptr"]) and np.array_equal(got["col"], want["col"])
+        del got
+        dev_plan = G.groot_dev_part_plan(part, T, F)
+        ids = G.groot_dev_part_view(part)["global_id"]
+        n_loc = dv["n_owned"] + dv["n_halo"]
+        Xp = torch.empty((n_loc, F), dtype=torch.float32, device="cuda")
+        G.groot_rows_gather(ids, X, Xp, F)
+        Yp_full.fill_(float("nan"))
+        G.groot_spmm_execute_rows(dev_plan, Xp, Yp_full, F, dv["n_owned"], ids)
+        torch.cuda.synchronize()
+        owned = torch.from_numpy(want["global_id"][:want["n_owned"]]).cuda()
+        assert float((Yp_full[owned] - Y[owned]).abs().max()) <= 1e-5
+        assert int((~torch.isnan(Yp_full[:, 0])).sum()) == want["n_owned"]
+        del dev_plan, part, Xp, owned
 
 
 def _stress_case(torch, log2n, thresholds):

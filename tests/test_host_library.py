@@ -267,6 +267,23 @@ def test_device_plan_lists_host_checks():
         G.groot_plan_query(plan, "ld_pipelined")          # not uploaded
 
 
+def test_device_regrow_host_checks():
+    """Argument checks of the device-side re-growth that need no GPU."""
+    aig = wl.csa_multiplier_aig(4)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    plan = G.groot_spmm_plan(g, 4)
+    lib = G.binding._lib
+    out = ctypes.c_void_p()
+    assert lib.groot_partition_regrow_device(plan.handle, 2, None, 1, 0, None, ctypes.byref(out)) == G.GROOT_EINVAL
+    assert "not on the device" in G.groot_last_error() and not out.value
+    assert lib.groot_partition_regrow_device(None, 2, None, 1, 0, None, ctypes.byref(out)) == G.GROOT_EINVAL
+    assert lib.groot_partition_regrow_device(plan.handle, 2, None, 1, 0, None, None) == G.GROOT_EINVAL
+    assert lib.groot_dev_part_view(None, None, None, None, None, None, None, None, None) == G.GROOT_EINVAL
+    assert lib.groot_dev_part_plan(None, 4, 64, None, ctypes.byref(out)) == G.GROOT_EINVAL
+    assert lib.groot_dev_part_download(None, None, None, None, None, None) == G.GROOT_EINVAL
+    lib.groot_dev_part_free(None)
+
+
 def test_build_module_is_importable_without_loading_the_library():
     """A tree without libgroot.so must still be able to import the build step (which makes the library);
     only the use of the binding needs it."""
