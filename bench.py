@@ -222,6 +222,8 @@ def main():
     ap.add_argument("--hd-chunk", type=int, default=None)
     ap.add_argument("--ld-pipeline", type=int, default=None, help="LD kernel choice: 1 pipelined, 0 plain, -1 auto")
     ap.add_argument("--sage-gap", type=int, default=None, help="pacing of the fused layer's matrix wavefronts (0..4)")
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="any other groot_set_tuning knob (repeatable), e.g. ld_strip_rows=0")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU by design); "
@@ -249,6 +251,9 @@ def main():
         G.groot_set_tuning("ld_pipeline", args.ld_pipeline)
     if args.sage_gap is not None:
         G.groot_set_tuning("sage_gap", args.sage_gap)
+    for item in args.tune:
+        name, _, value = item.partition("=")
+        G.groot_set_tuning(name, int(value))
 
     name = args.workload
     if name is None:
