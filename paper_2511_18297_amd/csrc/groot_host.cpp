@@ -601,7 +601,9 @@ extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const f
     int err = 0;
     if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F, hip_stream);
     if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, H_dev, F, hip_stream);
-    if (!err) err = launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
+    if (!err)
+        err = tuning().sage_kernel && plan->dev.weight_mode != (int)WeightMode::Explicit ? launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream)
+                                   : launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
     if (err) return fail(GROOT_EHIP, std::string("groot_sage_layer_forward: launch failed: ") + hip_error_text(err));
     return GROOT_OK;
 }
@@ -1035,6 +1037,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (k == "ld_pipeline") {
         if (value < -1 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: ld_pipeline must be -1, 0 or 1");
         tuning().ld_pipeline = (int)value;
+        return GROOT_OK;
+    }
+    if (k == "sage_split" || k == "sage_kernel") {
+        if (value < 0 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: " + k + " must be 0 or 1");
+        (k == "sage_split" ? tuning().sage_split : tuning().sage_kernel) = (int)value;
         return GROOT_OK;
     }
     if (k == "sage_gap") {

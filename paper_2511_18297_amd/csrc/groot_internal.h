@@ -37,6 +37,8 @@ struct Tuning {
     int xcd_remap = 1;
     int hd_chunk = 512;
     int sage_gap = 2;               // pacing of the fused layer's matrix wavefronts, see launch_sage
+    int sage_split = 1;             // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
+    int sage_kernel = 1;            // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
     int ld_pipeline = -1;           // pipelined LD kernel: 1 always (where it applies), 0 never, -1 when the rows are short
 };
 Tuning &tuning();
@@ -80,6 +82,8 @@ int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *s
 int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
+int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
+                     int relu, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
 int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
 // Device-side plan lists (groot_plan_device.hip).  Synchronises the stream; kErrOutOfDeviceMemory when its

@@ -21,6 +21,14 @@
 // nothing is exchanged through global memory, and the producers' loads stay in flight across it.
 // High-degree rows are aggregated beforehand by the HD kernel into H itself; the producers pick those
 // sums up from H instead of recomputing them.
+//
+// kSplit: the dense products run on the bf16 matrix instruction (v_mfma_f32_16x16x32_bf16, a sixteenth of the
+// fp32 instruction's time per multiply-add) without giving up fp32 accuracy.  Every fp32 operand is cut into
+// three bf16 pieces, x = hi + mid + lo exactly up to 2^-24 |x| (8 significant bits each); a product keeps the
+// six piece products down to 2^-16 relative size (hi hi, hi mid, mid hi, hi lo, lo hi, mid mid; the dropped
+// ones are below 2^-24) and sums them in fp32 in the instruction's accumulator.  The producers cut their rows
+// when they park them in LDS (three bf16 planes instead of one fp32 tile), the consumers cut their weights
+// once, so the cutting costs each SIMD 11 vector instructions per pair of tile elements, once.
 #include "groot_device.h"
 
 namespace groot {
@@ -29,6 +37,13 @@ constexpr int kSgRows = 64;                 // rows per tile
 constexpr int kSgF4 = 16;                   // 64 features = 16 float4
 constexpr int kSgAStride = 132;             // floats per LDS row of [agg | self] (128 + 4: conflict-free operand reads)
 constexpr int kSgOStride = 68;              // floats per LDS row of the output tile (conflict-free result writes)
+constexpr int kSgBRow = 272;                // bytes per LDS row of one bf16 plane of [agg | self] (256 + 16: conflict-free)
+constexpr int kSgPlane = kSgRows * kSgBRow; // bytes of one plane; a split tile is three planes: hi, mid, lo
+typedef __bf16 sg_bf2 __attribute__((ext_vector_type(2)));
+typedef __bf16 sg_bf8 __attribute__((ext_vector_type(8)));
+typedef unsigned int sg_u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int sg_u2 __attribute__((ext_vector_type(2)));
+typedef float sg_f2 __attribute__((ext_vector_type(2)));
 #ifndef GROOT_SAGE_PRODUCERS
 #define GROOT_SAGE_PRODUCERS 8      // 4 (one per SIMD, 16 rows each, four register sets) measured 30.3 ms against 29.2
 #endif
@@ -68,14 +83,45 @@ __device__ __forceinline__ void sage_consumer_pause()
     if (kGap == 4) asm volatile("s_nop 15\n\ts_nop 15");
 }
 
-template <int W, int kGap>
+// two fp32 values -> their bf16 roundings (nearest even), packed: a in the low half
+__device__ __forceinline__ unsigned sage_pack2(float a, float b)
+{
+    const sg_f2 x = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(x, sg_bf2));
+}
+
+// (a, b) = hi + mid + lo, three packed bf16 pairs; the remainders are exact in fp32
+__device__ __forceinline__ void sage_split3(float a, float b, unsigned &hi, unsigned &mid, unsigned &lo)
+{
+    hi = sage_pack2(a, b);
+    float ra = a - __builtin_bit_cast(float, hi << 16), rb = b - __builtin_bit_cast(float, hi & 0xffff0000u);
+    mid = sage_pack2(ra, rb);
+    ra -= __builtin_bit_cast(float, mid << 16);
+    rb -= __builtin_bit_cast(float, mid & 0xffff0000u);
+    lo = sage_pack2(ra, rb);
+}
+
+// four consecutive elements k..k+3 of tile row `row` into the three planes of a split tile
+__device__ __forceinline__ void sage_park_split(char *tile, int row, int k, v4f x)
+{
+    unsigned h0, m0, l0, h1, m1, l1;
+    sage_split3(x[0], x[1], h0, m0, l0);
+    sage_split3(x[2], x[3], h1, m1, l1);
+    char *p = tile + row * kSgBRow + k * 2;
+    *(sg_u2 *)p = (sg_u2){h0, h1};
+    *(sg_u2 *)(p + kSgPlane) = (sg_u2){m0, m1};
+    *(sg_u2 *)(p + 2 * kSgPlane) = (sg_u2){l0, l1};
+}
+
+template <int W, int kGap, bool kSplit>
 __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgThreads / 256, kSgThreads / 256))) void sage_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const v4f *__restrict__ X, v4f *H, const float *__restrict__ zero_row, const float *__restrict__ Wn,
     const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n, int32_t T, int64_t n_tiles, int64_t tiles_per_wg,
     int64_t wgs_per_xcd, int remap)
 {
-    __shared__ __align__(16) float s_A[2][kSgRows * kSgAStride];       // 67,584 B
+    constexpr int kABytes = kSplit ? 3 * kSgPlane : kSgRows * kSgAStride * 4;   // 52,224 or 33,792 B per tile
+    __shared__ __align__(16) char s_Araw[2][kABytes];
     __shared__ __align__(16) float s_O[2][kSgRows * kSgOStride];       // 34,816 B
     __shared__ __align__(8) int64_t s_slot[kSgProducers][kSgSlots];  // byte offset (from X) of slot k of row r at [6 r + k]
     __shared__ __align__(8) float s_slotw[kSgProducers][kSgSlots];   // its weight (explicit weights only)
@@ -91,26 +137,68 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
         // =================================== consumer ===================================
         const int w = wv;
         const int kq = l / 16, jcol = 16 * w + l % 16;           // k slot / output column
-        // A lane reads four consecutive k of a tile row at once (k = 16 j + 4 kq + i, i = 0..3); matrix
+        const float bias_v = bias ? bias[jcol] : 0.0f;
+        // Split path: matrix instruction (ks, pieces) contracts k = 32 ks + 8 kq + e, e = 0..7; a lane's B operand
+        // is the eight weights Wcat[32 ks + 8 kq + e][jcol], cut once into bw[ks][piece].
+        // fp32 path: a lane reads four consecutive k of a tile row at once (k = 16 j + 4 kq + i, i = 0..3); matrix
         // instruction (j, i) contracts the four k slots kq = 0..3, so its B operand is
         // bfrag[4 j + i] = Wcat[16 j + 4 kq + i][jcol].
-        float bfrag[32];
+        sg_u4 bw[kSplit ? 4 : 1][3];
+        float bfrag[kSplit ? 1 : 32];
+        if constexpr (kSplit) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+            for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = 16 * j + 4 * kq + i;
-                bfrag[4 * j + i] = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
-            }
-        const float bias_v = bias ? bias[jcol] : 0.0f;
+                for (int e = 0; e < 8; e += 2) {
+                    const int k = 32 * ks + 8 * kq + e;
+                    const float w0 = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
+                    const float w1 = k + 1 < 64 ? Wn[(k + 1) * 64 + jcol] : Ws[(k + 1 - 64) * 64 + jcol];
+                    unsigned h, m, lo_;
+                    sage_split3(w0, w1, h, m, lo_);
+                    bw[ks][0][e / 2] = h;
+                    bw[ks][1][e / 2] = m;
+                    bw[ks][2][e / 2] = lo_;
+                }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int k = 16 * j + 4 * kq + i;
+                    bfrag[4 * j + i] = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
+                }
+        }
         sage_lds_barrier();                                      // the first tile is in s_A[0]
         int cur = 0;
         for (int64_t tile = tile_begin; tile < tile_end; ++tile) {
-            const float *a_tile = s_A[cur];
             float *o_tile = s_O[cur];
             v4f acc[4];
 #pragma unroll
             for (int rb = 0; rb < 4; ++rb) acc[rb] = (v4f){bias_v, bias_v, bias_v, bias_v};
+            if constexpr (kSplit) {
+                const char *a_base = s_Araw[cur] + (l % 16) * kSgBRow + 16 * kq;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    sg_u4 a[3][4];
+#pragma unroll
+                    for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb)
+                            a[pc][rb] = *(const sg_u4 *)(a_base + pc * kSgPlane + rb * 16 * kSgBRow + 64 * ks);
+                    // the six piece products, smallest first; four independent accumulators per product
+                    constexpr int kPa[6] = {1, 2, 0, 1, 0, 0}, kPb[6] = {1, 0, 2, 0, 1, 0};
+#pragma unroll
+                    for (int t = 0; t < 6; ++t) {
+#pragma unroll
+                        for (int rb = 0; rb < 4; ++rb)
+                            acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sg_bf8, a[kPa[t]][rb]),
+                                                                              __builtin_bit_cast(sg_bf8, bw[ks][kPb[t]]),
+                                                                              acc[rb], 0, 0, 0);
+                        sage_consumer_pause<kGap>();
+                    }
+                }
+            } else {
+            const float *a_tile = (const float *)s_Araw[cur];
             // operands of step j+1 are read while the 16 matrix instructions of step j run
             v4f a[2][4];
 #pragma unroll
@@ -130,6 +218,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
                         acc[rb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j & 1][rb][i], bfrag[4 * j + i], acc[rb], 0, 0, 0);
                     sage_consumer_pause<kGap>();
                 }
+            }
             }
             // result (lane holds rows 4 kq + r of its column) to the output tile
 #pragma unroll
@@ -241,7 +330,18 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
             q.xs[k] = *(const v4f *)(Xf + off);
         }
     };
-    auto finish = [&](RowRegs &q, int grp, float *buf) {
+    // a row's [agg | self] slice of this lane into the LDS tile: fp32, or cut into the three bf16 planes
+    auto park = [&](char *buf, int row_in_tile, v4f agg, v4f self) {
+        if constexpr (kSplit) {
+            sage_park_split(buf, row_in_tile, 4 * f, agg);
+            sage_park_split(buf, row_in_tile, 64 + 4 * f, self);
+        } else {
+            float *dst = (float *)buf + row_in_tile * kSgAStride + 4 * f;
+            *(v4f *)dst = agg;
+            *(v4f *)(dst + 64) = self;
+        }
+    };
+    auto finish = [&](RowRegs &q, int grp, char *buf) {
         const int lr = grp * 4 + g;
         v4f agg = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -250,12 +350,10 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
             else agg += q.xs[k];
         }
         if (W != kExplicit) agg *= q.inv;
-        float *dst = &buf[(kSgProdRows * p + lr) * kSgAStride + 4 * f];
-        *(v4f *)dst = agg;
-        *(v4f *)(dst + 64) = q.self;                             // rows past the end are never stored
+        park(buf, kSgProdRows * p + lr, agg, q.self);            // rows past the end are never stored
     };
     // Any other row (long, high-degree, or next to one): straight from global memory, not overlapped.
-    auto slow_rows = [&](int64_t tile, int grp, float *buf) {
+    auto slow_rows = [&](int64_t tile, int grp, char *buf) {
         const int lr = grp * 4 + g;
         const int64_t row = tile * kSgRows + kSgProdRows * p + lr;
         v4f agg = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
@@ -265,9 +363,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
             if (e - s >= T) agg = H[row * kSgF4 + f];            // aggregated by the HD kernel
             else agg = ld_row_sum<W, false, kSgD>(s, e, col, val, X, kSgF4, f);
         }
-        float *dst = &buf[(kSgProdRows * p + lr) * kSgAStride + 4 * f];
-        *(v4f *)dst = agg;
-        *(v4f *)(dst + 64) = self;
+        park(buf, kSgProdRows * p + lr, agg, self);
     };
     // The producer's 8 rows of a finished tile: LDS output tile -> H, full rows.
     auto store_rows = [&](int64_t tile, const float *o_tile) {
@@ -283,7 +379,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
 
     // ---- prologue: the first tile is aggregated on its own, the second one is put in flight
 #pragma unroll 1
-    for (int grp = 0; grp < kSgGroups; ++grp) slow_rows(tile_begin, grp, s_A[0]);
+    for (int grp = 0; grp < kSgGroups; ++grp) slow_rows(tile_begin, grp, s_Araw[0]);
     rp_a = load_rp(tile_begin + 1);
     load_cols();
     stage();
@@ -300,7 +396,7 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
         // While the consumers multiply `tile` (s_A[cur] -> s_O[cur]): store the result of tile-1, finish
         // tile+1 into s_A[cur^1], put tile+2 in flight.  Past the workgroup's last tile the pipeline runs
         // on empty: the loads still go to valid addresses, the sums land in the LDS tile nobody reads.
-        float *a_next = s_A[cur ^ 1];
+        char *a_next = s_Araw[cur ^ 1];
         stage();                                                 // CSR of tile+2 -> slot table
         rp_a = rp_b;
         load_cols();                                             // column indices of tile+3
@@ -343,10 +439,13 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
     // when the matrix has no entries, or no weight array
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
-#define GROOT_SAGE_LAUNCH(GAP)                                                                                       \
-    GROOT_DISPATCH_W(dp.weight_mode, (sage_kernel<kW, GAP><<<dim3((unsigned)n_wg), dim3(kSgThreads), 0, st>>>(           \
+#define GROOT_SAGE_LAUNCH2(GAP, SPLIT)                                                                               \
+    GROOT_DISPATCH_W(dp.weight_mode, (sage_kernel<kW, GAP, SPLIT><<<dim3((unsigned)n_wg), dim3(kSgThreads), 0, st>>>(    \
                                          dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)H, dp.zero_row, Wn, Ws, bias, \
                                          relu, dp.n, dp.threshold, n_tiles, tiles_per_wg, n_wg / kXcds, remap)))
+#define GROOT_SAGE_LAUNCH(GAP)                                  \
+    if (tuning().sage_split) { GROOT_SAGE_LAUNCH2(GAP, true); } \
+    else { GROOT_SAGE_LAUNCH2(GAP, false); }
     switch (tuning().sage_gap) {
     case 0: GROOT_SAGE_LAUNCH(0); break;
     case 1: GROOT_SAGE_LAUNCH(1); break;
@@ -355,6 +454,7 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
     default: GROOT_SAGE_LAUNCH(2); break;
     }
 #undef GROOT_SAGE_LAUNCH
+#undef GROOT_SAGE_LAUNCH2
     return (int)hipGetLastError();
 }
 

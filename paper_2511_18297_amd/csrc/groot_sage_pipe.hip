@@ -1,0 +1,376 @@
+// Fused GraphSAGE-mean layer for gfx950, self-contained wavefronts (two per SIMD):
+//     H = act((A_hat X) Wn + X Ws + b),   F_in = F_out = 64.
+//
+// The aggregation is the software-pipelined LD kernel's (a persistent workgroup per CU, every wavefront walks
+// its own tiles and keeps a whole tile of gathers in flight; slot table in LDS, zero row for dead slots, no
+// workgroup barrier after the start).  A tile here is 16 rows, the height of a matrix instruction.  Instead
+// of storing the 16 sums, the wavefront parks [A_hat X | X] of its tile in its own LDS region, multiplies it
+// with the stacked weights [Wn; Ws] (128 x 64) on the matrix cores, passes the 16 x 64 result through LDS once
+// more to get whole rows per lane group, and stores them.  Nothing is shared between wavefronts, so nothing
+// waits for another wavefront; while a wavefront multiplies, the gathers of its next tile are in flight, and
+// the second wavefront of its SIMD issues whenever the first one waits (with one wavefront per SIMD, which
+// could keep the weights in registers, every wait of that wavefront idles the SIMD: 25.9 against 24.5 ms of
+// the 12-wavefront kernel).
+//
+// The dense product keeps fp32 accuracy on the bf16 matrix instruction (v_mfma_f32_16x16x32_bf16, a sixteenth
+// of the fp32 instruction's time per multiply-add): every fp32 operand is cut into three bf16 pieces,
+// x = hi + mid + lo up to 2^-24 |x|, and a product keeps the six piece products down to 2^-16 relative size
+// (hi hi, hi mid, mid hi, hi lo, lo hi, mid mid; the dropped ones are below 2^-24), summed in fp32 in the
+// instruction's accumulator.  The weights are cut once per workgroup into LDS, in the operand layout of the
+// instruction (48 KB, one 16-byte read per lane and operand); the tile is cut when it is parked.
+//
+// High-degree rows are aggregated beforehand by the HD kernel into H itself; a tile that contains one (or a
+// row with more than kSpD entries, or the ragged end) is redone by a plain path that picks those sums up.
+#include <type_traits>
+
+#include "groot_device.h"
+
+namespace groot {
+
+constexpr int kSpD = 6;                      // slots per row on the pipelined path
+constexpr int kSpWaves = 8;                  // wavefronts per workgroup, one workgroup per CU
+constexpr int kSpL = 16;                     // lanes per row: 64 features = 16 float4
+constexpr int kSpRpg = kWave / kSpL;         // rows per lane-group sweep
+constexpr int kSpG = 4;                      // sweeps per tile
+constexpr int kSpRows = kSpG * kSpRpg;       // 16 rows per tile
+constexpr int kSpSlots = kSpRows * kSpD;     // 96
+constexpr int kSpH = (kSpSlots + kWave - 1) / kWave;
+constexpr int kSpBRow = 272;                 // bytes per LDS row of one bf16 plane of [agg | self] (256 + 16: conflict-free)
+constexpr int kSpPlane = kSpRows * kSpBRow;  // 4,352 B
+constexpr int kSpOStride = 68;               // floats per LDS row of the result tile
+static_assert(kSpRows * 64 <= kTrashFloats, "rows past the end of the matrix are stored to the trash area");
+
+typedef __bf16 sp_bf2 __attribute__((ext_vector_type(2)));
+typedef __bf16 sp_bf8 __attribute__((ext_vector_type(8)));
+typedef unsigned int sp_u4 __attribute__((ext_vector_type(4)));
+typedef unsigned int sp_u2 __attribute__((ext_vector_type(2)));
+typedef float sp_f2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void sp_wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// two fp32 values -> their bf16 roundings (nearest even), packed: a in the low half
+__device__ __forceinline__ unsigned sp_pack2(float a, float b)
+{
+    const sp_f2 x = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(x, sp_bf2));
+}
+
+// (a, b) = hi + mid + lo, three packed bf16 pairs; the remainders are exact in fp32
+__device__ __forceinline__ void sp_split3(float a, float b, unsigned &hi, unsigned &mid, unsigned &lo)
+{
+    hi = sp_pack2(a, b);
+    float ra = a - __builtin_bit_cast(float, hi << 16), rb = b - __builtin_bit_cast(float, hi & 0xffff0000u);
+    mid = sp_pack2(ra, rb);
+    ra -= __builtin_bit_cast(float, mid << 16);
+    rb -= __builtin_bit_cast(float, mid & 0xffff0000u);
+    lo = sp_pack2(ra, rb);
+}
+
+// four consecutive elements k..k+3 of tile row `row` into the three planes
+__device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
+{
+    unsigned h0, m0, l0, h1, m1, l1;
+    sp_split3(x[0], x[1], h0, m0, l0);
+    sp_split3(x[2], x[3], h1, m1, l1);
+    char *p = tile + row * kSpBRow + k * 2;
+    *(sp_u2 *)p = (sp_u2){h0, h1};
+    *(sp_u2 *)(p + kSpPlane) = (sp_u2){m0, m1};
+    *(sp_u2 *)(p + 2 * kSpPlane) = (sp_u2){l0, l1};
+}
+
+template <int W>   // kOnes or kMean
+__global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void sage_pipe_kernel(
+    const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
+    const char *__restrict__ X, char *H, const char *__restrict__ zero_row, char *trash,
+    const float *__restrict__ Wn, const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n,
+    int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
+{
+    struct SlotW { int64_t off; float w; float pad; };
+    using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
+    __shared__ __align__(16) Slot s_slot[kSpWaves][kSpSlots];
+    __shared__ float s_inv[kSpWaves][kSpRows];
+    __shared__ __align__(16) char s_A[kSpWaves][3 * kSpPlane];           // 13,056 B per wavefront; the result tile reuses it
+    __shared__ __align__(16) sp_u4 s_W[4][4][3][kWave];                  // 49,152 B: [nb][ks][piece][lane] B operands
+    __shared__ float s_bias[64];
+    static_assert(kSpRows * kSpOStride * 4 <= 3 * kSpPlane, "the result tile fits the parked tile's space");
+
+    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
+    const int g = l / kSpL, f = l % kSpL;
+    const int kq = l / 16, jl = l % 16;                  // matrix instruction: k block / row (A), column (B, D)
+    const int64_t part = blockIdx.x % parts, j = (blockIdx.x / parts) * kSpWaves + w;
+    const int64_t x_begin = part * tiles_per_part;
+    const int64_t x_end = x_begin + tiles_per_part < n_tiles ? x_begin + tiles_per_part : n_tiles;
+    const int64_t t_first = x_begin + j, stride = waves_per_part;
+    const int64_t zero_off = zero_row - X;
+    const char *Xf = X + 16 * f;
+
+    // ---- the weights, cut once per workgroup: s_W[nb][ks][piece][lane] is the B operand of output columns
+    //      16 nb .. 16 nb + 15 for k = 32 ks + 8 kq + e, e = 0..7.  Wavefront w cuts (nb, ks) = (w / 2, 2 (w % 2) + 0..1).
+    //      Every wavefront reaches this barrier (none has left yet, nothing is in flight).
+    {
+        const int nb = w / 2, jcol = 16 * nb + jl;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int ks = 2 * (w % 2) + kk;
+            sp_u4 pc[3];
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                const int k = 32 * ks + 8 * kq + e;
+                const float w0 = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
+                const float w1 = k + 1 < 64 ? Wn[(k + 1) * 64 + jcol] : Ws[(k + 1 - 64) * 64 + jcol];
+                unsigned h, m, lo_;
+                sp_split3(w0, w1, h, m, lo_);
+                pc[0][e / 2] = h;
+                pc[1][e / 2] = m;
+                pc[2][e / 2] = lo_;
+            }
+#pragma unroll
+            for (int q = 0; q < 3; ++q) s_W[nb][ks][q][l] = pc[q];
+        }
+    }
+    if (threadIdx.x < 64) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
+    __syncthreads();
+    if (t_first >= x_end) return;
+
+    // ---- CSR pipeline: rp_a and cc/vv belong to the next tile to be staged, rp_b to the one after
+    int64_t rp_a = 0, rp_b = 0;
+    int32_t cc[kSpH];
+    float vv[kSpH];
+#pragma unroll
+    for (int h = 0; h < kSpH; ++h) { cc[h] = 0; vv[h] = 0.f; }
+    bool simple_a = false;
+    auto load_rp = [&](int64_t tile) -> int64_t {
+        const int64_t ri = tile * kSpRows + (l < kSpRows ? l : kSpRows);
+        return rowptr[ri < n ? ri : n];                  // lanes 0..kSpRows hold the pointers; rows past the end read rowptr[n]
+    };
+    auto load_cols = [&](int64_t tile) {                 // from rp_a
+        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kSpRows), rp_next = __shfl_down(rp_a, 1);
+        const int64_t len = rp_next - rp_a;
+        const bool full = (tile + 1) * kSpRows <= n && tile < x_end;
+        simple_a = full && __ballot(l < kSpRows && (len > kSpD || len >= T)) == 0;
+        const int32_t m = simple_a ? (int32_t)(t_end - begin) : 0;          // <= kSpSlots
+        // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
+#pragma unroll
+        for (int h = 0; h < kSpH; ++h) {
+            const int64_t i = l + kWave * h < m ? begin + l + kWave * h : 0;
+            cc[h] = __builtin_nontemporal_load(&col[i]);
+            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
+        }
+    };
+    auto stage = [&]() -> bool {                         // rp_a, cc, vv -> slot table; a tile that is not simple is staged as empty
+        const int32_t rel = simple_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
+#pragma unroll
+        for (int h = 0; h < kSpH; ++h) {
+            const int s = l + kWave * h;                 // slot s: row r, entry k
+            const int r = s / kSpD, k = s - r * kSpD;
+            const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
+            const int src = lo + k;
+            int32_t c = 0;
+            float wt = 0.f;
+#pragma unroll
+            for (int q = 0; q < kSpH; ++q) {
+                const int32_t cq = __shfl(cc[q], src - kWave * q);
+                c = (src >> 6) == q ? cq : c;
+                if (W == kExplicit) {
+                    const float wq = __shfl(vv[q], src - kWave * q);
+                    wt = (src >> 6) == q ? wq : wt;
+                }
+            }
+            const bool live = k < hi - lo;
+            if (s < kSpSlots) {
+                const int64_t off = live ? ((int64_t)c << 8) : zero_off;
+                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
+                else s_slot[w][s] = off;
+            }
+        }
+        const int32_t len = __shfl_down(rel, 1) - rel;   // all lanes take part in the exchange
+        if (W == kMean && l < kSpRows) s_inv[w][l] = row_weight<kMean>(len);
+        sp_wave_sync();
+        return simple_a;
+    };
+
+    // ---- one group: kSpRpg rows, one per lane group: the row's own features and its kSpD slots
+    struct Regs {
+        v4f xs[kSpD], self;
+        float ws[W == kExplicit ? kSpD : 1];
+        float inv;
+    };
+    Regs rr[kSpG];
+    auto issue = [&](Regs &q, int64_t tile, int grp) {
+        const int lr = grp * kSpRpg + g;
+        int64_t row = tile * kSpRows + lr;
+        row = row < n ? row : n - 1;                     // past the end: any valid row, the result is not kept
+        if (W == kMean) q.inv = s_inv[w][lr];
+        q.self = *(const v4f *)(Xf + (row << 8));
+#pragma unroll
+        for (int k = 0; k < kSpD; ++k) {
+            if constexpr (W == kExplicit) {
+                const SlotW sl = s_slot[w][lr * kSpD + k];
+                q.xs[k] = *(const v4f *)(Xf + sl.off);
+                q.ws[k] = sl.w;
+            } else {
+                q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * kSpD + k]);
+            }
+        }
+    };
+    auto sum = [&](const Regs &q) -> v4f {
+        v4f a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < kSpD; ++k) {
+            if (W == kExplicit) a += q.ws[k] * q.xs[k];
+            else a += q.xs[k];
+        }
+        if (W == kMean) a *= q.inv;
+        return a;
+    };
+
+    // ---- prologue: the first tile is staged and put in flight, the CSR of the next two is on its way
+    rp_a = load_rp(t_first);
+    load_cols(t_first);
+    bool simple_cur = stage();
+    rp_a = load_rp(t_first + stride);
+    load_cols(t_first + stride);
+    rp_b = load_rp(t_first + 2 * stride);
+#pragma unroll
+    for (int grp = 0; grp < kSpG; ++grp) issue(rr[grp], t_first, grp);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): the loop's own order of loads is the only one from here on
+
+    char *const a_tile = s_A[w];
+    float *const o_tile = (float *)s_A[w];               // after the products the parked tile is dead
+    for (int64_t tile = t_first; tile < x_end; tile += stride) {
+        const bool simple_next = stage();                // CSR of the next tile -> slot table (this tile's groups are all issued)
+        rp_a = rp_b;
+        load_cols(tile + 2 * stride);
+        rp_b = load_rp(tile + 3 * stride);
+        const int64_t base = tile * kSpRows;
+        // sums of this tile -> LDS, cut into bf16 pieces; the same register set takes the rows of the next tile
+#pragma unroll
+        for (int grp = 0; grp < kSpG; ++grp) {
+            const v4f a = sum(rr[grp]);
+            sp_park(a_tile, grp * kSpRpg + g, 4 * f, a);
+            sp_park(a_tile, grp * kSpRpg + g, 64 + 4 * f, rr[grp].self);
+            issue(rr[grp], tile + stride, grp);
+        }
+        if (!simple_cur) {
+            // plain path: the rows of this tile straight from global memory, high-degree sums from H
+#pragma unroll 1
+            for (int grp = 0; grp < kSpG; ++grp) {
+                const int64_t row = base + grp * kSpRpg + g;
+                v4f a = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
+                if (row < n) {
+                    self = *(const v4f *)(Xf + (row << 8));
+                    const int64_t s = rowptr[row], e = rowptr[row + 1];
+                    if (e - s >= T) a = *(const v4f *)(H + (row << 8) + 16 * f);
+                    else a = ld_row_sum<W, false, kSpD>(s, e, col, val, (const v4f *)X, kSpL, f);
+                }
+                sp_park(a_tile, grp * kSpRpg + g, 4 * f, a);
+                sp_park(a_tile, grp * kSpRpg + g, 64 + 4 * f, self);
+            }
+        }
+        sp_wave_sync();
+        // ---- [agg | self] (16 x 128) times [Wn; Ws] (128 x 64): lane (jl, kq) reads row jl, k = 32 ks + 8 kq + 0..7
+        v4f acc[4];
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            const float bv = s_bias[16 * nb + jl];
+            acc[nb] = (v4f){bv, bv, bv, bv};
+        }
+        const char *a_lane = a_tile + jl * kSpBRow + 16 * kq;
+        // Twelve steps (ks, weight piece pb = hi, mid, lo), each against the tile pieces whose product is kept
+        // (hi: lo, mid, hi; mid: mid, hi; lo: hi), on four independent accumulators.  The weight operands of step
+        // s + 1 are read from LDS while step s runs; a tile piece of the next ks is read as soon as its register
+        // is dead (lo after the first step, mid after the second, hi after the third, where the first eight
+        // matrix instructions of the next ks do not need it yet).
+        sp_u4 aop[3], bop[2][4];
+        auto read_a = [&](int ks, int pc) { aop[pc] = *(const sp_u4 *)(a_lane + pc * kSpPlane + 64 * ks); };
+        auto read_b = [&](int s_) {
+            const int ks = s_ / 3, pb = s_ % 3;
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) bop[s_ & 1][nb] = s_W[nb][ks][pb][l];
+        };
+        read_a(0, 2);
+        read_a(0, 1);
+        read_a(0, 0);
+        read_b(0);
+#pragma unroll
+        for (int s_ = 0; s_ < 12; ++s_) {
+            const int ks = s_ / 3, pb = s_ % 3;
+            if (s_ + 1 < 12) read_b(s_ + 1);
+            if (ks + 1 < 4 && pb == 1) read_a(ks + 1, 2);            // lo is dead after the first step of ks
+            if (ks + 1 < 4 && pb == 2) read_a(ks + 1, 1);            // mid after the second
+            __builtin_amdgcn_sched_barrier(0);                       // the reads stay ahead of this step's matrix instructions
+#pragma unroll
+            for (int pa = 2 - pb; pa >= 0; --pa)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sp_bf8, aop[pa]),
+                                                                      __builtin_bit_cast(sp_bf8, bop[s_ & 1][nb]),
+                                                                      acc[nb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < 4 && pb == 2) read_a(ks + 1, 0);            // hi after the third
+        }
+        sp_wave_sync();                                  // all reads of the parked tile are done: its space takes the result
+        // ---- result: lane holds rows 4 kq + r of column 16 nb + jl; through LDS to whole rows per lane group
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float v = acc[nb][r];
+                if (relu) v = v > 0.0f ? v : 0.0f;
+                o_tile[(4 * kq + r) * kSpOStride + 16 * nb + jl] = v;
+            }
+        sp_wave_sync();
+#pragma unroll
+        for (int grp = 0; grp < kSpG; ++grp) {
+            const int lr = grp * kSpRpg + g;
+            const int64_t row = base + lr;
+            const v4f v = *(const v4f *)&o_tile[lr * kSpOStride + 4 * f];
+            char *dst = row < n ? H + (row << 8) : trash + (lr << 8);
+            __builtin_nontemporal_store(v, (v4f *)(dst + 16 * f));
+        }
+        sp_wave_sync();                                  // the tiles in LDS are free for the next round
+        simple_cur = simple_next;
+    }
+}
+
+int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
+                     int relu, void *stream)
+{
+    if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
+    int dev = 0, cus = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return (int)e;
+    const int64_t n_tiles = (dp.n + kSpRows - 1) / kSpRows;
+    // one workgroup per CU; consecutive workgroup ids land on different XCDs
+    int64_t n_wg = cus / kXcds * kXcds;
+    if (n_wg < kXcds) n_wg = kXcds;
+    const int32_t parts = dp.xcd_remap ? kXcds : 1;
+    const int64_t tiles_per_part = (n_tiles + parts - 1) / parts;
+    const int64_t waves_per_part = n_wg / parts * kSpWaves;
+    if (!grid_ok(n_wg) || n_tiles <= 0) return (int)hipErrorInvalidConfiguration;
+    // the kernel reads entry 0 of the index (and weight) array from idle lanes: give it something to read
+    // when the matrix has no entries, or no weight array
+    const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
+    const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
+    char *trash = (char *)(dp.zero_row + kZeroRowFloats);
+    hipStream_t st = (hipStream_t)stream;
+    // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
+    if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
+#define GROOT_SAGE_PIPE_LAUNCH(WM)                                                                                    \
+    sage_pipe_kernel<WM><<<dim3((unsigned)n_wg), dim3(kSpWaves * kWave), 0, st>>>(                                    \
+        dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, (const char *)dp.zero_row, trash, Wn, Ws, bias, relu, \
+        dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts)
+    if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean);
+    else GROOT_SAGE_PIPE_LAUNCH(kOnes);
+#undef GROOT_SAGE_PIPE_LAUNCH
+    return (int)hipGetLastError();
+}
+
+}  // namespace groot
