@@ -179,7 +179,10 @@ groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev,
  * products on the matrix cores, so A_hat X is neither written nor re-read.
  * X_dev, H_dev (device): row-major [N,F] fp32, 16-byte aligned, not overlapping.
  * Wn_dev, Ws_dev (device): row-major [F,F] fp32 (input feature major: H = X W);
- * bias_dev: [F] fp32 or NULL.  F must be 64 (input = output width).  fp32 throughout.
+ * bias_dev: [F] fp32 or NULL.  F must be 64 (input = output width).  fp32 in and out,
+ * fp32 sums; a dense product is formed on the matrix cores from three bf16 pieces per
+ * fp32 operand (six piece products, fp32 accumulation), which keeps the relative error
+ * of a product below 2^-23, as an fp32 multiplication does.
  * The plan must be uploaded with max_F >= 64.  Only enqueues on hip_stream; one
  * call per plan in flight.  Errors: EINVAL (NULL, alignment, F != 64, plan not
  * uploaded), EHIP.
@@ -316,8 +319,12 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
 
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
  * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
- * 64..4096 non-zeros, read by groot_spmm_plan), "sage_gap" (0..4, the pause
- * between matrix instructions in groot_sage_layer_forward, read at each call)
+ * 64..4096 non-zeros, read by groot_spmm_plan), "sage_kernel" (1, default: the fused
+ * layer runs as self-contained wavefronts; 0: as producer and consumer
+ * wavefronts; graphs with explicit weights always take the latter),
+ * "sage_split" (kernel 0 only: 1 bf16 piece products, 0 fp32 matrix
+ * instructions), "sage_gap" (kernel 0 only: 0..4, the pause between its matrix
+ * instructions; all three read at each call of groot_sage_layer_forward)
  * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
  * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one for F = 64
  * and 128 when at least 99.9 % of the low-degree rows have at most 6 entries;

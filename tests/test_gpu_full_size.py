@@ -86,6 +86,17 @@ def test_config3_spmm_and_graphsage_forward(torch_cuda, one_copy):
     err2 = np.abs(H2.cpu().numpy().astype(np.float64) - H2_ref)
     assert np.isfinite(err2).all() and (err2 <= tol2).all(), f"layer 2: max err/tol {np.max(err2 / tol2)}"
 
+    # the same two layers through the fused layer kernel (aggregation kept on chip), same error model
+    F1 = torch.full_like(X, float("nan"))
+    F2 = torch.full_like(X, float("nan"))
+    G.groot_sage_layer_forward(plan, X, dev(W1n), dev(W1s), dev(b1), True, F1, F)
+    G.groot_sage_layer_forward(plan, F1, dev(W2n), dev(W2s), dev(b2), False, F2, F)
+    torch.cuda.synchronize()
+    e1 = np.abs(F1.cpu().numpy().astype(np.float64) - H1_ref.astype(np.float64))
+    assert np.isfinite(e1).all() and (e1 <= tol1).all(), f"fused layer 1: max err/tol {np.max(e1 / tol1)}"
+    e2 = np.abs(F2.cpu().numpy().astype(np.float64) - H2_ref)
+    assert np.isfinite(e2).all() and (e2 <= tol2).all(), f"fused layer 2: max err/tol {np.max(e2 / tol2)}"
+
 
 def _sample_rows(rng, n1, batch, n_random):
     picks = [rng.integers(0, n1 * batch, size=n_random)]

@@ -195,6 +195,21 @@ def test_transposed_spmm(torch_cuda, case):
     assert_close_to_oracle(dX, want, S, f"transposed {case}")
 
 
+SAGE_VARIANTS = {"wavefronts": dict(sage_kernel=1), "roles-bf16": dict(sage_kernel=0, sage_split=1),
+                 "roles-fp32": dict(sage_kernel=0, sage_split=0)}
+
+
+@pytest.fixture(params=sorted(SAGE_VARIANTS))
+def sage_variant(request):
+    """Every fused-layer test runs with each kernel: the self-contained wavefronts (bf16 piece products), and
+    the 12-wavefront kernel with bf16 piece products and with fp32 matrix instructions."""
+    for k, v in SAGE_VARIANTS[request.param].items():
+        G.groot_set_tuning(k, v)
+    yield request.param
+    G.groot_set_tuning("sage_kernel", 1)
+    G.groot_set_tuning("sage_split", 1)
+
+
 def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what):
     F = 64
     rng = np.random.default_rng(seed)
@@ -221,12 +236,13 @@ def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what):
     err = np.abs(out[guard:n + guard].astype(np.float64) - want)
     assert np.isfinite(err).all(), f"{what}: non-finite output"
     assert (err <= tol).all(), f"{what}: max err/tol {np.max(err / tol)}"
+    return out[guard:n + guard], scale
 
 
 @pytest.mark.parametrize("n_bits,batch,T,relu,with_bias", [(48, 2, 32, True, True), (48, 1, 32, False, False),
                                                             (3, 1, 32, True, True), (17, 3, 5, True, False),
                                                             (40, 1, 1, False, True)])
-def test_fused_sage_layer_on_multipliers(torch_cuda, n_bits, batch, T, relu, with_bias):
+def test_fused_sage_layer_on_multipliers(torch_cuda, sage_variant, n_bits, batch, T, relu, with_bias):
     """H = act((A_hat X) Wn + X Ws + b) with the aggregation kept on chip; rows counts that are not
     multiples of the 64-row tile, high-degree rows (picked up from the HD kernel), every row high-degree."""
     aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
@@ -234,7 +250,27 @@ def test_fused_sage_layer_on_multipliers(torch_cuda, n_bits, batch, T, relu, wit
                 f"sage {n_bits}x{batch} T={T}")
 
 
-def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda):
+def test_fused_sage_layer_bf16_pieces_keep_fp32_accuracy(torch_cuda):
+    """The six-piece products must be as accurate as fp32 matrix instructions, not merely within the layer's
+    tolerance: both kernels that use them stay within 4e-6 of the sum of absolute terms from the fp32 kernel's
+    result (dropping the low pieces, i.e. plain 16-bit operands, would leave about 1.5e-5)."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(40, 2)
+    n = 2 * aig.num_nodes
+    outs = {}
+    try:
+        for name, knobs in SAGE_VARIANTS.items():
+            for k, v in knobs.items():
+                G.groot_set_tuning(k, v)
+            outs[name], scale = _sage_check(torch_cuda, g, rowptr, col, val, 32, n, 77, False, True, f"sage {name}")
+    finally:
+        G.groot_set_tuning("sage_kernel", 1)
+        G.groot_set_tuning("sage_split", 1)
+    for name in ("wavefronts", "roles-bf16"):
+        diff = np.abs(outs[name].astype(np.float64) - outs["roles-fp32"].astype(np.float64))
+        assert (diff <= 4e-6 * scale + 1e-7).all(), f"{name}: {np.max(diff / (4e-6 * scale + 1e-7))}"
+
+
+def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda, sage_variant):
     torch = torch_cuda
     s = wl.stress_graph(11, 1 << 14, window=512, dmin=64, dmax=2048)
     g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
