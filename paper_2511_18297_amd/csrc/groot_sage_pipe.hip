@@ -206,7 +206,6 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
         int64_t row = tile * kSpRows + lr;
         row = row < n ? row : n - 1;                     // past the end: any valid row, the result is not kept
         if (W == kMean) q.inv = s_inv[w][lr];
-        q.self = *(const v4f *)(Xf + (row << 8));
 #pragma unroll
         for (int k = 0; k < kSpD; ++k) {
             if constexpr (W == kExplicit) {
@@ -217,6 +216,7 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
                 q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * kSpD + k]);
             }
         }
+        q.self = *(const v4f *)(Xf + (row << 8));
     };
     auto sum = [&](const Regs &q) -> v4f {
         v4f a = {0.f, 0.f, 0.f, 0.f};
