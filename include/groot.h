@@ -182,7 +182,9 @@ groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev,
  * bias_dev: [F] fp32 or NULL.  F must be 64 (input = output width).  fp32 in and out,
  * fp32 sums; a dense product is formed on the matrix cores from three bf16 pieces per
  * fp32 operand (six piece products, fp32 accumulation), which keeps the relative error
- * of a product below 2^-23, as an fp32 multiplication does.
+ * of a product below 2^-23, as an fp32 multiplication does (the pieces have the
+ * exponent range of fp32; an input above 3.38e38 in magnitude rounds to infinity in
+ * its first piece and gives NaN).
  * The plan must be uploaded with max_F >= 64.  Only enqueues on hip_stream; one
  * call per plan in flight.  Errors: EINVAL (NULL, alignment, F != 64, plan not
  * uploaded), EHIP.

@@ -210,10 +210,12 @@ def sage_variant(request):
     G.groot_set_tuning("sage_split", 1)
 
 
-def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what):
+def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None):
     F = 64
     rng = np.random.default_rng(seed)
     X = wl.uniform_features_numpy(seed, 0, n, F)
+    if row_scale is not None:
+        X = (X * row_scale[:, None]).astype(np.float32)
     Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
     b = rng.uniform(-0.125, 0.125, F).astype(np.float32) if with_bias else None
     plan = G.groot_spmm_plan(g, T)
@@ -268,6 +270,31 @@ def test_fused_sage_layer_bf16_pieces_keep_fp32_accuracy(torch_cuda):
     for name in ("wavefronts", "roles-bf16"):
         diff = np.abs(outs[name].astype(np.float64) - outs["roles-fp32"].astype(np.float64))
         assert (diff <= 4e-6 * scale + 1e-7).all(), f"{name}: {np.max(diff / (4e-6 * scale + 1e-7))}"
+
+
+def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):
+    """Feature rows scaled by powers of two from 2^-60 to 2^60 (each copy of the multiplier its own scale, so
+    that neighbours share it): the bf16 pieces have the exponent range of fp32, so the error stays relative
+    to the terms of each output element at every magnitude."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(24, 5)
+    n = 5 * aig.num_nodes
+    row_scale = np.repeat(np.ldexp(1.0, [-60, -20, 0, 20, 60]), aig.num_nodes).astype(np.float32)
+    F = 64
+    rng = np.random.default_rng(9)
+    X = (wl.uniform_features_numpy(9, 0, n, F) * row_scale[:, None]).astype(np.float32)
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
+    plan = G.groot_spmm_plan(g, 32)
+    G.groot_plan_upload(plan, F)
+    dev = lambda a: torch_cuda.from_numpy(a).cuda()
+    H = torch_cuda.full((n, F), float("nan"), device="cuda")
+    G.groot_sage_layer_forward(plan, dev(X), dev(Wn), dev(Ws), None, False, H, F)
+    torch_cuda.cuda.synchronize()
+    want, A, S = oracle.sage_layer_f64(rowptr, col, val, X, Wn, Ws, None, False)
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale = np.abs(A) @ a64(Wn) + a64(X) @ a64(Ws)
+    tol = (1e-5 * S) @ a64(Wn) + 2e-5 * scale          # purely relative: no absolute floor
+    err = np.abs(H.cpu().numpy().astype(np.float64) - want)
+    assert np.isfinite(err).all() and (err <= tol).all(), f"max err/tol {np.max(err / np.maximum(tol, 1e-300))}"
 
 
 def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda, sage_variant):
