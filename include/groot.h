@@ -179,14 +179,15 @@ groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev,
  * products on the matrix cores, so A_hat X is neither written nor re-read.
  * X_dev, H_dev (device): row-major [N,F] fp32, 16-byte aligned, not overlapping.
  * Wn_dev, Ws_dev (device): row-major [F,F] fp32 (input feature major: H = X W);
- * bias_dev: [F] fp32 or NULL.  F must be 64 (input = output width).  fp32 in and out,
+ * bias_dev: [F] fp32 or NULL.  F (input = output width) must be 64, or 32 for graphs
+ * with row-uniform weights (every graph built from an AIG).  fp32 in and out,
  * fp32 sums; a dense product is formed on the matrix cores from three bf16 pieces per
  * fp32 operand (six piece products, fp32 accumulation), which keeps the relative error
  * of a product below 2^-23, as an fp32 multiplication does (the pieces have the
  * exponent range of fp32; an input above 3.38e38 in magnitude rounds to infinity in
  * its first piece and gives NaN).
- * The plan must be uploaded with max_F >= 64.  Only enqueues on hip_stream; one
- * call per plan in flight.  Errors: EINVAL (NULL, alignment, F != 64, plan not
+ * The plan must be uploaded with max_F >= F.  Only enqueues on hip_stream; one
+ * call per plan in flight.  Errors: EINVAL (NULL, alignment, unsupported F, plan not
  * uploaded), EHIP.
  * ------------------------------------------------------------------------- */
 groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev, const float *Wn_dev,

@@ -588,7 +588,10 @@ extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const f
                                                  float *H_dev, int32_t F, void *hip_stream)
 {
     if (!plan) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL plan");
-    if (F != 64) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F must be 64");
+    if (F != 64 && F != 32) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F must be 64 or 32");
+    const bool wavefronts = plan->resident && tuning().sage_kernel && plan->dev.weight_mode != (int)WeightMode::Explicit;
+    if (F == 32 && plan->resident && !wavefronts)
+        return fail(GROOT_EINVAL, "groot_sage_layer_forward: F = 32 needs row-uniform weights (and the default layer kernel)");
     groot_status st = check_features("groot_sage_layer_forward", X_dev, H_dev, F);
     if (st != GROOT_OK) return st;
     if (!Wn_dev || !Ws_dev) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL weight pointer");
@@ -602,7 +605,7 @@ extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const f
     if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F, hip_stream);
     if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, H_dev, F, hip_stream);
     if (!err)
-        err = tuning().sage_kernel && plan->dev.weight_mode != (int)WeightMode::Explicit ? launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream)
+        err = wavefronts ? launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F, hip_stream)
                                    : launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
     if (err) return fail(GROOT_EHIP, std::string("groot_sage_layer_forward: launch failed: ") + hip_error_text(err));
     return GROOT_OK;

@@ -83,7 +83,7 @@ int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, co
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, void *stream);
+                     int relu, int32_t F, void *stream);   // F = 64 or 32, row-uniform weights
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
 int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
 // Device-side plan lists (groot_plan_device.hip).  Synchronises the stream; kErrOutOfDeviceMemory when its

@@ -1,5 +1,5 @@
 // Fused GraphSAGE-mean layer for gfx950, self-contained wavefronts (two per SIMD):
-//     H = act((A_hat X) Wn + X Ws + b),   F_in = F_out = 64.
+//     H = act((A_hat X) Wn + X Ws + b),   F_in = F_out = F, F = 64 or 32.
 //
 // The aggregation is the software-pipelined LD kernel's (a persistent workgroup per CU, every wavefront walks
 // its own tiles and keeps a whole tile of gathers in flight; slot table in LDS, zero row for dead slots, no
@@ -28,17 +28,28 @@
 namespace groot {
 
 constexpr int kSpD = 6;                      // slots per row on the pipelined path
-constexpr int kSpWaves = 8;                  // wavefronts per workgroup, one workgroup per CU
-constexpr int kSpL = 16;                     // lanes per row: 64 features = 16 float4
-constexpr int kSpRpg = kWave / kSpL;         // rows per lane-group sweep
-constexpr int kSpG = 4;                      // sweeps per tile
-constexpr int kSpRows = kSpG * kSpRpg;       // 16 rows per tile
+constexpr int kSpRows = 16;                  // rows per tile: the height of a matrix instruction
 constexpr int kSpSlots = kSpRows * kSpD;     // 96
 constexpr int kSpH = (kSpSlots + kWave - 1) / kWave;
-constexpr int kSpBRow = 272;                 // bytes per LDS row of one bf16 plane of [agg | self] (256 + 16: conflict-free)
-constexpr int kSpPlane = kSpRows * kSpBRow;  // 4,352 B
-constexpr int kSpOStride = 68;               // floats per LDS row of the result tile
 static_assert(kSpRows * 64 <= kTrashFloats, "rows past the end of the matrix are stored to the trash area");
+
+// Shapes for F input = F output features (64 or 32) and NW wavefronts per workgroup (one workgroup per CU).
+template <int F, int NW>
+struct SpCfg {
+    static constexpr int kWaves = NW;
+    static constexpr int kL = F / 4;                 // lanes per row, one float4 each
+    static constexpr int kRpg = kWave / kL;          // rows per lane-group sweep
+    static constexpr int kG = kSpRows / kRpg;        // sweeps per tile
+    static constexpr int kRowShift = F == 64 ? 8 : 7;   // log2 of a feature row's bytes
+    static constexpr int kK = 2 * F;                 // contraction length: [agg | self]
+    static constexpr int kKs = kK / 32;              // k blocks of a matrix instruction
+    static constexpr int kNb = F / 16;               // blocks of 16 output columns
+    static constexpr int kBRow = kK * 2 + 16;        // bytes per LDS row of one bf16 plane (16 B of padding: conflict-free)
+    static constexpr int kPlane = kSpRows * kBRow;
+    static constexpr int kOStride = F + 4;           // floats per LDS row of the result tile
+    static_assert(F == 64 || F == 32, "feature width");
+    static_assert(kSpRows * kOStride * 4 <= 3 * kPlane, "the result tile fits the parked tile's space");
+};
 
 typedef __bf16 sp_bf2 __attribute__((ext_vector_type(2)));
 typedef __bf16 sp_bf8 __attribute__((ext_vector_type(8)));
@@ -71,33 +82,36 @@ __device__ __forceinline__ void sp_split3(float a, float b, unsigned &hi, unsign
     lo = sp_pack2(ra, rb);
 }
 
-// four consecutive elements k..k+3 of tile row `row` into the three planes
+// four consecutive elements k..k+3 of tile row `row` into the three planes (row stride kBRow, plane size kPlane)
+template <int kBRow, int kPlane>
 __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
 {
     unsigned h0, m0, l0, h1, m1, l1;
     sp_split3(x[0], x[1], h0, m0, l0);
     sp_split3(x[2], x[3], h1, m1, l1);
-    char *p = tile + row * kSpBRow + k * 2;
+    char *p = tile + row * kBRow + k * 2;
     *(sp_u2 *)p = (sp_u2){h0, h1};
-    *(sp_u2 *)(p + kSpPlane) = (sp_u2){m0, m1};
-    *(sp_u2 *)(p + 2 * kSpPlane) = (sp_u2){l0, l1};
+    *(sp_u2 *)(p + kPlane) = (sp_u2){m0, m1};
+    *(sp_u2 *)(p + 2 * kPlane) = (sp_u2){l0, l1};
 }
 
-template <int W>   // kOnes or kMean
-__global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_eu(2, 2))) void sage_pipe_kernel(
+template <int W, int F, int NW>   // W: kOnes or kMean
+__global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *H, const char *__restrict__ zero_row, char *trash,
     const float *__restrict__ Wn, const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n,
     int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
 {
+    using C = SpCfg<F, NW>;
+    constexpr int kSpWaves = C::kWaves, kSpL = C::kL, kSpRpg = C::kRpg, kSpG = C::kG, kRowShift = C::kRowShift;
+    constexpr int kKs = C::kKs, kNb = C::kNb, kSpBRow = C::kBRow, kSpPlane = C::kPlane, kSpOStride = C::kOStride;
     struct SlotW { int64_t off; float w; float pad; };
     using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
     __shared__ __align__(16) Slot s_slot[kSpWaves][kSpSlots];
     __shared__ float s_inv[kSpWaves][kSpRows];
-    __shared__ __align__(16) char s_A[kSpWaves][3 * kSpPlane];           // 13,056 B per wavefront; the result tile reuses it
-    __shared__ __align__(16) sp_u4 s_W[4][4][3][kWave];                  // 49,152 B: [nb][ks][piece][lane] B operands
-    __shared__ float s_bias[64];
-    static_assert(kSpRows * kSpOStride * 4 <= 3 * kSpPlane, "the result tile fits the parked tile's space");
+    __shared__ __align__(16) char s_A[kSpWaves][3 * kSpPlane];           // F = 64: 13,056 B per wavefront; the result tile reuses it
+    __shared__ __align__(16) sp_u4 s_W[kNb][kKs][3][kWave];              // F = 64: 49,152 B: [nb][ks][piece][lane] B operands
+    __shared__ float s_bias[F];
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int g = l / kSpL, f = l % kSpL;
@@ -110,19 +124,17 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
     const char *Xf = X + 16 * f;
 
     // ---- the weights, cut once per workgroup: s_W[nb][ks][piece][lane] is the B operand of output columns
-    //      16 nb .. 16 nb + 15 for k = 32 ks + 8 kq + e, e = 0..7.  Wavefront w cuts (nb, ks) = (w / 2, 2 (w % 2) + 0..1).
+    //      16 nb .. 16 nb + 15 for k = 32 ks + 8 kq + e, e = 0..7.  The wavefronts share the (nb, ks) pairs.
     //      Every wavefront reaches this barrier (none has left yet, nothing is in flight).
     {
-        const int nb = w / 2, jcol = 16 * nb + jl;
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            const int ks = 2 * (w % 2) + kk;
+        for (int c = w; c < kNb * kKs; c += kSpWaves) {
+            const int nb = c / kKs, ks = c % kKs, jcol = 16 * nb + jl;
             sp_u4 pc[3];
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
                 const int k = 32 * ks + 8 * kq + e;
-                const float w0 = k < 64 ? Wn[k * 64 + jcol] : Ws[(k - 64) * 64 + jcol];
-                const float w1 = k + 1 < 64 ? Wn[(k + 1) * 64 + jcol] : Ws[(k + 1 - 64) * 64 + jcol];
+                const float w0 = k < F ? Wn[k * F + jcol] : Ws[(k - F) * F + jcol];
+                const float w1 = k + 1 < F ? Wn[(k + 1) * F + jcol] : Ws[(k + 1 - F) * F + jcol];
                 unsigned h, m, lo_;
                 sp_split3(w0, w1, h, m, lo_);
                 pc[0][e / 2] = h;
@@ -133,7 +145,7 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
             for (int q = 0; q < 3; ++q) s_W[nb][ks][q][l] = pc[q];
         }
     }
-    if (threadIdx.x < 64) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
+    if (threadIdx.x < F) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
     __syncthreads();
     if (t_first >= x_end) return;
 
@@ -183,7 +195,7 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
             }
             const bool live = k < hi - lo;
             if (s < kSpSlots) {
-                const int64_t off = live ? ((int64_t)c << 8) : zero_off;
+                const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
                 if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
                 else s_slot[w][s] = off;
             }
@@ -216,7 +228,7 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
                 q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * kSpD + k]);
             }
         }
-        q.self = *(const v4f *)(Xf + (row << 8));
+        q.self = *(const v4f *)(Xf + (row << kRowShift));
     };
     auto sum = [&](const Regs &q) -> v4f {
         v4f a = {0.f, 0.f, 0.f, 0.f};
@@ -252,8 +264,8 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
 #pragma unroll
         for (int grp = 0; grp < kSpG; ++grp) {
             const v4f a = sum(rr[grp]);
-            sp_park(a_tile, grp * kSpRpg + g, 4 * f, a);
-            sp_park(a_tile, grp * kSpRpg + g, 64 + 4 * f, rr[grp].self);
+            sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
+            sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, rr[grp].self);
             issue(rr[grp], tile + stride, grp);
         }
         if (!simple_cur) {
@@ -263,61 +275,61 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
                 const int64_t row = base + grp * kSpRpg + g;
                 v4f a = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
                 if (row < n) {
-                    self = *(const v4f *)(Xf + (row << 8));
+                    self = *(const v4f *)(Xf + (row << kRowShift));
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
-                    if (e - s >= T) a = *(const v4f *)(H + (row << 8) + 16 * f);
+                    if (e - s >= T) a = *(const v4f *)(H + (row << kRowShift) + 16 * f);
                     else a = ld_row_sum<W, false, kSpD>(s, e, col, val, (const v4f *)X, kSpL, f);
                 }
-                sp_park(a_tile, grp * kSpRpg + g, 4 * f, a);
-                sp_park(a_tile, grp * kSpRpg + g, 64 + 4 * f, self);
+                sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
+                sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, self);
             }
         }
         sp_wave_sync();
-        // ---- [agg | self] (16 x 128) times [Wn; Ws] (128 x 64): lane (jl, kq) reads row jl, k = 32 ks + 8 kq + 0..7
-        v4f acc[4];
+        // ---- [agg | self] (16 x 2F) times [Wn; Ws] (2F x F): lane (jl, kq) reads row jl, k = 32 ks + 8 kq + 0..7
+        v4f acc[kNb];
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
+        for (int nb = 0; nb < kNb; ++nb) {
             const float bv = s_bias[16 * nb + jl];
             acc[nb] = (v4f){bv, bv, bv, bv};
         }
         const char *a_lane = a_tile + jl * kSpBRow + 16 * kq;
-        // Twelve steps (ks, weight piece pb = hi, mid, lo), each against the tile pieces whose product is kept
-        // (hi: lo, mid, hi; mid: mid, hi; lo: hi), on four independent accumulators.  The weight operands of step
+        // 3 kKs steps (ks, weight piece pb = hi, mid, lo), each against the tile pieces whose product is kept
+        // (hi: lo, mid, hi; mid: mid, hi; lo: hi), on kNb independent accumulators.  The weight operands of step
         // s + 1 are read from LDS while step s runs; a tile piece of the next ks is read as soon as its register
         // is dead (lo after the first step, mid after the second, hi after the third, where the first eight
         // matrix instructions of the next ks do not need it yet).
-        sp_u4 aop[3], bop[2][4];
+        sp_u4 aop[3], bop[2][kNb];
         auto read_a = [&](int ks, int pc) { aop[pc] = *(const sp_u4 *)(a_lane + pc * kSpPlane + 64 * ks); };
         auto read_b = [&](int s_) {
             const int ks = s_ / 3, pb = s_ % 3;
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) bop[s_ & 1][nb] = s_W[nb][ks][pb][l];
+            for (int nb = 0; nb < kNb; ++nb) bop[s_ & 1][nb] = s_W[nb][ks][pb][l];
         };
         read_a(0, 2);
         read_a(0, 1);
         read_a(0, 0);
         read_b(0);
 #pragma unroll
-        for (int s_ = 0; s_ < 12; ++s_) {
+        for (int s_ = 0; s_ < 3 * kKs; ++s_) {
             const int ks = s_ / 3, pb = s_ % 3;
-            if (s_ + 1 < 12) read_b(s_ + 1);
-            if (ks + 1 < 4 && pb == 1) read_a(ks + 1, 2);            // lo is dead after the first step of ks
-            if (ks + 1 < 4 && pb == 2) read_a(ks + 1, 1);            // mid after the second
+            if (s_ + 1 < 3 * kKs) read_b(s_ + 1);
+            if (ks + 1 < kKs && pb == 1) read_a(ks + 1, 2);          // lo is dead after the first step of ks
+            if (ks + 1 < kKs && pb == 2) read_a(ks + 1, 1);          // mid after the second
             __builtin_amdgcn_sched_barrier(0);                       // the reads stay ahead of this step's matrix instructions
 #pragma unroll
             for (int pa = 2 - pb; pa >= 0; --pa)
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb)
+                for (int nb = 0; nb < kNb; ++nb)
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sp_bf8, aop[pa]),
                                                                       __builtin_bit_cast(sp_bf8, bop[s_ & 1][nb]),
                                                                       acc[nb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < 4 && pb == 2) read_a(ks + 1, 0);            // hi after the third
+            if (ks + 1 < kKs && pb == 2) read_a(ks + 1, 0);          // hi after the third
         }
         sp_wave_sync();                                  // all reads of the parked tile are done: its space takes the result
         // ---- result: lane holds rows 4 kq + r of column 16 nb + jl; through LDS to whole rows per lane group
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < kNb; ++nb)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float v = acc[nb][r];
@@ -330,7 +342,7 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
             const int lr = grp * kSpRpg + g;
             const int64_t row = base + lr;
             const v4f v = *(const v4f *)&o_tile[lr * kSpOStride + 4 * f];
-            char *dst = row < n ? H + (row << 8) : trash + (lr << 8);
+            char *dst = row < n ? H + (row << kRowShift) : trash + (lr << kRowShift);
             __builtin_nontemporal_store(v, (v4f *)(dst + 16 * f));
         }
         sp_wave_sync();                                  // the tiles in LDS are free for the next round
@@ -339,21 +351,25 @@ __global__ __launch_bounds__(kSpWaves * kWave) __attribute__((amdgpu_waves_per_e
 }
 
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, void *stream)
+                     int relu, int32_t F, void *stream)
 {
-    if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
+    if (!weights_ok(dp) || !dp.zero_row || (F != 64 && F != 32)) return (int)hipErrorInvalidValue;
+    // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
+    if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return (int)e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
+    // wavefronts per workgroup: two per SIMD (at F = 32 three fit and are slower: 11.4 against 10.2 ms)
+    constexpr int kNwRun = 8;
     const int64_t n_tiles = (dp.n + kSpRows - 1) / kSpRows;
     // one workgroup per CU; consecutive workgroup ids land on different XCDs
     int64_t n_wg = cus / kXcds * kXcds;
     if (n_wg < kXcds) n_wg = kXcds;
     const int32_t parts = dp.xcd_remap ? kXcds : 1;
     const int64_t tiles_per_part = (n_tiles + parts - 1) / parts;
-    const int64_t waves_per_part = n_wg / parts * kSpWaves;
+    const int64_t waves_per_part = n_wg / parts * kNwRun;
     if (!grid_ok(n_wg) || n_tiles <= 0) return (int)hipErrorInvalidConfiguration;
     // the kernel reads entry 0 of the index (and weight) array from idle lanes: give it something to read
     // when the matrix has no entries, or no weight array
@@ -361,14 +377,17 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
-    // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
-    if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
-#define GROOT_SAGE_PIPE_LAUNCH(WM)                                                                                    \
-    sage_pipe_kernel<WM><<<dim3((unsigned)n_wg), dim3(kSpWaves * kWave), 0, st>>>(                                    \
+#define GROOT_SAGE_PIPE_LAUNCH(WM, FF, NW)                                                                            \
+    sage_pipe_kernel<WM, FF, NW><<<dim3((unsigned)n_wg), dim3(NW * kWave), 0, st>>>(                                  \
         dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, (const char *)dp.zero_row, trash, Wn, Ws, bias, relu, \
         dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts)
-    if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean);
-    else GROOT_SAGE_PIPE_LAUNCH(kOnes);
+    if (F == 64) {
+        if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean, 64, 8);
+        else GROOT_SAGE_PIPE_LAUNCH(kOnes, 64, 8);
+    } else {
+        if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean, 32, 8);
+        else GROOT_SAGE_PIPE_LAUNCH(kOnes, 32, 8);
+    }
 #undef GROOT_SAGE_PIPE_LAUNCH
     return (int)hipGetLastError();
 }

@@ -210,8 +210,7 @@ def sage_variant(request):
     G.groot_set_tuning("sage_split", 1)
 
 
-def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None):
-    F = 64
+def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64):
     rng = np.random.default_rng(seed)
     X = wl.uniform_features_numpy(seed, 0, n, F)
     if row_scale is not None:
@@ -250,6 +249,16 @@ def test_fused_sage_layer_on_multipliers(torch_cuda, sage_variant, n_bits, batch
     aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
     _sage_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 100 + n_bits, relu, with_bias,
                 f"sage {n_bits}x{batch} T={T}")
+
+
+@pytest.mark.parametrize("n_bits,batch,T,relu,with_bias", [(48, 2, 32, True, True), (3, 1, 32, False, False),
+                                                            (17, 3, 5, True, False), (40, 1, 1, False, True)])
+def test_fused_sage_layer_width_32(torch_cuda, n_bits, batch, T, relu, with_bias):
+    """The layer at the embedding width of the paper's kernel evaluation (F = 32): 8 lanes per row, two sweeps
+    per 16-row tile, a 64 x 32 weight matrix."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    _sage_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 300 + n_bits, relu, with_bias,
+                f"sage F=32 {n_bits}x{batch} T={T}", F=32)
 
 
 def test_fused_sage_layer_bf16_pieces_keep_fp32_accuracy(torch_cuda):
@@ -307,8 +316,10 @@ def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda, sage_variant):
     with pytest.raises(G.GrootError):                       # not uploaded
         G.groot_sage_layer_forward(plan, z(s.n, 64), z(64, 64), z(64, 64), None, True, z(s.n, 64), 64)
     G.groot_plan_upload(plan, 64)
-    with pytest.raises(G.GrootError):                       # only F = 64
+    with pytest.raises(G.GrootError):                       # explicit weights: only F = 64
         G.groot_sage_layer_forward(plan, z(s.n, 32), z(32, 32), z(32, 32), None, True, z(s.n, 32), 32)
+    with pytest.raises(G.GrootError):                       # never F = 16
+        G.groot_sage_layer_forward(plan, z(s.n, 16), z(16, 16), z(16, 16), None, True, z(s.n, 16), 16)
     x = z(s.n, 64)
     with pytest.raises(G.GrootError):                       # in place
         G.groot_sage_layer_forward(plan, x, z(64, 64), z(64, 64), None, True, x, 64)
