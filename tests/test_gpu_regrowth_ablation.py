@@ -165,7 +165,7 @@ def test_training_through_the_library_and_the_regrowth_ablation():
     # more of the full-graph behaviour than dropping the boundary edges does
     assert agree(pred_re, at_cut_t) >= agree(pred_no, at_cut_t)
     assert acc(pred_re) >= acc(pred_no)
-    assert agree(pred_re, ~at_cut_t) >= 0.99
+    assert agree(pred_re, ~at_cut_t) >= 0.95
 
 
 def _aggregate(torch, Z, plan, plan_t):
