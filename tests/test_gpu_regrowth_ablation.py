@@ -128,6 +128,22 @@ def test_training_through_the_library_and_the_regrowth_ablation():
         pred_full = model(Xb, plan_big).argmax(1)
     acc_full = float((pred_full == yb).float().mean())
 
+    # the two 32 -> 32 layers through the fused layer kernel give the same classification
+    with torch.no_grad():
+        h = Xb
+        agg = torch.empty_like(h)
+        G.groot_spmm_execute(plan_big, h, agg, 4)
+        h = torch.relu(agg @ model.wn[0] + h @ model.ws[0] + model.b[0]).contiguous()
+        for layer in (1, 2):
+            nxt = torch.empty_like(h)
+            G.groot_sage_layer_forward(plan_big, h, model.wn[layer].detach().contiguous(), model.ws[layer].detach().contiguous(),
+                                       model.b[layer].detach().contiguous(), True, nxt, HIDDEN)
+            h = nxt
+        logits_fused = model.out(h)
+        logits_full = model(Xb, plan_big)
+    assert float((logits_fused - logits_full).abs().max()) <= 1e-3 * float(logits_full.abs().max())
+    assert bool((logits_fused.argmax(1) == pred_full).all())
+
     P = 8
     vb = G.groot_graph_view(g_big)
     part_of = np.minimum(P - 1, (np.arange(n) * P) // n)
