@@ -38,6 +38,9 @@ WORKLOADS = {
     # shape of the 4-LUT-mapped carry-save multiplier (rows of 7 entries; adjacency only, via groot_graph_from_csr)
     "lut4csa512_b16_F32": (512, 16, 32, 5, 32),
     "lut4csa256_b16_F32": (256, 16, 32, 5, 32),
+    # shape of the standard-cell-mapped carry-save multiplier (AND2 rows of 4 entries, full-adder rows of 6)
+    "cellcsa512_b16_F32": (512, 16, 32, 6, 32),
+    "cellcsa1024_b16_F32": (1024, 16, 32, 6, 32),
 }
 
 
@@ -269,12 +272,12 @@ def main():
     bits, batch, F, seed, T = WORKLOADS[name]
 
     t0 = time.time()
-    lut = wl.lut4_csa_graph(bits, 1) if name.startswith("lut4") else None
-    if lut is not None:
+    shape_only = wl.lut4_csa_graph if name.startswith("lut4") else wl.cellmap_csa_graph if name.startswith("cell") else None
+    if shape_only is not None:
         if args.transposed or args.partitioned or args.sage_layer:
-            sys.exit("the LUT-shape workloads run the plain SpMM only")
+            sys.exit("the mapped-netlist shape workloads run the plain SpMM only")
         aig = None
-        g = G.groot_graph_from_csr(*(lambda b: (b.rowptr, b.col, b.val))(wl.lut4_csa_graph(bits, batch)))
+        g = G.groot_graph_from_csr(*(lambda b: (b.rowptr, b.col, b.val))(shape_only(bits, batch)))
     else:
         aig = wl.booth_multiplier_aig(bits) if name.startswith("booth") else wl.csa_multiplier_aig(bits)
         g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
@@ -353,6 +356,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
 
+        lut = shape_only(bits, 1) if shape_only is not None else None
         n1 = lut.n if lut is not None else aig.num_nodes
         if lut is not None:
             rp, col, val = lut.rowptr, lut.col, lut.val

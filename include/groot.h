@@ -127,6 +127,11 @@ groot_status groot_plan_view(const groot_plan *plan, int64_t *n_hd, int64_t *n_l
  * called once before groot_spmm_execute; max_F (multiple of 4 in [4,512]) is
  * the widest feature matrix the plan will be executed with and sizes the
  * scratch for split high-degree rows.  Calling it again re-uploads.
+ * For a graph from groot_graph_from_csr it also looks (one pass over the weights)
+ * whether they are bit for bit fl(1 / row length), or all 1; then the kernels
+ * recompute them from the row pointer like for a graph built from an AIG and do
+ * not read the weight array (results agree with the entry-by-entry form within
+ * rounding: the row sum is scaled once instead of every term).
  * Errors: EINVAL, EHIP, ENOMEM. */
 groot_status groot_plan_upload(groot_plan *plan, int32_t max_F);
 
@@ -314,24 +319,30 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
                                 float *Y_dev, int32_t F, void *hip_stream);
 
 /* What the library decided for an uploaded plan, for diagnostics and benchmarks:
- * "ld_pipelined" (0 the plain LD kernel always, 1 the pipelined one for F = 64
- * and 128, 2 also for F = 32), "hd_pieces" (launch size of the HD kernel),
- * "hd_partials" (partial-sum slots of split high-degree rows).
+ * "ld_pipelined" (0 the plain LD kernel always, 2 the pipelined one for F = 32,
+ * 64 and 128), "hd_pieces" (launch size of the HD kernel),
+ * "hd_partials" (partial-sum slots of split high-degree rows), "weight_mode"
+ * (how the kernels take the weights: 0 all 1, 1 fl(1 / row length) recomputed
+ * from the row pointer, 2 read from the weight array).
  * Errors: EINVAL (NULL, unknown name, plan not uploaded). */
 groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t *value);
 
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
  * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
- * 64..4096 non-zeros, read by groot_spmm_plan), "sage_kernel" (1, default: the fused
+ * 64..4096 non-zeros, read by groot_spmm_plan), "uniform_detect" (1, default:
+ * groot_plan_upload checks whether the weights of a graph from
+ * groot_graph_from_csr are bit for bit fl(1 / row length), or all 1, and then
+ * runs it like a graph built from an AIG, without reading the weight array; 0:
+ * never), "sage_kernel" (1, default: the fused
  * layer runs as self-contained wavefronts; 0: as producer and consumer
  * wavefronts; graphs with explicit weights always take the latter),
  * "sage_split" (kernel 0 only: 1 bf16 piece products, 0 fp32 matrix
  * instructions), "sage_gap" (kernel 0 only: 0..4, the pause between its matrix
  * instructions; all three read at each call of groot_sage_layer_forward)
  * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
- * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one for F = 64
- * and 128 when at least 99.9 % of the low-degree rows have at most 6 entries;
- * read by groot_plan_upload).
+ * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one when at
+ * most one low-degree row in 100,000 has more than 6 entries; read by
+ * groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

@@ -479,6 +479,20 @@ groot_status to_device(T **dst, const T *src, size_t count, const char *what)
 }
 }  // namespace
 
+namespace {
+// Which LD kernel an uploaded plan uses (DevicePlan::ld_pipelined): the pipelined one for F = 32, 64 and 128 when
+// practically all low-degree rows have at most 6 entries (n_short of n_ld; at most one in 100,000 longer).
+// Measured: carry-save multipliers and the cell-mapped shape (no longer rows at all) gain 4-11 % at every
+// width; Booth multipliers (0.012 % of the rows have 8 entries, and a tile with one of them is redone by the
+// plain loop after a drain of the pipeline) lose 2-10 %, so they stay with the plain kernel.
+int pipelined_by_default(int knob, int64_t n_ld, int64_t n_short)
+{
+    if (knob > 0) return 2;
+    if (knob == 0 || n_ld <= 0) return 0;
+    return (n_ld - n_short) * 100000 <= n_ld ? 2 : 0;
+}
+}  // namespace
+
 extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
 {
     if (!plan) return fail(GROOT_EINVAL, "groot_plan_upload: NULL plan");
@@ -494,8 +508,35 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
     d.nnz = g->nnz;
     d.threshold = plan->threshold;
     d.xcd_remap = tuning().xcd_remap;
-    d.weight_mode = (int)g->weight_mode;
+    d.weight_mode = d.graph_weight_mode = (int)g->weight_mode;
     const bool need_val = g->weight_mode == WeightMode::Explicit;   // row-uniform weights are recomputed on the device
+    if (need_val && tuning().uniform_detect && g->nnz > 0) {
+        // Weights given entry by entry are often the mean normalisation all the same (a mapped netlist that
+        // comes in as a CSR matrix): if every entry is bit for bit fl(1 / row length), or every entry is 1,
+        // the kernels recompute the weight from the row pointer and never read the array (4 bytes per entry),
+        // and the kernels for row-uniform weights apply.
+        std::atomic<bool> mean{true}, ones{true};
+        parallel_for(g->n, 1 << 16, [&](int64_t lo, int64_t hi) {
+            bool m = true, o = true;
+            for (int64_t i = lo; i < hi && (m || o); ++i) {
+                const int64_t b = g->rowptr[i], e = g->rowptr[i + 1];
+                const float w = e > b ? 1.0f / (float)(e - b) : 0.0f;
+                for (int64_t q = b; q < e; ++q) {
+                    uint32_t bits, want, one;
+                    const float f1 = 1.0f;
+                    std::memcpy(&bits, &g->val[q], 4);
+                    std::memcpy(&want, &w, 4);
+                    std::memcpy(&one, &f1, 4);
+                    m = m && bits == want;
+                    o = o && bits == one;
+                }
+            }
+            if (!m) mean = false;
+            if (!o) ones = false;
+        });
+        if (ones) d.weight_mode = (int)WeightMode::Ones;
+        else if (mean) d.weight_mode = (int)WeightMode::Mean;
+    }
     groot_status st;
     const std::vector<float> zeros(kZeroRowFloats + kTrashFloats, 0.0f);
     if ((st = to_device(&d.zero_row, zeros.data(), zeros.size(), "zero row")) != GROOT_OK ||
@@ -516,9 +557,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         const int32_t short_deg = std::min<int32_t>(7, plan->threshold);
         const int64_t n_short = plan->ld_deg_offsets.empty() ? 0 : plan->ld_deg_offsets[short_deg];
         const int knob = tuning().ld_pipeline;
-        // (a tile with one longer row is redone by the plain loop after a drain of the pipeline: with 0.55 % of
-        // such rows, the Booth multipliers, the pipelined kernel measured 11 % slower than the plain one)
-        d.ld_pipelined = knob > 0 ? 2 : (knob < 0 && n_ld > 0 && n_short * 1000 >= n_ld * 999) ? 1 : 0;
+        d.ld_pipelined = pipelined_by_default(knob, n_ld, n_short);
     }
     d.n_chunks = (int64_t)plan->chunks.size();
     d.n_tiles = (g->n + kRowsPerLdTile - 1) / kRowsPerLdTile;
@@ -825,7 +864,7 @@ extern "C" groot_status groot_partition_regrow_device(const groot_plan *plan, in
     if (flags & ~GROOT_REGROW) return fail(GROOT_EINVAL, "groot_partition_regrow_device: unknown flag bits");
     std::unique_ptr<groot_dev_part> part(new (std::nothrow) groot_dev_part);
     if (!part) return fail(GROOT_ENOMEM, "groot_partition_regrow_device: out of host memory");
-    part->weight_mode = (WeightMode)plan->dev.weight_mode;
+    part->weight_mode = (WeightMode)plan->dev.graph_weight_mode;
     const int64_t n1 = plan->g ? plan->g->n1 : n;
     int err = launch_regrow_device(plan->dev, n1, num_parts, part_of_dev, p, (flags & GROOT_REGROW) ? 1 : 0, hip_stream,
                                    &part->d);
@@ -962,7 +1001,7 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
         d.nnz = part->d.nnz;
         d.threshold = T;
         d.xcd_remap = tuning().xcd_remap;
-        d.weight_mode = (int)part->weight_mode;
+        d.weight_mode = d.graph_weight_mode = (int)part->weight_mode;
         d.n_tiles = (n + kRowsPerLdTile - 1) / kRowsPerLdTile;
         d.n_chunks = (int64_t)pl->chunks.size();
         d.n_split_rows = (int64_t)pl->split_rows.size();
@@ -970,7 +1009,7 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
         {
             const int64_t n_short = offs[std::min<int32_t>(7, T)];
             const int knob = tuning().ld_pipeline;
-            d.ld_pipelined = knob > 0 ? 2 : (knob < 0 && n_ld > 0 && n_short * 1000 >= n_ld * 999) ? 1 : 0;
+            d.ld_pipelined = pipelined_by_default(knob, n_ld, n_short);
         }
         // the sub-graph moves into the plan
         d.rowptr = part->d.rowptr;
@@ -1026,6 +1065,7 @@ extern "C" groot_status groot_plan_query(const groot_plan *plan, const char *wha
     if (!plan->resident) return fail(GROOT_EINVAL, "groot_plan_query: plan is not on the device (call groot_plan_upload)");
     const std::string k(what);
     if (k == "ld_pipelined") *value = plan->dev.ld_pipelined;
+    else if (k == "weight_mode") *value = plan->dev.weight_mode;
     else if (k == "hd_pieces") *value = plan->dev.n_chunks;
     else if (k == "hd_partials") *value = plan->dev.n_partials;
     else return fail(GROOT_EINVAL, "groot_plan_query: unknown name '" + k + "'");
@@ -1042,9 +1082,9 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
         tuning().ld_pipeline = (int)value;
         return GROOT_OK;
     }
-    if (k == "sage_split" || k == "sage_kernel") {
+    if (k == "sage_split" || k == "sage_kernel" || k == "uniform_detect") {
         if (value < 0 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: " + k + " must be 0 or 1");
-        (k == "sage_split" ? tuning().sage_split : tuning().sage_kernel) = (int)value;
+        (k == "sage_split" ? tuning().sage_split : k == "sage_kernel" ? tuning().sage_kernel : tuning().uniform_detect) = (int)value;
         return GROOT_OK;
     }
     if (k == "sage_gap") {

@@ -39,6 +39,7 @@ struct Tuning {
     int sage_gap = 2;               // pacing of the fused layer's matrix wavefronts, see launch_sage
     int sage_split = 1;             // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
     int sage_kernel = 1;            // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
+    int uniform_detect = 1;         // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
     int ld_pipeline = -1;           // pipelined LD kernel: 1 always (where it applies), 0 never, -1 when the rows are short
 };
 Tuning &tuning();
@@ -50,7 +51,9 @@ struct DevicePlan {
     int64_t *rowptr = nullptr;
     int32_t *col = nullptr;
     float *val = nullptr;
-    int weight_mode = 0;            // WeightMode; val is NULL unless Explicit
+    int weight_mode = 0;            // WeightMode the kernels run in; explicit weights that turn out to be 1/row length
+                                    // (or all 1) run as row-uniform weights and their array is not read
+    int graph_weight_mode = 0;      // WeightMode of the graph itself; val is NULL unless this is Explicit
     int64_t n_tiles = 0;            // LD tiles of kRowsPerLdTile rows
     HdChunk *chunks = nullptr;
     int64_t n_chunks = 0;

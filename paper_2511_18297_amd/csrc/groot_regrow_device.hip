@@ -531,7 +531,7 @@ int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int3
     if (n < 1 || n > 0x7fffffffLL || n1 < 1 || n1 > n || P < 1 || p < 0 || p >= P) return (int)hipErrorInvalidValue;
     // slice of the built-in rule: ceil(p n1 / P) .. ceil((p + 1) n1 / P), exact in 64 bits (n1, P < 2^31)
     const uint32_t lo = (uint32_t)(((int64_t)p * n1 + P - 1) / P), hi = (uint32_t)(((int64_t)(p + 1) * n1 + P - 1) / P);
-    RgGraph g{dp.rowptr, dp.col, dp.weight_mode == kExplicit ? dp.val : nullptr, n, n1, part_of_dev, p, lo, hi};
+    RgGraph g{dp.rowptr, dp.col, dp.graph_weight_mode == kExplicit ? dp.val : nullptr, n, n1, part_of_dev, p, lo, hi};
     const int64_t n_blocks = (n + kRgRowsPerBlock - 1) / kRgRowsPerBlock;
 
     Scratch scratch;

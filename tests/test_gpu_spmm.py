@@ -73,7 +73,7 @@ def test_booth_multiplier_degree_profile(torch_cuda, n_bits, batch, F, T):
 
 
 @pytest.mark.parametrize("n_bits,batch,F,T", [(48, 2, 32, 32), (32, 1, 64, 8), (24, 3, 128, 7)])
-def test_lut4_mapped_multiplier_shape(torch_cuda, n_bits, batch, F, T):
+def test_lut4_mapped_multiplier_shape(torch_cuda, uniform_detect, n_bits, batch, F, T):
     """4-LUT-mapped carry-save array: interior rows of 7 entries (longer than the pipelined kernel's 6
     slots: there they go through its plain loop), 2n rows of 2n+1; T = 7 makes almost every row high-degree."""
     s = wl.lut4_csa_graph(n_bits, batch)
@@ -82,6 +82,18 @@ def test_lut4_mapped_multiplier_shape(torch_cuda, n_bits, batch, F, T):
     Y, plan, _, _ = _run(torch_cuda, g, T, X)
     Y64, S = oracle.spmm_f64(s.rowptr, s.col, s.val, X)
     assert_close_to_oracle(Y, Y64, S, f"lut4 {n_bits}x{batch} F={F} T={T}")
+
+
+@pytest.mark.parametrize("n_bits,batch,F,T", [(48, 2, 32, 32), (40, 1, 64, 16), (24, 3, 128, 5)])
+def test_cell_mapped_multiplier_shape(torch_cuda, uniform_detect, n_bits, batch, F, T):
+    """Standard-cell-mapped carry-save array: AND2 rows of 4 entries, adder rows of 6 (all within the
+    pipelined kernel's slots), 2n rows of n+1; T = 5 makes every adder row high-degree."""
+    s = wl.cellmap_csa_graph(n_bits, batch)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    X = wl.uniform_features_numpy(70 + n_bits, 0, s.n, F)
+    Y, plan, _, _ = _run(torch_cuda, g, T, X)
+    Y64, S = oracle.spmm_f64(s.rowptr, s.col, s.val, X)
+    assert_close_to_oracle(Y, Y64, S, f"cells {n_bits}x{batch} F={F} T={T}")
 
 
 def test_config1_32bit_structural_features(torch_cuda):
@@ -164,7 +176,7 @@ def test_tiny_graphs(torch_cuda):
 
 
 @pytest.mark.parametrize("T", [16, 32, 64, 128])
-def test_stress_graph_threshold_sweep(torch_cuda, T):
+def test_stress_graph_threshold_sweep(torch_cuda, uniform_detect, T):
     """Polarized degrees (scaled-down law of the 16M-row stress workload): rows
     of up to 16,385 non-zeros are split over several workgroups."""
     s = wl.stress_graph(4, 1 << 16, window=4096, dmin=64, dmax=16384)
@@ -172,6 +184,7 @@ def test_stress_graph_threshold_sweep(torch_cuda, T):
     X = wl.uniform_features_numpy(4, 0, s.n, 128)
     Y, plan, _, _ = _run(torch_cuda, g, T, X)
     deg = np.diff(s.rowptr)
+    assert G.groot_plan_query(plan, "weight_mode") == (1 if uniform_detect else 2)
     assert G.groot_plan_view(plan)["n_hd"] == int((deg >= T).sum())
     Y64, S = oracle.spmm_f64(s.rowptr, s.col, s.val, X)
     assert_close_to_oracle(Y, Y64, S, f"stress T={T}")
@@ -193,6 +206,15 @@ def test_transposed_spmm(torch_cuda, case):
     dX, _, _, _ = _run(torch_cuda, gt, T, dY)
     want, S = oracle.spmm_t_f64(rowptr, col, val, dY)
     assert_close_to_oracle(dX, want, S, f"transposed {case}")
+
+
+@pytest.fixture(params=[1, 0], ids=["detect-uniform", "as-given"])
+def uniform_detect(request):
+    """Graphs given as CSR with weights 1/row length run as row-uniform weights (the weight array is not read)
+    when groot_plan_upload detects that, and entry by entry when it is told not to look: both must be right."""
+    G.groot_set_tuning("uniform_detect", request.param)
+    yield request.param
+    G.groot_set_tuning("uniform_detect", 1)
 
 
 SAGE_VARIANTS = {"wavefronts": dict(sage_kernel=1), "roles-bf16": dict(sage_kernel=0, sage_split=1),
@@ -306,9 +328,20 @@ def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):
     assert np.isfinite(err).all() and (err <= tol).all(), f"max err/tol {np.max(err / np.maximum(tol, 1e-300))}"
 
 
+def test_fused_sage_layer_on_csr_graph_with_mean_weights(torch_cuda, uniform_detect):
+    """A graph given as CSR whose weights are 1/row length: with the detection the layer runs as self-contained
+    wavefronts (rows of up to 2,048 entries take its plain path), without it as the kernel for explicit weights."""
+    s = wl.stress_graph(12, 1 << 14, window=512, dmin=64, dmax=2048)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    _sage_check(torch_cuda, g, s.rowptr, s.col, s.val, 32, s.n, 6, True, True, "sage csr mean")
+    if uniform_detect:
+        _sage_check(torch_cuda, g, s.rowptr, s.col, s.val, 32, s.n, 7, False, False, "sage csr mean F=32", F=32)
+
+
 def test_fused_sage_layer_explicit_weights_and_errors(torch_cuda, sage_variant):
     torch = torch_cuda
     s = wl.stress_graph(11, 1 << 14, window=512, dmin=64, dmax=2048)
+    s.val[:] = np.random.default_rng(3).uniform(0.01, 0.5, s.val.shape[0]).astype(np.float32)   # not 1 / row length
     g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
     _sage_check(torch, g, s.rowptr, s.col, s.val, 32, s.n, 5, True, True, "sage stress")
     plan = G.groot_spmm_plan(g, 32)

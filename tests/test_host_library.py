@@ -232,7 +232,7 @@ def test_partition_and_misc_error_paths():
         G.groot_set_tuning("hd_chunk", 7)
     G.groot_set_tuning("hd_chunk", 512)
     for knob, bad, good in (("ld_pipeline", 2, -1), ("ld_pipeline", -2, -1), ("sage_gap", 5, 2), ("sage_gap", -1, 2),
-                            ("sage_kernel", 2, 1), ("sage_split", -1, 1)):
+                            ("sage_kernel", 2, 1), ("sage_split", -1, 1), ("uniform_detect", 2, 1)):
         with pytest.raises(G.GrootError):
             G.groot_set_tuning(knob, bad)
         G.groot_set_tuning(knob, good)

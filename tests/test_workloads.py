@@ -274,3 +274,29 @@ def test_lut4_graph_shape(n, batch):
     if n >= 5:
         assert np.bincount(deg).argmax() == 7
     assert np.array_equal(deg[:n1], deg[n1 * (batch - 1):])             # same profile in every copy
+
+
+@pytest.mark.parametrize("n,batch", [(2, 1), (5, 3), (32, 2)])
+def test_cellmap_graph_shape(n, batch):
+    """Standard-cell-mapped shape: symmetric, self-loops, sorted rows, mean weights bit-exact, block-diagonal
+    copies, and the documented degree profile (2n input rows of n+1 entries, AND2 rows of 4, adder rows of
+    at most 6)."""
+    g = wl.cellmap_csa_graph(n, batch)
+    n1 = g.n // batch
+    assert n1 == 2 * n + 2 * n * n + n + 2 * n
+    rows = np.repeat(np.arange(g.n), np.diff(g.rowptr))
+    pairs = set(zip(rows.tolist(), g.col.tolist()))
+    assert all((c, r) in pairs for r, c in pairs)
+    assert all((v, v) in pairs for v in range(g.n))
+    assert all(r // n1 == c // n1 for r, c in pairs)
+    for v in range(g.n):
+        seg = g.col[g.rowptr[v]:g.rowptr[v + 1]]
+        assert (np.diff(seg) > 0).all()
+    deg = np.diff(g.rowptr)
+    want = (np.float32(1.0) / deg.astype(np.float32)).astype(np.float32)
+    assert np.array_equal(g.val.view(np.uint32), np.repeat(want, deg).view(np.uint32))
+    assert (deg[:2 * n] == n + 1).all()                                 # every input feeds n AND2 cells
+    and2 = 2 * n + 2 * np.arange(n * n)
+    assert (deg[and2] == 4).all()                                       # two inputs, its adder, itself
+    assert deg[2 * n:n1].max() <= 6
+    assert np.array_equal(deg[:n1], deg[n1 * (batch - 1):])

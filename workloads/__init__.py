@@ -325,6 +325,14 @@ def lut4_csa_graph(n_bits: int, batch: int = 1) -> Csr:
     edges(s_id[:, 0], po0 + np.arange(n))                             # low product bits leave the array's first column
     edges(add0 + 2 * k, po0 + n + k)
     n1 = po0 + 2 * n
+    return _symmetric_mean_csr(src, dst, int(n1), batch)
+
+
+def _symmetric_mean_csr(src, dst, n1: int, batch: int) -> Csr:
+    """Directed edge lists -> symmetric adjacency with self-loops, mean-normalised (weights fl(1/row length)),
+    replicated block-diagonally `batch` times."""
+    import scipy.sparse as sp
+
     src = np.concatenate(src).astype(np.int64)
     dst = np.concatenate(dst).astype(np.int64)
     ones = np.ones(src.shape[0], dtype=np.int8)
@@ -340,3 +348,49 @@ def lut4_csa_graph(n_bits: int, batch: int = 1) -> Csr:
     col = np.concatenate([col1 + c * n1 for c in range(batch)]).astype(np.int32)
     val = np.tile(val1, batch)
     return Csr(int(n1) * batch, rowptr, col, val)
+
+
+def cellmap_csa_graph(n_bits: int, batch: int = 1) -> Csr:
+    """Shape of a carry-save array multiplier after mapping to standard cells (stand-in for the paper's
+    technology-mapped dataset, which needs ABC and a cell library): every array cell (i, j) becomes an AND2
+    cell (fanins a_j, b_i) and a full-adder cell (fanins: that AND2, the adder of cell (i-1, j+1) for its sum
+    and the adder of cell (i-1, j) for its carry, those that exist); a last row of n full adders forms the
+    ripple adder; 2n primary outputs have one fanin each.  A cell is one node whatever its number of output
+    pins; no logic is modelled, only the adjacency.  Node order: a_0.., b_0.., cells row by row (AND2, adder
+    interleaved), adder row, outputs.  Symmetric, self-loops, mean-normalised, `batch` copies.
+    Degree profile: 2n primary-input rows of n+1 entries (the high-degree class); AND2 rows of 4 entries;
+    interior adder rows of 6 (3 fanins, 2 fanouts, itself): half as many nodes per multiplier bit as the AIG."""
+    n = n_bits
+    if n < 2 or n > 2048 or batch < 1:
+        raise ValueError("bad cell graph parameters")
+    a = np.arange(n)
+    b = n + np.arange(n)
+    cell0 = 2 * n
+    i, j = np.meshgrid(np.arange(n), np.arange(n), indexing="ij")
+    and_id = cell0 + 2 * (i * n + j)
+    fa_id = and_id + 1
+    src, dst = [], []
+
+    def edges(frm, to, mask=None):
+        frm, to = np.broadcast_arrays(frm, to)
+        if mask is not None:
+            frm, to = frm[mask], to[mask]
+        src.append(np.asarray(frm).ravel())
+        dst.append(np.asarray(to).ravel())
+
+    edges(a[j], and_id)
+    edges(b[i], and_id)
+    edges(and_id, fa_id)
+    up = (i > 0) & (j + 1 < n)
+    edges(np.where(up, fa_id - 2 * n + 2, 0), fa_id, up)               # sum of cell (i-1, j+1)
+    edges(np.where(i > 0, fa_id - 2 * n, 0), fa_id, i > 0)             # carry of cell (i-1, j)
+    add0 = cell0 + 2 * n * n
+    k = np.arange(n)
+    edges(np.where(k + 1 < n, fa_id[n - 1, np.minimum(k + 1, n - 1)], 0), add0 + k, k + 1 < n)
+    edges(fa_id[n - 1, k], add0 + k)
+    edges(np.where(k > 0, add0 + k - 1, 0), add0 + k, k > 0)
+    po0 = add0 + n
+    edges(fa_id[:, 0], po0 + np.arange(n))                              # low product bits leave the array's first column
+    edges(add0 + k, po0 + n + k)
+    n1 = po0 + 2 * n
+    return _symmetric_mean_csr(src, dst, int(n1), batch)
