@@ -206,8 +206,11 @@ def dense_adjacency(rowptr, col, val):
 
 
 def sage_layer_f64(rowptr, col, val, X, Wn, Ws, b, relu):
-    """One GraphSAGE-mean layer in fp64: act((A_hat X) Wn + X Ws + b); also returns A_hat X and its
-    sum of absolute terms (for the error scale)."""
+    """One GraphSAGE-mean layer in fp64 (Section "GNN and Edge Re-growth After Partition": the layer
+    aggregates the neighbours' features, then transforms): act((A_hat X) Wn + X Ws + b), act = ReLU applied
+    after the bias, or the identity; also returns A_hat X and its sum of absolute terms (for the error
+    scale).  Pinned by the dense layer on the 18- and 51-node multipliers, the Wn = I / Ws = I reductions
+    and a closed-form case where ReLU clips."""
     A, S = spmm_f64(rowptr, col, val, X)
     H = A @ Wn.astype(np.float64) + np.asarray(X, dtype=np.float64) @ Ws.astype(np.float64)
     if b is not None:
@@ -220,9 +223,9 @@ def sage_forward_f64(rowptr, col, val, X, W1n, W1s, b1, W2n, W2s, b2):
     Partition": the layer aggregates neighbour features, then transforms):
         H1 = relu((A_hat X) W1n + X W1s + b1),  H2 = (A_hat H1) W2n + H1 W2s + b2.
     The aggregation input of layer 2 is H1 rounded to fp32, as the library
-    receives it.  Parity of the layer composition itself is unpinned (the paper
-    gives no hyper-parameters); it composes the pinned SpMM with dense fp64
-    products."""
+    receives it.  The paper gives no hyper-parameters (width, depth, where the
+    activation sits): those are this build's reading; the arithmetic is pinned
+    as two applications of the pinned layer."""
     X64 = np.asarray(X, dtype=np.float64)
     A1, _ = spmm_f64(rowptr, col, val, X, want_abs=False)
     H1 = np.maximum(A1 @ W1n.astype(np.float64) + X64 @ W1s.astype(np.float64) + b1.astype(np.float64), 0.0)

@@ -336,6 +336,82 @@ def test_sage_forward_reduces_to_spmm():
     assert np.array_equal(H1s, X) and np.allclose(H2s, X.astype(np.float64) + 1)
 
 
+def _layer_inputs(n, F, seed):
+    aig, (rowptr, col, val, pol) = _csr(n)
+    N = aig.num_nodes
+    A = _dense_from_aig(aig)
+    A_hat = (np.float32(1.0) / A.sum(axis=1).astype(np.float32)).astype(np.float64)[:, None] * A
+    X = wl.uniform_features_numpy(seed, 0, N, F)
+    Wn = wl.uniform_features_numpy(seed + 1, 0, F, F) * np.float32(0.125)
+    Ws = wl.uniform_features_numpy(seed + 2, 0, F, F) * np.float32(0.125)
+    b = wl.uniform_features_numpy(seed + 3, 0, 1, F)[0] * np.float32(0.125)
+    return (rowptr, col, val), A_hat, X, Wn, Ws, b
+
+
+@pytest.mark.parametrize("n", [2, 3])
+def test_sage_layer_equals_dense_layer(n):
+    """Section "GNN and Edge Re-growth After Partition": a GraphSAGE-mean layer aggregates, then transforms.
+    On the 18- and 51-node multipliers the layer is checked against the dense adjacency written from the
+    fanin records, with the products associated the other way round (A_hat (X Wn) instead of (A_hat X) Wn),
+    element by element in explicit loops for the 18-node case."""
+    csr, A_hat, X, Wn, Ws, b, = _layer_inputs(n, 8, 41)
+    X64, Wn64, Ws64, b64 = (np.asarray(a, dtype=np.float64) for a in (X, Wn, Ws, b))
+    pre = A_hat @ (X64 @ Wn64) + X64 @ Ws64 + b64
+    assert (pre < -1e-3).any() and (pre > 1e-3).any()          # ReLU has something to clip and something to keep
+    for relu in (False, True):
+        H, A, S = oracle.sage_layer_f64(*csr, X, Wn, Ws, b, relu)
+        want = np.maximum(pre, 0.0) if relu else pre
+        assert np.allclose(H, want, rtol=0, atol=1e-14)
+        assert np.allclose(A, A_hat @ X64, rtol=0, atol=1e-15)
+        assert np.allclose(S, A_hat @ np.abs(X64), rtol=0, atol=1e-15)
+    H0, _, _ = oracle.sage_layer_f64(*csr, X, Wn, Ws, None, False)            # bias off = bias of zeros
+    assert np.allclose(H0, pre - b64, rtol=0, atol=1e-14)
+    if n == 2:
+        N, F = X.shape
+        H, _, _ = oracle.sage_layer_f64(*csr, X, Wn, Ws, b, True)
+        for i in range(N):
+            for o in range(F):
+                acc = float(b[o])
+                for k in range(F):
+                    acc += sum(A_hat[i, j] * float(X[j, k]) for j in range(N)) * float(Wn[k, o])
+                    acc += float(X[i, k]) * float(Ws[k, o])
+                assert abs(H[i, o] - max(acc, 0.0)) <= 1e-14
+
+
+def test_sage_layer_special_cases():
+    """Wn = I, Ws = 0: the layer is the aggregation; Wn = 0, Ws = I: the layer is the identity on X (the self
+    term); X = 1 with Wn = -I, Ws = I/4 and a bias that alternates between 1 and 1/2: every row aggregates to
+    1 (row weights sum to 1 within 2^-23), so the layer gives 1/4 and -1/4, and ReLU, which acts after the
+    bias, turns the second into exactly 0."""
+    csr, A_hat, X, _, _, b = _layer_inputs(3, 6, 51)
+    F = X.shape[1]
+    I, Z = np.eye(F, dtype=np.float32), np.zeros((F, F), dtype=np.float32)
+    Y, S = oracle.spmm_f64(*csr, X)
+    H, A, S2 = oracle.sage_layer_f64(*csr, X, I, Z, None, False)
+    assert np.array_equal(H, Y) and np.array_equal(A, Y) and np.array_equal(S2, S)
+    H, _, _ = oracle.sage_layer_f64(*csr, X, Z, I, None, False)
+    assert np.array_equal(H, X.astype(np.float64))
+    H, _, _ = oracle.sage_layer_f64(*csr, X, Z, I, b, False)
+    assert np.array_equal(H, X.astype(np.float64) + b.astype(np.float64))
+    ones = np.ones_like(X)
+    alt = np.where(np.arange(F) % 2 == 0, 1.0, 0.5).astype(np.float32)
+    H, _, _ = oracle.sage_layer_f64(*csr, ones, -I, np.float32(0.25) * I, alt, False)
+    assert np.allclose(H, np.where(np.arange(F) % 2 == 0, 0.25, -0.25)[None, :], rtol=0, atol=2e-7)
+    H, _, _ = oracle.sage_layer_f64(*csr, ones, -I, np.float32(0.25) * I, alt, True)
+    assert np.allclose(H[:, 0::2], 0.25, rtol=0, atol=2e-7) and (H[:, 1::2] == 0.0).all()
+
+
+def test_sage_forward_is_two_layers():
+    """The two-layer forward is the layer applied twice: ReLU and rounding to fp32 between the layers, none after."""
+    csr, _, X, W1n, W1s, b1 = _layer_inputs(4, 8, 61)
+    _, _, _, W2n, W2s, b2 = _layer_inputs(4, 8, 71)
+    H1, H2 = oracle.sage_forward_f64(*csr, X, W1n, W1s, b1, W2n, W2s, b2)
+    L1, _, _ = oracle.sage_layer_f64(*csr, X, W1n, W1s, b1, True)
+    assert H1.dtype == np.float32 and np.array_equal(H1, L1.astype(np.float32))
+    L2, _, _ = oracle.sage_layer_f64(*csr, H1, W2n, W2s, b2, False)
+    assert np.allclose(H2, L2, rtol=0, atol=1e-14) and (H2 < 0).any()
+
+
 # ---------------------------------------------------------- transposed SpMM
 @pytest.mark.parametrize("n,flags", [(2, 7), (3, 7), (3, 0), (3, 4)])
 def test_transposed_spmm_equals_dense_transpose(n, flags):

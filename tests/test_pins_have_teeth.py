@@ -1,8 +1,10 @@
 """The pins must be able to fail: plausible mistakes are planted in a COPY of the
 oracle source (a dropped term, a wrong sign, index, comparison or operand), the
-copy is compiled on the CPU, and the pin tests are re-run against it -- at
-least one pin has to object to every planted mistake."""
+copy is compiled on the CPU (or, for the oracle's numpy functions, executed in
+place of the function), and the pin tests are re-run against it -- at least one
+pin has to object to every planted mistake."""
 import ctypes
+import inspect
 import os
 import subprocess
 
@@ -55,7 +57,44 @@ PIN_CALLS = [
     lambda: pins.test_transposed_spmm_adjoint_identity(),
     lambda: wpins.test_two_bit_example_matches_paper(),
     lambda: wpins.test_multiplier_function_equals_integer_product(5),
+    lambda: [pins.test_sage_layer_equals_dense_layer(n) for n in (2, 3)],
+    lambda: pins.test_sage_layer_special_cases(),
+    lambda: pins.test_sage_forward_is_two_layers(),
+    lambda: pins.test_sage_forward_reduces_to_spmm(),
 ]
+
+# mistakes planted in the oracle's numpy functions: (what, function, text, replacement)
+PY_MUTATIONS = [
+    ("layer: self term dropped", "sage_layer_f64", " + np.asarray(X, dtype=np.float64) @ Ws.astype(np.float64)", ""),
+    ("layer: ReLU before the bias", "sage_layer_f64",
+     "    if b is not None:\n        H = H + b.astype(np.float64)\n",
+     "    if relu:\n        H = np.maximum(H, 0.0)\n    if b is not None:\n        H = H + b.astype(np.float64)\n"),
+    ("layer: neighbour and self weights swapped", "sage_layer_f64",
+     "A @ Wn.astype(np.float64) + np.asarray(X, dtype=np.float64) @ Ws.astype(np.float64)",
+     "A @ Ws.astype(np.float64) + np.asarray(X, dtype=np.float64) @ Wn.astype(np.float64)"),
+    ("layer: weight matrix transposed", "sage_layer_f64", "A @ Wn.astype(np.float64)", "A @ Wn.astype(np.float64).T"),
+    ("layer: bias subtracted", "sage_layer_f64", "H = H + b.astype(np.float64)", "H = H - b.astype(np.float64)"),
+    ("forward: no ReLU between the layers", "sage_forward_f64",
+     "H1 = np.maximum(A1 @ W1n.astype(np.float64) + X64 @ W1s.astype(np.float64) + b1.astype(np.float64), 0.0)",
+     "H1 = A1 @ W1n.astype(np.float64) + X64 @ W1s.astype(np.float64) + b1.astype(np.float64)"),
+    ("forward: second layer aggregates the input again", "sage_forward_f64",
+     "A2, _ = spmm_f64(rowptr, col, val, H1f, want_abs=False)", "A2, _ = spmm_f64(rowptr, col, val, X, want_abs=False)"),
+]
+
+
+ORACLE_SYMBOLS = ("orc_aig_simulate", "orc_csr_nnz", "orc_csr_build", "orc_spmm_f64", "orc_plan",
+                  "orc_part_of_default", "orc_regrow_sizes", "orc_regrow_fill", "orc_spmm_t_f64", "orc_csr_transpose")
+
+
+def test_symbol_list_covers_the_oracle_library():
+    """Every function the oracle's C source exports gets its argument types copied onto a mutant."""
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "groot_oracle.c")).read()
+    import re
+    exported = set(re.findall(r"^(?:int32_t|void|int64_t|double)\s+(orc_\w+)\s*\(", src, flags=re.M))
+    assert exported == set(ORACLE_SYMBOLS), exported ^ set(ORACLE_SYMBOLS)
+    good = oracle._load()
+    for name in ORACLE_SYMBOLS:
+        assert getattr(good, name).argtypes is not None, name
 
 
 def _build_mutant(tmp_path, idx, old, new):
@@ -74,11 +113,27 @@ def test_every_planted_mistake_is_caught(idx, tmp_path, monkeypatch):
     what, old, new = MUTATIONS[idx]
     mutant = ctypes.CDLL(_build_mutant(tmp_path, idx, old, new))
     good = oracle._load()
-    for name in ("orc_aig_simulate", "orc_csr_nnz", "orc_csr_build", "orc_spmm_f64", "orc_plan",
-                 "orc_part_of_default", "orc_regrow_sizes", "orc_regrow_fill"):
+    for name in ORACLE_SYMBOLS:
         getattr(mutant, name).restype = getattr(good, name).restype
         getattr(mutant, name).argtypes = getattr(good, name).argtypes
     monkeypatch.setattr(oracle, "_lib", mutant)
+    caught = 0
+    for call in PIN_CALLS:
+        try:
+            call()
+        except (AssertionError, ValueError, IndexError):
+            caught += 1
+    assert caught > 0, f"no pin noticed: {what}"
+
+
+@pytest.mark.parametrize("idx", range(len(PY_MUTATIONS)))
+def test_every_planted_mistake_in_the_numpy_functions_is_caught(idx, monkeypatch):
+    what, fn, old, new = PY_MUTATIONS[idx]
+    src = inspect.getsource(getattr(oracle, fn))
+    assert src.count(old) == 1, f"mutation {idx}: pattern must occur exactly once"
+    scope = dict(vars(oracle))
+    exec(compile(src.replace(old, new), f"<mutant of {fn}>", "exec"), scope)
+    monkeypatch.setattr(oracle, fn, scope[fn])
     caught = 0
     for call in PIN_CALLS:
         try:
