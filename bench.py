@@ -41,18 +41,61 @@ WORKLOADS = {
     # shape of the standard-cell-mapped carry-save multiplier (AND2 rows of 4 entries, full-adder rows of 6)
     "cellcsa512_b16_F32": (512, 16, 32, 6, 32),
     "cellcsa1024_b16_F32": (1024, 16, 32, 6, 32),
+    # polarized stress graph: 2^24 rows, 1 % heavy rows of 64..262,144 entries (Zipf 1.2), F = 128, thresholds swept
+    # (first field: log2 of the row count; batch field unused)
+    "stress16m_F128": (24, 1, 128, 4, 32),
+    "stress1m_F128": (20, 1, 128, 4, 32),
 }
+STRESS_THRESHOLDS = (16, 32, 64, 128)
 
 
-# HBM-side traffic of one launch of the LD kernel in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs
-# (see profiles/); filled in per workload and kernel once measured, None otherwise.
-TRAFFIC = {("csa1024_b16_F64", "ld_pipe_kernel"): 83.91e9,   # 49.59 GB read + 34.32 GB written
-           ("csa1024_b16_F64", "ld_kernel"): 80.52e9}        # 46.20 GB read + 34.32 GB written
+# HBM-side traffic of one launch of the LD kernel in bytes, from rocprofv3 FETCH_SIZE + WRITE_SIZE runs (the
+# summaries under profiles/ give the commands and the scaling against a copy of known size).  Each entry is
+# stamped with the hash of the kernel sources it was measured on (kernel_sources_sha16 below): when the
+# sources have changed since, the figure no longer describes the kernel that is timed and the line reports
+# traffic null instead.
+TRAFFIC = {
+    ("csa1024_b16_F64", "ld_pipe_kernel"): {"bytes": 83.91e9, "read": 49.59e9, "written": 34.32e9,
+                                            "sources_sha16": "unstamped (measured before stamping was introduced)"},
+    ("csa1024_b16_F64", "ld_kernel"): {"bytes": 80.52e9, "read": 46.20e9, "written": 34.32e9,
+                                       "sources_sha16": "unstamped (measured before stamping was introduced)"},
+}
+KERNEL_SOURCES = ("groot_device.h", "groot_internal.h", "groot_kernels.hip", "groot_ld_pipe.hip")
+
+
+def kernel_sources_sha16():
+    """Hash of the sources of the aggregation kernels (the files a traffic measurement depends on)."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2511_18297_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kernel):
+    """-> (bytes or None, note)"""
+    entry = TRAFFIC.get((workload, kernel))
+    if entry is None:
+        return None, "no counter run recorded for this workload and kernel"
+    now = kernel_sources_sha16()
+    if entry["sources_sha16"] != now:
+        return None, f"counter run was made on kernel sources {entry['sources_sha16']}, the timed ones are {now}"
+    return entry["bytes"], f"FETCH_SIZE + WRITE_SIZE on kernel sources {now}"
 
 
 def algorithmic_bytes(n, nnz, F):
-    """row pointers + column indices + weights + X read once + Y written once"""
+    """The per-step byte count by definition: row pointers (int64) + column indices + weights + X read once +
+    Y written once."""
     return 8 * (n + 1) + 4 * nnz + 4 * nnz + 4 * n * F + 4 * n * F
+
+
+def bytes_needed(csr_bytes, n_in, n_out, F):
+    """What a launch has to move at least, given the data structures the kernels really read: the device CSR as
+    the library keeps it (groot_plan_query "csr_bytes": no weight array when the weights are row-uniform,
+    compressed arrays where the library compresses) + the feature rows read once + the result rows written once."""
+    return csr_bytes + 4 * n_in * F + 4 * n_out * F
 
 
 def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props):
@@ -139,15 +182,32 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
     worst_dev = 0.0
     for lo in range(0, n, 1 << 24):
         worst_dev = max(worst_dev, float((Yout[lo:lo + (1 << 24)] - Y[lo:lo + (1 << 24)]).abs().max()))
+    # the same device-built plans with their columns renamed to global rows: no gather, X read in place
+    for plan, ids, n_owned, n_loc in items:
+        G.groot_plan_use_global_columns(plan, ids, n)
+    torch.cuda.synchronize()
+
+    def one_pass_in_place():
+        for plan, ids, n_owned, n_loc in items:
+            G.groot_spmm_execute_rows(plan, X, Yout, F, n_owned, ids)
+
+    Yout.fill_(float("nan"))
+    ms_in_place = timed(one_pass_in_place)
+    worst_in_place = 0.0
+    for lo in range(0, n, 1 << 24):
+        worst_in_place = max(worst_in_place, float((Yout[lo:lo + (1 << 24)] - Y[lo:lo + (1 << 24)]).abs().max()))
     full_foot = 8 * (n + 1) + 4 * nnz + 2 * 4 * n * F
     undirected = (nnz - n) // 2
     print(json.dumps({
-        "metric": "partitioned-mode SpMM (gather, per-part SpMM of the owned rows into place), 1024-bit CSA AIG, F=64",
-        "value": round(2.0 * nnz * F / (ms * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "metric": "partitioned-mode SpMM (per part: the owned rows computed into place from the resident feature "
+                  "matrix), 1024-bit CSA AIG, F=64",
+        "value": round(2.0 * nnz * F / (ms_in_place * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_in_place, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": name + f"_partitioned{P}", "N": n, "nnz": nnz, "F": F, "parts": P},
-        "ms_per_step_with_scatter_pass": round(ms_copies, 4),
+        "max_abs_diff_vs_full_graph_in_place": worst_in_place,
+        "ms_per_step_with_gather_pass": round(ms, 4),
+        "ms_per_step_with_gather_and_scatter_pass": round(ms_copies, 4),
         "boundary_edge_fraction": round(cross / 2 / undirected, 4),
         "rows_with_boundary": sum(it[3] for it in items), "largest_part_rows": max_loc,
         "device_bytes_full_graph": full_foot, "device_bytes_largest_part": max(foot),
@@ -199,7 +259,7 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name
     # The dense products run as bf16 piece products (a sixteenth of the fp32 matrix instruction's time per
     # multiply-add, six per fp32 product), so the layer is bound like the aggregation alone: by the bytes of X,
     # of the CSR and of H.
-    bytes_layer = algorithmic_bytes(n, nnz, F)
+    bytes_layer = bytes_needed(G.groot_plan_query(plan, "csr_bytes"), n, n, F)
     gbps = bytes_layer / (ms_fused * 1e-3) / 1e9
     print(json.dumps({
         "metric": f"GraphSAGE-mean layer forward H = relu((A_hat X) Wn + X Ws + b), fused, 1024-bit CSA AIG, F={F}",
@@ -215,6 +275,120 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name
         "max_abs_diff_vs_unfused": worst, "device": props.name}))
 
 
+def stress_bench(args, G, torch, np, wl, name, props):
+    """The polarized stress workload: N = 2^24 rows, 99 % light rows (3-5 entries within +-4096), 1 % heavy rows
+    of 64 .. 262,144 entries with uniformly random columns, F = 128; one SpMM per degree threshold of the sweep.
+    The gathers of the heavy rows (4 F bytes per stored entry, spread uniformly over the whole feature matrix,
+    34 times the size of the last-level cache) cannot be served from any cache, so the bound of this workload is
+    the gather demand 4 F nnz against the HBM peak, not the read-once byte count."""
+    log2n, _, F, seed, T_default = WORKLOADS[name]
+    n = 1 << log2n
+    thresholds = tuple(args.thresholds) if args.thresholds else STRESS_THRESHOLDS
+    t0 = time.time()
+    s = wl.stress_graph(seed, n, window=4096, dmin=64, dmax=262144, verbose=True)
+    nnz = int(s.rowptr[-1])
+    deg = np.diff(s.rowptr)
+    t_gen = time.time() - t0
+    t0 = time.time()
+    g = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    X = wl.uniform_features(seed, 0, n, F, device="cuda")
+    Y = torch.empty_like(X)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+    flops = 2.0 * nnz * F
+    gather_bytes = 4.0 * F * nnz
+
+    sweep, headline, cpu, parity = [], None, None, None
+    T_head = T_default if T_default in thresholds else thresholds[0]
+    for T in thresholds:
+        plan = G.groot_spmm_plan(g, T)
+        pv = G.groot_plan_view(plan)
+        G.groot_plan_upload(plan, F)
+        for _ in range(max(1, args.warmup)):
+            G.groot_spmm_execute(plan, X, Y, F)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            G.groot_spmm_execute(plan, X, Y, F)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+        def timed_phase(phases):
+            G.groot_spmm_execute_phases(plan, X, Y, F, phases)
+            start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            start.record()
+            for _ in range(args.steps):
+                G.groot_spmm_execute_phases(plan, X, Y, F, phases)
+            stop.record()
+            stop.synchronize()
+            return start.elapsed_time(stop) / args.steps
+
+        ms_ld = timed_phase(G.GROOT_PHASE_LD)
+        ms_hd = timed_phase(G.GROOT_PHASE_HD) if pv["n_hd"] else 0.0
+        ms_fin = timed_phase(G.GROOT_PHASE_FINISH) if pv["n_hd"] else 0.0
+        nnz_hd = G.groot_plan_query(plan, "nnz_hd")
+        csr_bytes = G.groot_plan_query(plan, "csr_bytes")
+        item = {"degree_threshold": T, "n_hd_rows": pv["n_hd"], "nnz_hd": nnz_hd, "ms_per_step": round(ms, 3),
+                "gflops": round(flops / (ms * 1e-3) / 1e9, 1),
+                "gather_demand_gbps": round(gather_bytes / (ms * 1e-3) / 1e9, 1),
+                "ld_ms": round(ms_ld, 3), "hd_ms": round(ms_hd, 3), "finish_ms": round(ms_fin, 3),
+                "hd_gather_gbps": round(4.0 * F * nnz_hd / (ms_hd * 1e-3) / 1e9, 1) if ms_hd else None,
+                "hd_pieces": G.groot_plan_query(plan, "hd_pieces"), "csr_bytes": csr_bytes,
+                "weight_mode": G.groot_plan_query(plan, "weight_mode")}
+        sweep.append(item)
+        print(f"stress T={T}: {item}", file=sys.stderr, flush=True)
+        if T == T_head:
+            headline = item
+            G.groot_spmm_execute(plan, X, Y, F)
+            torch.cuda.synchronize()
+            # ---- CPU oracle on sampled rows (light rows at random, heavy rows at random, the eight longest)
+            if not args.no_cpu_baseline:
+                import oracle
+
+                rng = np.random.default_rng(5)
+                heavy = np.nonzero(deg >= 16)[0]
+                rows = np.unique(np.concatenate([rng.integers(0, n, 20000), rng.choice(heavy, min(600, heavy.shape[0]), replace=False),
+                                                 heavy[np.argsort(deg[heavy])[-8:]], [0, n - 1]]))
+                sub_rowptr = np.concatenate([[0], np.cumsum(deg[rows])])
+                idx = np.concatenate([np.arange(s.rowptr[v], s.rowptr[v + 1]) for v in rows])
+                uniq, inv = np.unique(s.col[idx], return_inverse=True)
+                Xs = X[torch.from_numpy(uniq.astype(np.int64)).cuda()].cpu().numpy()
+                sub_col, sub_val = inv.astype(np.int32), s.val[idx]
+                threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+                t0 = time.perf_counter()
+                Y64, _ = oracle.spmm_f64(sub_rowptr, sub_col, sub_val, Xs, want_abs=False)
+                t_cpu = time.perf_counter() - t0
+                _, S = oracle.spmm_f64(sub_rowptr, sub_col, sub_val, Xs, want_abs=True)
+                got = Y[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+                parity = float(np.max(np.abs(got - Y64) / (1e-5 * S + 1e-6)))
+                cpu = {"value": round(2.0 * idx.shape[0] * F / t_cpu / 1e9, 3), "unit": "GFLOP/s", "cores": threads,
+                       "kind": "oracle", "seconds": round(t_cpu, 3),
+                       "sample": f"{rows.shape[0]} sampled rows (20,000 random, 600 heavy, the 8 longest) with "
+                                 f"{idx.shape[0]} stored entries of the {n}-row graph, their {uniq.shape[0]} feature "
+                                 f"rows gathered into a compact matrix first, F={F} (fp64, row-parallel OpenMP)"}
+        del plan
+    out = {
+        "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak), polarized stress graph, F=128",
+        "value": headline["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": headline["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": name, "N": n, "nnz": nnz, "F": F, "degree_threshold": headline["degree_threshold"],
+                   "heavy_rows": int((deg >= 64).sum()), "longest_row": int(deg.max())},
+        "hbm_gbps": round(algorithmic_bytes(n, nnz, F) / (headline["ms_per_step"] * 1e-3) / 1e9, 1),
+        "algorithmic_bytes_per_step": algorithmic_bytes(n, nnz, F),
+        "bytes_needed_per_step": bytes_needed(headline["csr_bytes"], n, n, F),
+        "roofline": {"bound": "hbm", "kernel": "hd_kernel", "achieved": headline["hd_gather_gbps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(headline["hd_gather_gbps"] / HBM_PEAK_GBPS, 4) if headline["hd_gather_gbps"] else None,
+                     "traffic": None, "ms": headline["hd_ms"],
+                     "algorithmic_bytes": 4.0 * F * headline["nnz_hd"],
+                     "note": "gather demand of the high-degree rows (4 F bytes per stored entry; uniformly random "
+                             "columns over a feature matrix 34 times the last-level cache) over the HD kernel's time"},
+        "threshold_sweep": sweep,
+        "cpu_baseline": cpu, "parity_max_err_over_tol": parity,
+        "generation_seconds": round(t_gen, 1), "setup_seconds": round(t_setup, 1), "device": props.name}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -223,6 +397,7 @@ def main():
     ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
+    ap.add_argument("--thresholds", type=int, nargs="*", default=None, help="stress workload: degree thresholds to sweep")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
     ap.add_argument("--partitioned", type=int, default=0, metavar="P",
                     help="time the partitioned mode instead: P parts with re-grown boundary, gather -> SpMM -> scatter")
@@ -233,7 +408,7 @@ def main():
     ap.add_argument("--ld-pipeline", type=int, default=None, help="LD kernel choice: 1 pipelined, 0 plain, -1 auto")
     ap.add_argument("--sage-gap", type=int, default=None, help="pacing of the fused layer's matrix wavefronts (0..4)")
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
-                    help="any other groot_set_tuning knob (repeatable), e.g. ld_strip_rows=0")
+                    help="any other groot_set_tuning knob (repeatable), e.g. uniform_detect=0")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path is single-GPU by design); "
@@ -270,6 +445,9 @@ def main():
         # the headline graph needs ~76 GB of HBM; fall back to one copy on smaller parts
         name = "csa1024_b16_F64" if props.total_memory > 100e9 else "csa1024_b1_F64"
     bits, batch, F, seed, T = WORKLOADS[name]
+    if name.startswith("stress"):
+        stress_bench(args, G, torch, np, wl, name, props)
+        return
 
     t0 = time.time()
     shape_only = wl.lut4_csa_graph if name.startswith("lut4") else wl.cellmap_csa_graph if name.startswith("cell") else None
@@ -315,9 +493,11 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     flops = 2.0 * nnz * F
-    bytes_all = algorithmic_bytes(n, nnz, F)
+    bytes_all = algorithmic_bytes(n, nnz, F)                 # by the definition (int64 row pointers, weights counted)
+    bytes_min = bytes_needed(G.groot_plan_query(plan, "csr_bytes"), n, n, F)   # what the kernels have to move
     gflops = flops / (ms_per_step * 1e-3) / 1e9
-    gbps = bytes_all / (ms_per_step * 1e-3) / 1e9
+    gbps = bytes_min / (ms_per_step * 1e-3) / 1e9
+    gbps_formula = bytes_all / (ms_per_step * 1e-3) / 1e9
 
     # ---- dominant kernel (LD) alone, HIP events on the launch stream
     def timed_phase(phases):
@@ -332,8 +512,11 @@ def main():
     ms_ld = timed_phase(G.GROOT_PHASE_LD)
     ms_hd = timed_phase(G.GROOT_PHASE_HD) if n_hd else 0.0
     ms_fin = timed_phase(G.GROOT_PHASE_FINISH) if n_hd else 0.0
-    # LD launch, algorithmic bytes: all row pointers, the LD rows' indices and weights, X once, the LD rows of Y
-    bytes_ld = 8 * (n + 1) + 8 * (nnz - nnz_hd) + 4 * n * F + 4 * n_ld * F
+    # LD launch: the bytes it has to move (the LD part of the device CSR as the kernels read it, X once, the LD
+    # rows of Y), and the same by the definition's formula (all row pointers as int64, index and weight of every
+    # LD entry) for comparison
+    bytes_ld = bytes_needed(G.groot_plan_query(plan, "csr_bytes_ld"), n, n_ld, F)
+    bytes_ld_formula = 8 * (n + 1) + 8 * (nnz - nnz_hd) + 4 * n * F + 4 * n_ld * F
     ld_gbps = bytes_ld / (ms_ld * 1e-3) / 1e9
 
     # ---- device copy of the same N x F matrix: the practical streaming ceiling of this machine
@@ -386,6 +569,8 @@ def main():
     # which LD kernel the library picked for this plan and F
     mode = G.groot_plan_query(plan, "ld_pipelined")
     ld_name = "ld_pipe_kernel" if (mode == 2 and F in (32, 64, 128)) or (mode == 1 and F in (64, 128)) else "ld_kernel"
+    traffic, traffic_note = (None, "not measured for the transposed graph") if args.transposed else \
+        measured_traffic(name, ld_name)
     out = {
         "metric": "SpMM GFLOP/s and achieved HBM GB/s (% of peak), 1024-bit CSA AIG, F=64",
         "value": round(gflops, 2),
@@ -404,11 +589,18 @@ def main():
                    "xcd_remap": args.xcd_remap if args.xcd_remap is not None else 1},
         "hbm_gbps": round(gbps, 1),
         "hbm_pct_of_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
-        "algorithmic_bytes_per_step": bytes_all,
+        "bytes_needed_per_step": bytes_min,
+        "formula": {"algorithmic_bytes_per_step": bytes_all, "hbm_gbps": round(gbps_formula, 1),
+                    "hbm_pct_of_peak": round(100.0 * gbps_formula / HBM_PEAK_GBPS, 2),
+                    "note": "8(N+1) + 4 nnz + 4 nnz + 4NF + 4NF: counts a weight array and 8-byte row pointers "
+                            "whether or not the kernels read them; hbm_gbps / hbm_pct_of_peak above use "
+                            "bytes_needed_per_step"},
         "roofline": {"bound": "hbm", "kernel": ld_name, "achieved": round(ld_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(ld_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None if args.transposed else TRAFFIC.get((name, ld_name)),
-                     "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld},
+                     "traffic": traffic, "traffic_note": traffic_note,
+                     "ms": round(ms_ld, 4), "algorithmic_bytes": bytes_ld, "formula_bytes": bytes_ld_formula},
+        "weight_mode": G.groot_plan_query(plan, "weight_mode"),
+        "kernel_sources_sha16": kernel_sources_sha16(),
         "hd_ms": round(ms_hd, 4),
         "finish_ms": round(ms_fin, 4),
         "copy_kernel_gbps": round(copy_gbps, 1),

@@ -18,8 +18,9 @@
  *     released with the matching *_free (NULL is accepted).  Pointers returned
  *     by the *_view calls are borrowed and live as long as the viewed object.
  *   - Node ids and columns are int32 (N < 2^31), row pointers are int64.
- *   - No global state except a thread-local error string and the tuning table
- *     of groot_set_tuning().
+ *   - No global state except a thread-local error string, the tuning table of
+ *     groot_set_tuning() (atomic integers, each read at the call its
+ *     description names).
  */
 #ifndef GROOT_H
 #define GROOT_H
@@ -176,6 +177,29 @@ groot_status groot_spmm_execute_rows(const groot_plan *plan, const float *X_dev,
                                      int32_t F, int64_t n_rows, const int64_t *out_ids_dev,
                                      void *hip_stream);
 /* ---------------------------------------------------------------------------
+ * groot_plan_use_global_columns -- lets the plan of a part's sub-graph read the
+ * feature matrix of the WHOLE graph in place.
+ * Paper: Section "GNN and Edge Re-growth After Partition", Algorithm 1: the
+ * sub-graph (S_p+, E_p+) names its nodes by local ids, and global_id maps them
+ * back.  When the whole feature matrix is resident on the device anyway, there
+ * is no need to copy the rows of S_p+ into a compact matrix first: this call
+ * rewrites the plan's resident column indices once, col <- global_id[col], and
+ * from then on X_dev of groot_spmm_execute / groot_spmm_execute_rows is the
+ * whole graph's matrix ([n_global, F]); rows (and Y without out_ids) stay
+ * local.  With out_ids = global_id a partitioned pass is then one
+ * groot_spmm_execute_rows per part and nothing else.  (The compact form remains
+ * the one to use when only one part's features fit on the device.)
+ * plan: resident; global_id_dev (device, int64 [rows of the plan]): the part's
+ * global_id, every entry in [0, n_global) (not checked); n_global < 2^31.
+ * Enqueues one kernel on hip_stream; the plan's next execute must be ordered
+ * after it (same stream, or synchronise).  Afterwards groot_sage_layer_forward
+ * and groot_partition_regrow_device refuse the plan, and a second call is
+ * EINVAL.  Errors: EINVAL, ERANGE (n_global >= 2^31), EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_plan_use_global_columns(groot_plan *plan, const int64_t *global_id_dev,
+                                           int64_t n_global, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * groot_sage_layer_forward -- one GraphSAGE-mean layer with the aggregation fused in:
  *     H = act( (A_hat X) Wn + X Ws + b ),   act = ReLU if relu != 0, identity otherwise.
  * Paper: Section "GNN and Edge Re-growth After Partition" (the GraphSAGE layer takes
@@ -323,7 +347,11 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
  * 64 and 128), "hd_pieces" (launch size of the HD kernel),
  * "hd_partials" (partial-sum slots of split high-degree rows), "weight_mode"
  * (how the kernels take the weights: 0 all 1, 1 fl(1 / row length) recomputed
- * from the row pointer, 2 read from the weight array).
+ * from the row pointer, 2 read from the weight array), "nnz_hd" (stored entries
+ * of the high-degree rows), "csr_bytes" (bytes of the graph's device arrays
+ * that one execute reads: row pointers, column indices, the weights only when
+ * the kernels read them, the high-degree pieces' descriptors; "csr_bytes_ld" /
+ * "csr_bytes_hd" its split over the low-degree and the high-degree kernel).
  * Errors: EINVAL (NULL, unknown name, plan not uploaded). */
 groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t *value);
 

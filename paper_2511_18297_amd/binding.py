@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
     "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
@@ -59,6 +59,7 @@ _lib.groot_plan_upload.argtypes = [_vp, _i32]
 _lib.groot_spmm_execute.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.groot_spmm_execute_phases.argtypes = [_vp, _vp, _vp, _i32, _u32, _vp]
 _lib.groot_spmm_execute_rows.argtypes = [_vp, _vp, _vp, _i32, _i64, _vp, _vp]
+_lib.groot_plan_use_global_columns.argtypes = [_vp, _vp, _i64, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
@@ -217,6 +218,9 @@ def groot_spmm_plan(g: Graph, degree_threshold: int) -> Plan:
     _check(_lib.groot_spmm_plan(g.handle, degree_threshold, ctypes.byref(out)))
     pl = Plan(out.value, g)
     pl.degree_threshold = degree_threshold
+    n = _i64(0)
+    _check(_lib.groot_graph_view(g.handle, ctypes.byref(n), None, None, None, None, None))
+    pl.n_rows = n.value
     return pl
 
 
@@ -254,23 +258,57 @@ def _stream_handle(stream):
     return stream.cuda_stream
 
 
-def groot_spmm_execute(pl: Plan, X, Y, F: int = None, stream=None) -> None:
+def _plan_rows(pl: Plan) -> int:
+    """rows of the plan's graph (sub-graph rows for a plan built from a device part)"""
+    return pl.n_rows
+
+
+def _feature_rows(pl: Plan) -> int:
+    """rows of the feature matrix the plan's columns index (the whole graph's once its columns are global)"""
+    return getattr(pl, "n_cols", pl.n_rows)
+
+
+def _features(t, what, rows, F):
+    """The C ABI cannot know buffer sizes: a float32 CUDA tensor that holds at least rows x F elements, or TypeError /
+    ValueError before anything is launched (a kernel that runs off a short buffer faults the GPU)."""
     import torch
 
-    if X.dtype != torch.float32 or Y.dtype != torch.float32:
-        raise TypeError("X and Y must be float32")
+    ptr = _dev_ptr(t, what)
+    if t.dtype != torch.float32:
+        raise TypeError(f"{what} must be float32")
+    if t.dim() == 2 and t.shape[1] != F:
+        raise ValueError(f"{what} has {t.shape[1]} columns, F = {F}")
+    if t.numel() < rows * F:
+        raise ValueError(f"{what} holds {t.numel()} elements, {rows} rows x F = {F} are needed")
+    return ptr
+
+
+def groot_spmm_execute(pl: Plan, X, Y, F: int = None, stream=None) -> None:
     F = X.shape[1] if F is None else F
-    _check(_lib.groot_spmm_execute(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, _stream_handle(stream)))
+    _check(_lib.groot_spmm_execute(pl.handle, _features(X, "X", _feature_rows(pl), F),
+                                   _features(Y, "Y", _plan_rows(pl), F), F, _stream_handle(stream)))
 
 
 def groot_spmm_execute_phases(pl: Plan, X, Y, F: int, phases: int, stream=None) -> None:
-    _check(_lib.groot_spmm_execute_phases(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Y, "Y"), F, phases,
-                                          _stream_handle(stream)))
+    _check(_lib.groot_spmm_execute_phases(pl.handle, _features(X, "X", _feature_rows(pl), F),
+                                          _features(Y, "Y", _plan_rows(pl), F), F, phases, _stream_handle(stream)))
+
+
+def groot_plan_use_global_columns(pl: Plan, global_id, n_global: int, stream=None) -> None:
+    """global_id: the part's int64 ids on the device (tensor or library-owned array), one per row of the plan."""
+    if global_id.shape[0] < _plan_rows(pl):
+        raise ValueError("global_id must have one entry per row of the plan")
+    _check(_lib.groot_plan_use_global_columns(pl.handle, _ids(global_id, "global_id"), n_global, _stream_handle(stream)))
+    pl.n_cols = n_global
 
 
 def groot_spmm_execute_rows(pl: Plan, X, Y, F: int, n_rows: int, out_ids=None, stream=None) -> None:
+    """Y must hold every row that out_ids names (not checked: the ids live on the device); without out_ids it
+    must hold n_rows rows."""
     import torch
 
+    _features(X, "X", _feature_rows(pl), F)
+    _features(Y, "Y", n_rows if out_ids is None else 0, F)
     if isinstance(out_ids, RawDeviceArray):
         if out_ids.dtype != np.int64 or out_ids.shape[0] < n_rows:
             raise TypeError("out_ids must be int64 with at least n_rows entries")
@@ -283,27 +321,29 @@ def groot_spmm_execute_rows(pl: Plan, X, Y, F: int, n_rows: int, out_ids=None, s
 
 def groot_sage_layer_forward(pl: Plan, X, Wn, Ws, bias, relu: bool, H, F: int = None, stream=None) -> None:
     F = X.shape[1] if F is None else F
-    _check(_lib.groot_sage_layer_forward(pl.handle, _dev_ptr(X, "X"), _dev_ptr(Wn, "Wn"), _dev_ptr(Ws, "Ws"),
-                                         None if bias is None else _dev_ptr(bias, "bias"), 1 if relu else 0,
-                                         _dev_ptr(H, "H"), F, _stream_handle(stream)))
+    n = _plan_rows(pl)
+    _check(_lib.groot_sage_layer_forward(pl.handle, _features(X, "X", n, F), _features(Wn, "Wn", F, F),
+                                         _features(Ws, "Ws", F, F),
+                                         None if bias is None else _features(bias, "bias", 1, F), 1 if relu else 0,
+                                         _features(H, "H", n, F), F, _stream_handle(stream)))
 
 
 def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_degree, ld_deg_offsets, counts,
-                            stream=None) -> None:
+                            stream=None, _entry=None) -> None:
     """Caller-allocated CUDA tensors: uint8[N], int32[N] x3, int64[T+1], int64[2]."""
     import torch
 
-    n = pl.n_rows if pl.graph is None else groot_graph_view(pl.graph)["n"]
+    n = _plan_rows(pl)
     for t, dt, size, what in ((row_class, torch.uint8, n, "row_class"), (hd_rows, torch.int32, n, "hd_rows"),
                               (ld_rows, torch.int32, n, "ld_rows"), (ld_rows_by_degree, torch.int32, n, "ld_rows_by_degree"),
                               (ld_deg_offsets, torch.int64, pl.degree_threshold + 1, "ld_deg_offsets"),
                               (counts, torch.int64, 2, "counts")):
         if t.dtype != dt or t.numel() < max(size, 1):
             raise TypeError(f"{what} must be {dt} with at least {max(size, 1)} elements")
-    _check(_lib.groot_plan_lists_device(pl.handle, _dev_ptr(row_class, "row_class"), _dev_ptr(hd_rows, "hd_rows"),
-                                        _dev_ptr(ld_rows, "ld_rows"), _dev_ptr(ld_rows_by_degree, "ld_rows_by_degree"),
-                                        _dev_ptr(ld_deg_offsets, "ld_deg_offsets"), _dev_ptr(counts, "counts"),
-                                        _stream_handle(stream)))
+    entry = _entry or _lib.groot_plan_lists_device
+    _check(entry(pl.handle, _dev_ptr(row_class, "row_class"), _dev_ptr(hd_rows, "hd_rows"),
+                 _dev_ptr(ld_rows, "ld_rows"), _dev_ptr(ld_rows_by_degree, "ld_rows_by_degree"),
+                 _dev_ptr(ld_deg_offsets, "ld_deg_offsets"), _dev_ptr(counts, "counts"), _stream_handle(stream)))
 
 
 def groot_plan_query(pl: Plan, what: str) -> int:
@@ -395,16 +435,26 @@ def groot_dev_part_plan(part: DevPart, degree_threshold: int, max_F: int, stream
     return pl
 
 
+def _ids(ids, what="ids"):
+    import torch
+
+    if (ids.dtype != np.int64) if isinstance(ids, RawDeviceArray) else (ids.dtype != torch.int64):
+        raise TypeError(f"{what} must be int64")
+    return _dev_ptr(ids, what)
+
+
 def groot_rows_gather(ids, X, out, F: int = None, stream=None) -> None:
+    """X must hold every row that ids names (not checked: the ids live on the device)."""
     F = X.shape[1] if F is None else F
-    _check(_lib.groot_rows_gather(_dev_ptr(ids, "ids"), ids.shape[0], _dev_ptr(X, "X"), _dev_ptr(out, "out"), F,
-                                  _stream_handle(stream)))
+    _check(_lib.groot_rows_gather(_ids(ids), ids.shape[0], _features(X, "X", 0, F), _features(out, "out", ids.shape[0], F),
+                                  F, _stream_handle(stream)))
 
 
 def groot_rows_scatter(ids, inp, Y, F: int = None, stream=None) -> None:
+    """Y must hold every row that ids names (not checked: the ids live on the device)."""
     F = Y.shape[1] if F is None else F
-    _check(_lib.groot_rows_scatter(_dev_ptr(ids, "ids"), ids.shape[0], _dev_ptr(inp, "in"), _dev_ptr(Y, "Y"), F,
-                                   _stream_handle(stream)))
+    _check(_lib.groot_rows_scatter(_ids(ids), ids.shape[0], _features(inp, "in", ids.shape[0], F), _features(Y, "Y", 0, F),
+                                   F, _stream_handle(stream)))
 
 
 def groot_set_tuning(name: str, value: int) -> None:

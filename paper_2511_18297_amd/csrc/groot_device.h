@@ -87,6 +87,13 @@ __device__ __forceinline__ v4f ld_row_sum(int64_t s, int64_t e, const int32_t *_
     default: { constexpr int kW = kExplicit; CALL; } break; \
     }
 
+// Signed byte distance between two device addresses that belong to different allocations (the row of zeros
+// of a plan, seen from a feature matrix): integer arithmetic on the addresses, not a pointer difference.
+inline int64_t byte_distance(const void *from, const void *to)
+{
+    return (int64_t)((uintptr_t)to - (uintptr_t)from);
+}
+
 inline bool grid_ok(int64_t blocks) { return blocks > 0 && blocks <= 0x7fffffffLL; }
 
 // explicit weights need the weight array on the device; the other modes never touch it

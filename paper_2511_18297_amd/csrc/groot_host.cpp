@@ -343,7 +343,7 @@ template <class Begin, class Degree>
 groot_status hd_schedule(int64_t n_hd, const int32_t *hd_rows, Begin begin_of, Degree degree_of,
                          std::vector<HdChunk> &chunks, std::vector<HdSplitRow> &split_rows, int64_t &n_partials)
 {
-    const int64_t chunk = std::max(64, tuning().hd_chunk);
+    const int64_t chunk = std::max(64, tuning().hd_chunk.load());
     int64_t slots = 0;
     for (int64_t k = 0; k < n_hd; ++k) {
         const int32_t row = hd_rows[k];
@@ -504,7 +504,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
     if (plan->resident) release_device(plan);
     const groot_graph *g = plan->g;
     DevicePlan &d = plan->dev;
-    d.n = g->n;
+    d.n = d.n_cols = g->n;
     d.nnz = g->nnz;
     d.threshold = plan->threshold;
     d.xcd_remap = tuning().xcd_remap;
@@ -560,6 +560,8 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         d.ld_pipelined = pipelined_by_default(knob, n_ld, n_short);
     }
     d.n_chunks = (int64_t)plan->chunks.size();
+    d.nnz_hd = 0;
+    for (const HdChunk &ch : plan->chunks) d.nnz_hd += ch.len;
     d.n_tiles = (g->n + kRowsPerLdTile - 1) / kRowsPerLdTile;
     d.n_split_rows = (int64_t)plan->split_rows.size();
     d.n_partials = plan->n_partials;
@@ -588,8 +590,8 @@ extern "C" groot_status groot_spmm_execute_phases(const groot_plan *plan, const 
     if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_spmm_execute: F exceeds the max_F given to groot_plan_upload");
     if (phases & ~GROOT_PHASE_ALL) return fail(GROOT_EINVAL, "groot_spmm_execute: unknown phase bits");
     const char *a = (const char *)X_dev, *b = (const char *)Y_dev;
-    const int64_t bytes = plan->dev.n * (int64_t)F * 4;
-    if (a < b + bytes && b < a + bytes) return fail(GROOT_EINVAL, "groot_spmm_execute: X and Y overlap");
+    const int64_t x_bytes = plan->dev.n_cols * (int64_t)F * 4, y_bytes = plan->dev.n * (int64_t)F * 4;
+    if (a < b + y_bytes && b < a + x_bytes) return fail(GROOT_EINVAL, "groot_spmm_execute: X and Y overlap");
     int err = 0;
     if (!err && (phases & GROOT_PHASE_LD)) err = launch_ld(plan->dev, X_dev, Y_dev, F, hip_stream);
     if (!err && (phases & GROOT_PHASE_HD) && plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, Y_dev, F, hip_stream);
@@ -636,6 +638,8 @@ extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const f
     if (!Wn_dev || !Ws_dev) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL weight pointer");
     if (!plan->resident) return fail(GROOT_EINVAL, "groot_sage_layer_forward: plan is not on the device (call groot_plan_upload)");
     if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F exceeds the max_F given to groot_plan_upload");
+    if (plan->dev.n_cols != plan->dev.n)
+        return fail(GROOT_EINVAL, "groot_sage_layer_forward: the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
     const char *a = (const char *)X_dev, *b = (const char *)H_dev;
     const int64_t bytes = plan->dev.n * (int64_t)F * 4;
     if (a < b + bytes && b < a + bytes) return fail(GROOT_EINVAL, "groot_sage_layer_forward: X and H overlap");
@@ -664,6 +668,20 @@ extern "C" groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t 
                                  ld_rows_by_degree_dev, ld_deg_offsets_dev, counts_dev, hip_stream);
     if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, "groot_plan_lists_device: scratch allocation failed");
     if (err) return fail(GROOT_EHIP, std::string("groot_plan_lists_device: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_plan_use_global_columns(groot_plan *plan, const int64_t *global_id_dev, int64_t n_global,
+                                                      void *hip_stream)
+{
+    if (!plan || !global_id_dev) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: NULL argument");
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: plan is not on the device (call groot_plan_upload)");
+    if (plan->dev.n_cols != plan->dev.n) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: the columns were renamed before");
+    if (n_global < plan->dev.n) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: n_global is smaller than the plan's own row count");
+    if (n_global > std::numeric_limits<int32_t>::max()) return fail(GROOT_ERANGE, "groot_plan_use_global_columns: n_global does not fit int32 columns");
+    int err = launch_col_map(plan->dev.col, plan->dev.nnz, global_id_dev, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_plan_use_global_columns: launch failed: ") + hip_error_text(err));
+    plan->dev.n_cols = n_global;
     return GROOT_OK;
 }
 
@@ -859,6 +877,8 @@ extern "C" groot_status groot_partition_regrow_device(const groot_plan *plan, in
     if (!plan || !out) return fail(GROOT_EINVAL, "groot_partition_regrow_device: NULL argument");
     if (!plan->resident) return fail(GROOT_EINVAL, "groot_partition_regrow_device: plan is not on the device (call groot_plan_upload)");
     const int64_t n = plan->dev.n;
+    if (plan->dev.n_cols != n)
+        return fail(GROOT_EINVAL, "groot_partition_regrow_device: the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
     if (num_parts < 1 || num_parts > n) return fail(GROOT_EINVAL, "groot_partition_regrow_device: num_parts must be in [1,N]");
     if (p < 0 || p >= num_parts) return fail(GROOT_EINVAL, "groot_partition_regrow_device: part index outside [0,P)");
     if (flags & ~GROOT_REGROW) return fail(GROOT_EINVAL, "groot_partition_regrow_device: unknown flag bits");
@@ -997,13 +1017,15 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
             set_error(keep);
             return st;
         }
-        d.n = n;
+        d.n = d.n_cols = n;
         d.nnz = part->d.nnz;
         d.threshold = T;
         d.xcd_remap = tuning().xcd_remap;
         d.weight_mode = d.graph_weight_mode = (int)part->weight_mode;
         d.n_tiles = (n + kRowsPerLdTile - 1) / kRowsPerLdTile;
         d.n_chunks = (int64_t)pl->chunks.size();
+        d.nnz_hd = 0;
+        for (const HdChunk &ch : pl->chunks) d.nnz_hd += ch.len;
         d.n_split_rows = (int64_t)pl->split_rows.size();
         d.n_partials = pl->n_partials;
         {
@@ -1068,6 +1090,17 @@ extern "C" groot_status groot_plan_query(const groot_plan *plan, const char *wha
     else if (k == "weight_mode") *value = plan->dev.weight_mode;
     else if (k == "hd_pieces") *value = plan->dev.n_chunks;
     else if (k == "hd_partials") *value = plan->dev.n_partials;
+    else if (k == "nnz_hd") *value = plan->dev.nnz_hd;
+    else if (k == "csr_bytes" || k == "csr_bytes_ld" || k == "csr_bytes_hd") {
+        // what the kernels read of the graph per execute: every row pointer and every entry's column index, the
+        // entry's weight only when the kernels take the weights from the array; the HD kernel reads its pieces'
+        // descriptors instead of row pointers
+        const DevicePlan &d = plan->dev;
+        const int64_t per_entry = 4 + (d.weight_mode == (int)WeightMode::Explicit ? 4 : 0);
+        const int64_t ld = 8 * (d.n + 1) + per_entry * (d.nnz - d.nnz_hd);
+        const int64_t hd = per_entry * d.nnz_hd + (int64_t)sizeof(HdChunk) * d.n_chunks;
+        *value = k == "csr_bytes_ld" ? ld : k == "csr_bytes_hd" ? hd : ld + hd;
+    }
     else return fail(GROOT_EINVAL, "groot_plan_query: unknown name '" + k + "'");
     return GROOT_OK;
 }
@@ -1084,7 +1117,7 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     }
     if (k == "sage_split" || k == "sage_kernel" || k == "uniform_detect") {
         if (value < 0 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: " + k + " must be 0 or 1");
-        (k == "sage_split" ? tuning().sage_split : k == "sage_kernel" ? tuning().sage_kernel : tuning().uniform_detect) = (int)value;
+        (k == "sage_split" ? tuning().sage_split : k == "sage_kernel" ? tuning().sage_kernel : tuning().uniform_detect).store((int)value);
         return GROOT_OK;
     }
     if (k == "sage_gap") {

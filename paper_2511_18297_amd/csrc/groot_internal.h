@@ -1,6 +1,8 @@
 // Internal declarations shared by the host side and the HIP kernels of libgroot.
 #pragma once
 
+#include <atomic>
+#include <cstddef>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -33,14 +35,16 @@ struct HdSplitRow {
     int32_t pad;
 };
 
+// Process-wide launch-shape knobs (groot_set_tuning).  Every knob is an atomic integer: a call that reads one
+// sees either the old or the new value, never a torn one; which of two racing calls wins is up to the caller.
 struct Tuning {
-    int xcd_remap = 1;
-    int hd_chunk = 512;
-    int sage_gap = 2;               // pacing of the fused layer's matrix wavefronts, see launch_sage
-    int sage_split = 1;             // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
-    int sage_kernel = 1;            // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
-    int uniform_detect = 1;         // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
-    int ld_pipeline = -1;           // pipelined LD kernel: 1 always (where it applies), 0 never, -1 when the rows are short
+    std::atomic<int> xcd_remap{1};
+    std::atomic<int> hd_chunk{512};
+    std::atomic<int> sage_gap{2};          // pacing of the fused layer's matrix wavefronts, see launch_sage
+    std::atomic<int> sage_split{1};        // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
+    std::atomic<int> sage_kernel{1};       // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
+    std::atomic<int> uniform_detect{1};    // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
+    std::atomic<int> ld_pipeline{-1};      // pipelined LD kernel: 1 always (where it applies), 0 never, -1 by the row lengths
 };
 Tuning &tuning();
 
@@ -61,9 +65,12 @@ struct DevicePlan {
     int64_t n_split_rows = 0;
     float *partials = nullptr;      // [n_partials, partial_stride]
     int64_t n_partials = 0;
+    int64_t nnz_hd = 0;             // stored entries of the high-degree rows (sum of the pieces' lengths)
     int xcd_remap = 1;
     float *zero_row = nullptr;      // kZeroRowFloats zeros (the gather target of unused slots in the pipelined
                                     // kernels), followed by kTrashFloats that those kernels may overwrite
+    int64_t n_cols = 0;             // rows of the feature matrix the columns index: n, or the whole graph's row
+                                    // count once a part's plan reads the global matrix in place
     int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
 };
 
@@ -87,6 +94,8 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                      int relu, int32_t F, void *stream);   // F = 64 or 32, row-uniform weights
+// col[p] = ids[col[p]] for p < nnz, in place (a part's local columns -> rows of the whole graph's feature matrix)
+int launch_col_map(int32_t *col, int64_t nnz, const int64_t *ids, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);
 int launch_rows_scatter(const int64_t *ids, int64_t n, const float *in, float *Y, int32_t F, void *stream);
 // Device-side plan lists (groot_plan_device.hip).  Synchronises the stream; kErrOutOfDeviceMemory when its

@@ -206,6 +206,14 @@ __global__ __launch_bounds__(kBlock) void rows_move_kernel(const int64_t *__rest
     }
 }
 
+// col[p] = ids[col[p]]: the columns of a part's sub-graph renamed from local ids to rows of the whole graph
+__global__ __launch_bounds__(kBlock) void col_map_kernel(int32_t *__restrict__ col, int64_t nnz,
+                                                         const int64_t *__restrict__ ids)
+{
+    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * kBlock)
+        col[p] = (int32_t)ids[col[p]];
+}
+
 // ---------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------
@@ -228,7 +236,7 @@ int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *s
     const int32_t F4 = F / 4;
     const int64_t *out_ids = out ? out->ids : nullptr;
     const int64_t n_out = out ? out->n_out : dp.n;
-    // the pipelined kernel pays off from F = 64 on (F = 32: equal on the large graphs, slower on small ones)
+    // the pipelined kernel serves whole graphs at F = 32, 64 and 128 (ld_pipelined: 2 all three widths, 1 only the two wider)
     if (!out && dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
         return launch_ld_pipelined(dp, X, Y, F, stream);
     const int64_t n_tiles = (n_out + kRowsPerLdTile - 1) / kRowsPerLdTile;
@@ -271,6 +279,15 @@ int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, co
     hipStream_t st = (hipStream_t)stream;
     GROOT_DISPATCH_L(L, (hd_finish_kernel<kL><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
                             dp.split_rows, dp.n_split_rows, (const v4f *)dp.partials, (v4f *)Y, F4, out_ids, n_out)));
+    return (int)hipGetLastError();
+}
+
+int launch_col_map(int32_t *col, int64_t nnz, const int64_t *ids, void *stream)
+{
+    if (nnz <= 0) return 0;
+    int64_t grid = (nnz + kBlock - 1) / kBlock;
+    if (grid > 65536) grid = 65536;                      // grid-stride loop
+    col_map_kernel<<<dim3((unsigned)grid), dim3(kBlock), 0, (hipStream_t)stream>>>(col, nnz, ids);
     return (int)hipGetLastError();
 }
 

@@ -39,7 +39,7 @@ __device__ __forceinline__ void pipe_wave_sync()
 template <int L, int W, int G>
 __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void ld_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
-    const char *__restrict__ X, char *__restrict__ Y, const char *__restrict__ zero_row, char *trash, int64_t n,
+    const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
     int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
 {
     constexpr int kRpg = kWave / L;                      // rows per lane group sweep
@@ -64,7 +64,6 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     const int64_t x_end = x_begin + tiles_per_part < n_tiles ? x_begin + tiles_per_part : n_tiles;
     const int64_t t_first = x_begin + j, stride = waves_per_part;
     if (t_first >= x_end) return;
-    const int64_t zero_off = zero_row - X;
     const char *Xf = X + 16 * f;
 
     // ---- CSR pipeline: rp_a and cc/vv belong to the next tile to be staged, rp_b to the one after
@@ -205,7 +204,7 @@ struct PipeArgs {
     const float *val;
     const char *X;
     char *Y;
-    const char *zero_row;
+    int64_t zero_off;                        // byte distance from X to the plan's row of zeros
     char *trash;
     int64_t n;
     int32_t T;
@@ -219,7 +218,7 @@ template <int L, int W, int G>
 static void pipe_launch(const PipeArgs &a)
 {
     ld_pipe_kernel<L, W, G><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
-        a.rowptr, a.col, a.val, a.X, a.Y, a.zero_row, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part, a.waves_per_part,
+        a.rowptr, a.col, a.val, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part, a.waves_per_part,
         a.parts);
 }
 
@@ -257,7 +256,7 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
-    const PipeArgs a{dp.rowptr, col_arg, val_arg, (const char *)X, (char *)Y, (const char *)dp.zero_row, trash, dp.n,
+    const PipeArgs a{dp.rowptr, col_arg, val_arg, (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
                      dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st};
     GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG>(F4, a)));
     return (int)hipGetLastError();

@@ -116,7 +116,7 @@ __device__ __forceinline__ void sage_park_split(char *tile, int row, int k, v4f 
 template <int W, int kGap, bool kSplit>
 __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgThreads / 256, kSgThreads / 256))) void sage_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
-    const v4f *__restrict__ X, v4f *H, const float *__restrict__ zero_row, const float *__restrict__ Wn,
+    const v4f *__restrict__ X, v4f *H, int64_t zero_off, const float *__restrict__ Wn,
     const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n, int32_t T, int64_t n_tiles, int64_t tiles_per_wg,
     int64_t wgs_per_xcd, int remap)
 {
@@ -238,7 +238,6 @@ __global__ __launch_bounds__(kSgThreads) __attribute__((amdgpu_waves_per_eu(kSgT
     // =================================== producer ===================================
     const int p = wv - kSgConsumers;             // rows 8p .. 8p+7 of every tile
     const int g = l / 16, f = l % 16;            // lane group / float4 slice
-    const int64_t zero_off = (const char *)zero_row - (const char *)X;   // where unused slots point
 
     // ---- CSR pipeline for the producer's 8 rows of a tile
     // rp_a: row pointers of the tile whose column indices are in cc (the next tile to be staged);
@@ -441,12 +440,12 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
 #define GROOT_SAGE_LAUNCH2(GAP, SPLIT)                                                                               \
     GROOT_DISPATCH_W(dp.weight_mode, (sage_kernel<kW, GAP, SPLIT><<<dim3((unsigned)n_wg), dim3(kSgThreads), 0, st>>>(    \
-                                         dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)H, dp.zero_row, Wn, Ws, bias, \
+                                         dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)H, byte_distance(X, dp.zero_row), Wn, Ws, bias, \
                                          relu, dp.n, dp.threshold, n_tiles, tiles_per_wg, n_wg / kXcds, remap)))
 #define GROOT_SAGE_LAUNCH(GAP)                                  \
     if (tuning().sage_split) { GROOT_SAGE_LAUNCH2(GAP, true); } \
     else { GROOT_SAGE_LAUNCH2(GAP, false); }
-    switch (tuning().sage_gap) {
+    switch (tuning().sage_gap.load()) {
     case 0: GROOT_SAGE_LAUNCH(0); break;
     case 1: GROOT_SAGE_LAUNCH(1); break;
     case 3: GROOT_SAGE_LAUNCH(3); break;

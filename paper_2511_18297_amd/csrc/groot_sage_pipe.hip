@@ -98,7 +98,7 @@ __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
 template <int W, int F, int NW>   // W: kOnes or kMean
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
-    const char *__restrict__ X, char *H, const char *__restrict__ zero_row, char *trash,
+    const char *__restrict__ X, char *H, int64_t zero_off, char *trash,
     const float *__restrict__ Wn, const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n,
     int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
 {
@@ -120,7 +120,6 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     const int64_t x_begin = part * tiles_per_part;
     const int64_t x_end = x_begin + tiles_per_part < n_tiles ? x_begin + tiles_per_part : n_tiles;
     const int64_t t_first = x_begin + j, stride = waves_per_part;
-    const int64_t zero_off = zero_row - X;
     const char *Xf = X + 16 * f;
 
     // ---- the weights, cut once per workgroup: s_W[nb][ks][piece][lane] is the B operand of output columns
@@ -379,7 +378,7 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     hipStream_t st = (hipStream_t)stream;
 #define GROOT_SAGE_PIPE_LAUNCH(WM, FF, NW)                                                                            \
     sage_pipe_kernel<WM, FF, NW><<<dim3((unsigned)n_wg), dim3(NW * kWave), 0, st>>>(                                  \
-        dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, (const char *)dp.zero_row, trash, Wn, Ws, bias, relu, \
+        dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, byte_distance(X, dp.zero_row), trash, Wn, Ws, bias, relu, \
         dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts)
     if (F == 64) {
         if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean, 64, 8);

@@ -160,6 +160,51 @@ def test_device_built_plans_fill_the_full_result(torch_cuda, n, batch, P, T, F):
     assert_close_to_oracle(out[guard:N + guard], Y64, S, f"device-built parts, P={P} T={T} F={F}")
 
 
+@pytest.mark.parametrize("n,batch,P,T,F", [(32, 2, 4, 32, 64), (48, 1, 5, 8, 32), (24, 3, 2, 200, 20)])
+@pytest.mark.parametrize("built_on", ["device", "host"])
+def test_parts_read_the_whole_feature_matrix_in_place(torch_cuda, built_on, n, batch, P, T, F):
+    """Partitioned mode without any row copies: the columns of every part's plan are renamed to global rows once
+    (groot_plan_use_global_columns), then one groot_spmm_execute_rows per part reads the whole graph's X in
+    place and writes the owned rows of Y in place.  Every element against the oracle on the full graph."""
+    torch = torch_cuda
+    aig = wl.csa_multiplier_aig(n)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, batch)
+    N = batch * aig.num_nodes
+    X_np = wl.uniform_features_numpy(23, 0, N, F)
+    X = torch.from_numpy(X_np).cuda()
+    guard = 2
+    buf = torch.full((N + 2 * guard, F), float("nan"), device="cuda")
+    buf[:guard] = 555.0
+    buf[N + guard:] = 555.0
+    Y = buf[guard:N + guard]
+    full = _resident_plan(g, T, F)
+    host_parts = G.groot_partition_regrow(g, P) if built_on == "host" else None
+    for p in range(P):
+        if built_on == "device":
+            part = G.groot_partition_regrow_device(full, P, p)
+            view = G.groot_dev_part_view(part)
+            n_owned, ids = view["n_owned"], view["global_id"]
+            plan = G.groot_dev_part_plan(part, T, F)
+        else:
+            pv = G.groot_parts_view(host_parts, p)
+            n_owned, ids = pv["n_owned"], torch.from_numpy(pv["global_id"].copy()).cuda()
+            plan = G.groot_spmm_plan(pv["sub"], T)
+            G.groot_plan_upload(plan, F)
+        print(f"global columns: {built_on} part {p}/{P} csa{n}x{batch} T={T} F={F}", flush=True)
+        G.groot_plan_use_global_columns(plan, ids, N)
+        with pytest.raises(G.GrootError):
+            G.groot_plan_use_global_columns(plan, ids, N)           # only once
+        with pytest.raises(ValueError):
+            G.groot_spmm_execute_rows(plan, X[:N - 1], Y, F, n_owned, ids)   # X is the whole matrix now
+        G.groot_spmm_execute_rows(plan, X, Y, F, n_owned, ids)
+        torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert (out[:guard] == 555.0).all() and (out[N + guard:] == 555.0).all(), "wrote outside Y"
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
+    assert_close_to_oracle(out[guard:N + guard], Y64, S, f"global columns, {built_on}-built parts, P={P} T={T} F={F}")
+
+
 def test_device_built_plan_with_split_high_degree_rows_and_nested_partition(torch_cuda):
     """Explicit weights, rows far above the piece size (several pieces per row), all kernels of the
     device-built plan against the oracle on the oracle's sub-graph; then the sub-graph is partitioned again

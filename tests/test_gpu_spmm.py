@@ -472,8 +472,14 @@ def test_execute_rows_prefix_without_map_and_errors(torch_cuda):
         assert (out[n_rows:] == -3.0).all(), f"n_rows={n_rows}: wrote past the requested rows"
         if n_rows:
             assert_close_to_oracle(out[:n_rows], Y64[:n_rows], S[:n_rows], f"prefix of {n_rows} rows")
-    with pytest.raises(G.GrootError):
+    with pytest.raises(ValueError):            # the binding: Y would be too short
         G.groot_spmm_execute_rows(plan, X, torch.empty_like(X), F, N + 1)
+    with pytest.raises(G.GrootError):          # the library: more rows than the graph has
+        G.groot_spmm_execute_rows(plan, X, torch.empty((N + 1, F), device="cuda"), F, N + 1)
+    with pytest.raises(ValueError):            # a feature matrix with fewer rows than the graph
+        G.groot_spmm_execute(plan, X[:N - 1], torch.empty_like(X), F)
+    with pytest.raises(TypeError):
+        G.groot_spmm_execute(plan, X.double(), torch.empty_like(X), F)
     with pytest.raises(G.GrootError):
         G.groot_spmm_execute_rows(plan, X, torch.empty_like(X), F, -1)
 
