@@ -20,7 +20,8 @@
  *   - Node ids and columns are int32 (N < 2^31), row pointers are int64.
  *   - No global state except a thread-local error string, the tuning table of
  *     groot_set_tuning() (atomic integers, each read at the call its
- *     description names).
+ *     description names) and the fixed scratch array of
+ *     groot_plan_lists_device_static().
  */
 #ifndef GROOT_H
 #define GROOT_H
@@ -249,6 +250,32 @@ groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t *row_class_
                                      int32_t *hd_rows_dev, int32_t *ld_rows_dev,
                                      int32_t *ld_rows_by_degree_dev, int64_t *ld_deg_offsets_dev,
                                      int64_t *counts_dev, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * groot_plan_lists_device_static -- groot_plan_lists_device for callers that
+ * cannot allocate device memory or synchronise: code under HIP graph capture,
+ * tight serving loops that rebuild the lists of a changing graph every step,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and bit for
+ * bit the same outputs; the per-block degree table lives in a fixed 8 MiB
+ * array inside the library (one copy per GPU, held until the process ends)
+ * instead of allocated scratch, so the call only enqueues four kernels on
+ * hip_stream: no hipMalloc, no hipFree, no synchronisation, no memset (the
+ * kernels write every scratch byte they later read).
+ * Limit: 256-byte-rounded 8 (T+2) + 4 (T+2) ceil(N / 4096) bytes must fit
+ * 8 MiB (T = the plan's degree threshold), e.g. 134 M rows up to T = 62,
+ * 16.7 M rows up to T = 509; beyond that the call fails with ERANGE and leaves
+ * the outputs untouched.
+ * All calls on one GPU share that array: two calls whose kernels can overlap
+ * on the same GPU (different streams, or the same plan from two threads) race
+ * and give wrong lists; calls on one stream are ordered and safe.
+ * Errors: EINVAL (NULL, plan not uploaded), ERANGE (threshold > 1024, scratch
+ * limit), EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_plan_lists_device_static(const groot_plan *plan, uint8_t *row_class_dev,
+                                            int32_t *hd_rows_dev, int32_t *ld_rows_dev,
+                                            int32_t *ld_rows_by_degree_dev,
+                                            int64_t *ld_deg_offsets_dev, int64_t *counts_dev,
+                                            void *hip_stream);
 
 /* ---------------------------------------------------------------------------
  * groot_partition_regrow -- partition into sub-graphs with re-grown boundary.

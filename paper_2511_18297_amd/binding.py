@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
     "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
@@ -62,6 +62,7 @@ _lib.groot_spmm_execute_rows.argtypes = [_vp, _vp, _vp, _i32, _i64, _vp, _vp]
 _lib.groot_plan_use_global_columns.argtypes = [_vp, _vp, _i64, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.groot_plan_lists_device_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
 _lib.groot_plan_free.argtypes = [_vp]
 _lib.groot_plan_free.restype = None
@@ -344,6 +345,13 @@ def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_de
     _check(entry(pl.handle, _dev_ptr(row_class, "row_class"), _dev_ptr(hd_rows, "hd_rows"),
                  _dev_ptr(ld_rows, "ld_rows"), _dev_ptr(ld_rows_by_degree, "ld_rows_by_degree"),
                  _dev_ptr(ld_deg_offsets, "ld_deg_offsets"), _dev_ptr(counts, "counts"), _stream_handle(stream)))
+
+
+def groot_plan_lists_device_static(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_degree, ld_deg_offsets, counts,
+                                   stream=None) -> None:
+    """The same lists without any allocation or synchronisation inside the call (fixed scratch in the library)."""
+    groot_plan_lists_device(pl, row_class, hd_rows, ld_rows, ld_rows_by_degree, ld_deg_offsets, counts, stream,
+                            _entry=_lib.groot_plan_lists_device_static)
 
 
 def groot_plan_query(pl: Plan, what: str) -> int:

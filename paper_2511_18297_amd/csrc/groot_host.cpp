@@ -671,6 +671,30 @@ extern "C" groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t 
     return GROOT_OK;
 }
 
+extern "C" groot_status groot_plan_lists_device_static(const groot_plan *plan, uint8_t *row_class_dev,
+                                                       int32_t *hd_rows_dev, int32_t *ld_rows_dev,
+                                                       int32_t *ld_rows_by_degree_dev, int64_t *ld_deg_offsets_dev,
+                                                       int64_t *counts_dev, void *hip_stream)
+{
+    if (!plan) return fail(GROOT_EINVAL, "groot_plan_lists_device_static: NULL plan");
+    if (!row_class_dev || !hd_rows_dev || !ld_rows_dev || !ld_rows_by_degree_dev || !ld_deg_offsets_dev || !counts_dev)
+        return fail(GROOT_EINVAL, "groot_plan_lists_device_static: NULL output pointer");
+    if (!plan->resident)
+        return fail(GROOT_EINVAL, "groot_plan_lists_device_static: plan is not on the device (call groot_plan_upload)");
+    if (plan->threshold > kPlanDeviceMaxThreshold)
+        return fail(GROOT_ERANGE, "groot_plan_lists_device_static: degree threshold above " + std::to_string(kPlanDeviceMaxThreshold));
+    const size_t need = plan_static_scratch_needed(plan->dev.n, plan->threshold);
+    if (need > kPlanStaticScratchBytes)
+        return fail(GROOT_ERANGE, "groot_plan_lists_device_static: " + std::to_string(plan->dev.n) + " rows at threshold " +
+                                      std::to_string(plan->threshold) + " need " + std::to_string(need) +
+                                      " bytes of scratch, the built-in array holds " + std::to_string(kPlanStaticScratchBytes) +
+                                      " (use groot_plan_lists_device)");
+    int err = launch_plan_device_static(plan->dev.rowptr, plan->dev.n, plan->threshold, row_class_dev, hd_rows_dev,
+                                        ld_rows_dev, ld_rows_by_degree_dev, ld_deg_offsets_dev, counts_dev, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string("groot_plan_lists_device_static: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" groot_status groot_plan_use_global_columns(groot_plan *plan, const int64_t *global_id_dev, int64_t n_global,
                                                       void *hip_stream)
 {

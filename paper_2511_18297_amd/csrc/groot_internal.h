@@ -104,6 +104,13 @@ constexpr int kPlanDeviceMaxThreshold = 1024;
 constexpr int kErrOutOfDeviceMemory = 2;   // hipErrorOutOfMemory
 int launch_plan_device(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
                        int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts, void *stream);
+// The same lists with the block table in a fixed array inside the library instead of allocated memory: no
+// allocation, no synchronisation; hipErrorInvalidValue when plan_static_scratch_needed exceeds the array.
+constexpr size_t kPlanStaticScratchBytes = (size_t)8 << 20;
+size_t plan_static_scratch_needed(int64_t n, int32_t T);
+int launch_plan_device_static(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
+                              int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts,
+                              void *stream);
 // One part of a partition with re-grown boundary, built on the device (groot_regrow_device.hip).  All pointers
 // are device memory owned by the struct's holder; val is NULL unless the source graph has explicit weights.
 struct DevicePart {

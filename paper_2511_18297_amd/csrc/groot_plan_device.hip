@@ -10,6 +10,8 @@
 //   plan_scatter  per block again: every row gets its position = column start + rows of the same
 //                 column in earlier blocks + in earlier wavefronts of the block + earlier in its own
 //                 wavefront (ballot ranks in lane order), which is exactly the stable order
+#include <mutex>
+
 #include "groot_device.h"
 
 namespace groot {
@@ -156,6 +158,56 @@ __global__ __launch_bounds__(kBlock) void plan_scatter(const int64_t *__restrict
     }
 }
 
+namespace {
+
+// the four launches on the caller's stream, with the block table and the column totals where the caller says
+int plan_launches(const int64_t *rowptr_dev, int64_t n, int32_t T, int32_t cols, int64_t n_blocks, int32_t *hist,
+                  int64_t *total, uint8_t *row_class, int32_t *hd_rows, int32_t *ld_rows, int32_t *by_degree,
+                  int64_t *deg_offsets, int64_t *counts, hipStream_t st)
+{
+    if (n_blocks)
+        plan_count<<<dim3((unsigned)n_blocks), dim3(kBlock), 0, st>>>(rowptr_dev, n, T, cols, hist, row_class);
+    plan_scan<<<dim3((unsigned)cols), dim3(kBlock), 0, st>>>(hist, n_blocks, cols, total);   // an empty graph: all totals 0
+    plan_offsets<<<dim3(1), dim3(64), 0, st>>>(total, T, deg_offsets, counts);
+    if (n_blocks)
+        plan_scatter<<<dim3((unsigned)n_blocks), dim3(kBlock), 0, st>>>(rowptr_dev, n, T, cols, hist, deg_offsets,
+                                                                      hd_rows, ld_rows, by_degree);
+    return (int)hipGetLastError();
+}
+
+// Scratch of the entry point that may not allocate: the column totals (int64 [cols]) at offset 0 and the
+// block table (int32 [n_blocks][cols]) behind them.  One copy per GPU, held until the process ends; every
+// call on a GPU uses the same bytes.  In host code `scratch` is only a handle for hipGetSymbolAddress: the
+// device address it yields is what kernels, copies and clears are given.
+static __device__ __align__(256) unsigned char scratch[kPlanStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// device address of the current device's copy of `scratch` (looked up once per device)
+int static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = (unsigned char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return 0;
+}
+
+constexpr size_t plan_totals_bytes(int32_t cols) { return ((size_t)cols * sizeof(int64_t) + 255) / 256 * 256; }
+
+}  // namespace
+
 int launch_plan_device(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
                        int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts, void *stream)
 {
@@ -169,18 +221,37 @@ int launch_plan_device(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t 
     if (e != hipSuccess) return (int)hipErrorOutOfMemory;
     e = hipMalloc((void **)&total, (size_t)cols * sizeof(int64_t));
     if (e != hipSuccess) { (void)hipFree(hist); return (int)hipErrorOutOfMemory; }
-    if (n_blocks)
-        plan_count<<<dim3((unsigned)n_blocks), dim3(kBlock), 0, st>>>(rowptr_dev, n, T, cols, hist, row_class);
-    plan_scan<<<dim3((unsigned)cols), dim3(kBlock), 0, st>>>(hist, n_blocks, cols, total);   // an empty graph: all totals 0
-    plan_offsets<<<dim3(1), dim3(64), 0, st>>>(total, T, deg_offsets, counts);
-    if (n_blocks)
-        plan_scatter<<<dim3((unsigned)n_blocks), dim3(kBlock), 0, st>>>(rowptr_dev, n, T, cols, hist, deg_offsets,
-                                                                      hd_rows, ld_rows, by_degree);
-    e = hipGetLastError();
+    const int err = plan_launches(rowptr_dev, n, T, cols, n_blocks, hist, total, row_class, hd_rows, ld_rows, by_degree,
+                                  deg_offsets, counts, st);
     hipError_t e2 = hipStreamSynchronize(st);               // the scratch is freed below
     (void)hipFree(hist);
     (void)hipFree(total);
-    return (int)(e != hipSuccess ? e : e2);
+    return err ? err : (int)e2;
+}
+
+size_t plan_static_scratch_needed(int64_t n, int32_t T)
+{
+    const int64_t n_blocks = (n + kPlanRowsPerBlock - 1) / kPlanRowsPerBlock;
+    return plan_totals_bytes(T + 2) + (size_t)n_blocks * (size_t)(T + 2) * sizeof(int32_t);
+}
+
+int launch_plan_device_static(const int64_t *rowptr_dev, int64_t n, int32_t T, uint8_t *row_class, int32_t *hd_rows,
+                              int32_t *ld_rows, int32_t *by_degree, int64_t *deg_offsets, int64_t *counts,
+                              void *stream)
+{
+    const int32_t cols = T + 2;
+    const int64_t n_blocks = (n + kPlanRowsPerBlock - 1) / kPlanRowsPerBlock;
+    if (T < 1 || cols > kPlanMaxCols || n < 0 || n > 0x7fffffffLL) return (int)hipErrorInvalidValue;
+    if (plan_static_scratch_needed(n, T) > kPlanStaticScratchBytes) return (int)hipErrorInvalidValue;
+    unsigned char *base = nullptr;
+    const int err = static_scratch(&base);
+    if (err) return err;
+    // Nothing in the scratch has to start at zero: plan_count writes every column of every block's table
+    // entry, plan_scan every total, before anything reads them.
+    int64_t *total = (int64_t *)base;
+    int32_t *hist = (int32_t *)(base + plan_totals_bytes(cols));
+    return plan_launches(rowptr_dev, n, T, cols, n_blocks, hist, total, row_class, hd_rows, ld_rows, by_degree,
+                         deg_offsets, counts, (hipStream_t)stream);
 }
 
 }  // namespace groot
