@@ -371,7 +371,9 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
 
 /* What the library decided for an uploaded plan, for diagnostics and benchmarks:
  * "ld_pipelined" (0 the plain LD kernel always, 2 the pipelined one for F = 32,
- * 64 and 128), "hd_pieces" (launch size of the HD kernel),
+ * 64 and 128), "pipe_depth" (gather slots per row of the pipelined kernel, 6 or
+ * 8), "mid_rows" (low-degree rows with more entries than that, which a row-list
+ * kernel computes), "hd_pieces" (launch size of the HD kernel),
  * "hd_partials" (partial-sum slots of split high-degree rows), "weight_mode"
  * (how the kernels take the weights: 0 all 1, 1 fl(1 / row length) recomputed
  * from the row pointer, 2 read from the weight array), "nnz_hd" (stored entries
@@ -396,8 +398,8 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
  * instructions; all three read at each call of groot_sage_layer_forward)
  * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
  * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one when at
- * most one low-degree row in 100,000 has more than 6 entries; read by
- * groot_plan_upload).
+ * most 2 low-degree rows in 100 have more entries than its 6, or else its 8,
+ * gather slots per row; read by groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

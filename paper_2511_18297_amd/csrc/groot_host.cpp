@@ -455,7 +455,7 @@ void release_device(groot_plan *pl)
 {
     DevicePlan &d = pl->dev;
     dev_free(d.rowptr); dev_free(d.col); dev_free(d.val);
-    dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials); dev_free(d.zero_row);
+    dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials); dev_free(d.zero_row); dev_free(d.mid_rows);
     d = DevicePlan{};
     pl->resident = false;
 }
@@ -480,16 +480,21 @@ groot_status to_device(T **dst, const T *src, size_t count, const char *what)
 }  // namespace
 
 namespace {
-// Which LD kernel an uploaded plan uses (DevicePlan::ld_pipelined): the pipelined one for F = 32, 64 and 128 when
-// practically all low-degree rows have at most 6 entries (n_short of n_ld; at most one in 100,000 longer).
-// Measured: carry-save multipliers and the cell-mapped shape (no longer rows at all) gain 4-11 % at every
-// width; Booth multipliers (0.012 % of the rows have 8 entries, and a tile with one of them is redone by the
-// plain loop after a drain of the pipeline) lose 2-10 %, so they stay with the plain kernel.
-int pipelined_by_default(int knob, int64_t n_ld, int64_t n_short)
+// Which LD kernel an uploaded plan uses, from the number of low-degree rows with at most 6 and at most 8 entries
+// (n_le6, n_le8 of n_ld).  The pipelined kernel gives every row 6 or 8 gather slots; a longer low-degree row is
+// masked there and computed by a row-list kernel (one lane group per row, nothing overlapped), so it pays as
+// long as such rows are few: at most 2 in 100 with 6 slots, else at most 2 in 100 with 8 slots, else the plain
+// kernel serves the graph.  -> DevicePlan::ld_pipelined (0 / 2), and the slot count
+struct PipeChoice {
+    int pipelined;
+    int depth;
+};
+PipeChoice choose_ld_kernel(int knob, int64_t n_ld, int64_t n_le6, int64_t n_le8)
 {
-    if (knob > 0) return 2;
-    if (knob == 0 || n_ld <= 0) return 0;
-    return (n_ld - n_short) * 100000 <= n_ld ? 2 : 0;
+    if (knob == 0 || n_ld <= 0) return {0, 6};
+    if ((n_ld - n_le6) * 50 <= n_ld) return {2, 6};
+    if ((n_ld - n_le8) * 50 <= n_ld) return {2, 8};
+    return {knob > 0 ? 2 : 0, 8};
 }
 }  // namespace
 
@@ -551,13 +556,24 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         set_error(keep);
         return st;
     }
-    // The pipelined LD kernel serves rows of at most 6 entries; longer ones take an unoverlapped path there.
+    // LD kernel choice; the low-degree rows with more entries than the pipelined kernel has slots are the tail
+    // of the degree-sorted list
     {
         const int64_t n_ld = (int64_t)plan->ld_rows.size();
-        const int32_t short_deg = std::min<int32_t>(7, plan->threshold);
-        const int64_t n_short = plan->ld_deg_offsets.empty() ? 0 : plan->ld_deg_offsets[short_deg];
-        const int knob = tuning().ld_pipeline;
-        d.ld_pipelined = pipelined_by_default(knob, n_ld, n_short);
+        const std::vector<int64_t> &offs = plan->ld_deg_offsets;        // [d]: low-degree rows with fewer than d entries
+        auto at_most = [&](int32_t len) { return offs.empty() ? 0 : offs[std::min<int32_t>(len + 1, plan->threshold)]; };
+        const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most(6), at_most(8));
+        d.ld_pipelined = ch.pipelined;
+        d.pipe_depth = ch.depth;
+        const int64_t first_mid = at_most(ch.depth);
+        d.n_mid_rows = ch.pipelined ? n_ld - first_mid : 0;
+        if (d.n_mid_rows &&
+            (st = to_device(&d.mid_rows, plan->ld_rows_by_degree.data() + first_mid, (size_t)d.n_mid_rows, "long low-degree rows")) != GROOT_OK) {
+            std::string keep = groot_last_error();
+            release_device(plan);
+            set_error(keep);
+            return st;
+        }
     }
     d.n_chunks = (int64_t)plan->chunks.size();
     d.nnz_hd = 0;
@@ -1053,9 +1069,21 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
         d.n_split_rows = (int64_t)pl->split_rows.size();
         d.n_partials = pl->n_partials;
         {
-            const int64_t n_short = offs[std::min<int32_t>(7, T)];
-            const int knob = tuning().ld_pipeline;
-            d.ld_pipelined = pipelined_by_default(knob, n_ld, n_short);
+            auto at_most = [&](int32_t len) { return offs[std::min<int32_t>(len + 1, T)]; };
+            const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most(6), at_most(8));
+            d.ld_pipelined = ch.pipelined;
+            d.pipe_depth = ch.depth;
+            const int64_t first_mid = at_most(ch.depth);
+            d.n_mid_rows = ch.pipelined ? n_ld - first_mid : 0;
+            if (d.n_mid_rows) {             // the tail of the degree-sorted list, which is on the device already
+                if ((st = to_device<int32_t>(&d.mid_rows, nullptr, (size_t)d.n_mid_rows, "long low-degree rows")) != GROOT_OK ||
+                    (err = device_copy(d.mid_rows, by_degree.as<int32_t>() + first_mid, (size_t)d.n_mid_rows * 4, hip_stream))) {
+                    std::string keep = err ? std::string(who) + hip_error_text(err) : std::string(groot_last_error());
+                    release_device(pl.get());
+                    set_error(keep);
+                    return err ? GROOT_EHIP : st;
+                }
+            }
         }
         // the sub-graph moves into the plan
         d.rowptr = part->d.rowptr;
@@ -1115,6 +1143,8 @@ extern "C" groot_status groot_plan_query(const groot_plan *plan, const char *wha
     else if (k == "hd_pieces") *value = plan->dev.n_chunks;
     else if (k == "hd_partials") *value = plan->dev.n_partials;
     else if (k == "nnz_hd") *value = plan->dev.nnz_hd;
+    else if (k == "pipe_depth") *value = plan->dev.pipe_depth;
+    else if (k == "mid_rows") *value = plan->dev.n_mid_rows;
     else if (k == "csr_bytes" || k == "csr_bytes_ld" || k == "csr_bytes_hd") {
         // what the kernels read of the graph per execute: every row pointer and every entry's column index, the
         // entry's weight only when the kernels take the weights from the array; the HD kernel reads its pieces'
@@ -1134,6 +1164,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (!name) return fail(GROOT_EINVAL, "groot_set_tuning: NULL name");
     std::string k(name);
     if (k == "xcd_remap") { tuning().xcd_remap = value ? 1 : 0; return GROOT_OK; }
+    if (k == "ld_burst") {
+        if (value < 0 || value > 2) return fail(GROOT_EINVAL, "groot_set_tuning: ld_burst must be 0, 1 or 2");
+        tuning().ld_burst = (int)value;
+        return GROOT_OK;
+    }
     if (k == "ld_pipeline") {
         if (value < -1 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: ld_pipeline must be -1, 0 or 1");
         tuning().ld_pipeline = (int)value;

@@ -44,6 +44,7 @@ struct Tuning {
     std::atomic<int> sage_split{1};        // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
     std::atomic<int> sage_kernel{1};       // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
     std::atomic<int> uniform_detect{1};    // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
+    std::atomic<int> ld_burst{0};          // experiment: pipelined LD kernel with two register sets (1: 4 groups, 2: 3 groups)
     std::atomic<int> ld_pipeline{-1};      // pipelined LD kernel: 1 always (where it applies), 0 never, -1 by the row lengths
 };
 Tuning &tuning();
@@ -72,6 +73,9 @@ struct DevicePlan {
     int64_t n_cols = 0;             // rows of the feature matrix the columns index: n, or the whole graph's row
                                     // count once a part's plan reads the global matrix in place
     int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
+    int pipe_depth = 6;             // slots per row of the pipelined LD kernel: 6 or 8
+    int32_t *mid_rows = nullptr;    // low-degree rows with more than pipe_depth entries (the pipelined kernel
+    int64_t n_mid_rows = 0;         // masks them; a row-list kernel computes them), ordered by (length, id)
 };
 
 constexpr int kZeroRowFloats = 128;
@@ -130,6 +134,7 @@ int device_row_extents(const int64_t *rowptr_dev, const int32_t *rows_dev, int64
                        int64_t *end_host, void *stream);
 int device_gather_col(const int32_t *col_dev, const int64_t *idx_host, int64_t n_idx, int32_t *out_host, void *stream);
 int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream);
+int device_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream);   // device to device, synchronous
 const char *hip_error_text(int err);
 
 // Device memory helpers (groot_kernels.hip, so that the host file needs no HIP headers).

@@ -3,22 +3,25 @@
 //
 // One persistent workgroup of four wavefronts per CU, i.e. one wavefront per SIMD.  Every wavefront walks
 // its own tiles of G lane groups x (64 / L) rows (L = F / 4 lanes per row) and keeps a whole tile in
-// flight: G register sets of kPipeD gathered float4 each.  Right after the rows of a group of tile t have
-// been summed and stored, the same register set is loaded with the group's rows of tile t+1, so the
-// wavefront never waits with nothing in flight.  Compared with the plain LD kernel (32 wavefronts per CU,
-// four rows in flight each, all of them drained at every tile) this keeps fewer requests in flight per CU
-// (measured to be what the memory system of this chip prefers for this access pattern) and never lets
-// the stream of requests stop.
+// flight: G register sets of D gathered float4 each (D = 6 or 8 slots per row, chosen per plan).  Right
+// after the rows of a group of tile t have been summed and stored, the same register set is loaded with
+// the group's rows of tile t+1, so the wavefront never waits with nothing in flight.  Compared with the
+// plain LD kernel (32 wavefronts per CU, four rows in flight each, all of them drained at every tile) this
+// keeps fewer requests in flight per CU (measured to be what the memory system of this chip prefers for
+// this access pattern) and never lets the stream of requests stop.
 //
 // What makes the pipeline work (each item was a measured dead end without it):
-//  * All address arithmetic is done once per tile, lane-parallel: lane s prepares slot s = 6 r + k of a
+//  * All address arithmetic is done once per tile, lane-parallel: lane s prepares slot s = D r + k of a
 //    wavefront-private table in LDS (byte offset of the k-th neighbour of row r) from register shuffles of
 //    the CSR, which was loaded two tiles ahead (row pointers three).  A slot past a row's end points at a
-//    row of zeros outside X: the sum of a row is the plain sum of its kPipeD slots, in CSR order.
+//    row of zeros outside X: the sum of a row is the plain sum of its D slots, in CSR order.
 //  * The steady state has no branch and no conditional load or store, so the compiler's vmcnt waits are
-//    exact: the wait before a group's sum leaves the G-1 younger groups in flight.  The sums of a tile
-//    that is not "simple" (a row with more than kPipeD entries, a high-degree row, the ragged last tile)
-//    are stored to a trash area instead of Y, and the tile is then redone by a plain, unoverlapped path.
+//    exact: the wait before a group's sum leaves the G-1 younger groups in flight.  A row that does not
+//    fit (more than D entries, or a high-degree row) is masked: all its slots point at the zero row and
+//    its sum is stored to a trash area instead of Y (an address select, not a branch); the high-degree
+//    kernel, or the row-list kernel below for low-degree rows longer than D, computes it.  Only a tile
+//    whose entries exceed the wavefront's index registers (a run of high-degree rows) and the ragged last
+//    tile are masked as a whole and redone by a plain, unoverlapped path.
 //  * No workgroup barrier anywhere: wavefronts share nothing.
 #include <type_traits>
 
@@ -26,7 +29,6 @@
 
 namespace groot {
 
-constexpr int kPipeD = 6;                    // slots per row
 constexpr int kPipeWaves = 4;                // wavefronts per workgroup, one workgroup per CU
 
 __device__ __forceinline__ void pipe_wave_sync()
@@ -36,7 +38,7 @@ __device__ __forceinline__ void pipe_wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int L, int W, int G>
+template <int L, int W, int G, int D, int S = 1>
 __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void ld_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
@@ -44,7 +46,9 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
 {
     constexpr int kRpg = kWave / L;                      // rows per lane group sweep
     constexpr int kTileRows = G * kRpg;
+    constexpr int kPipeD = D;                            // slots per row
     constexpr int kSlots = kTileRows * kPipeD, kH = (kSlots + kWave - 1) / kWave;
+    constexpr int kCap = kH * kWave;                     // entries of a tile that the index registers hold
     constexpr int kRowShift = L == 8 ? 7 : L == 16 ? 8 : 9;   // log2 of a feature row's bytes
     static_assert(L == 8 || L == 16 || L == 32, "one float4 per lane");
     static_assert(kTileRows + 1 <= kWave, "row pointers of a tile fit one wavefront");
@@ -53,7 +57,7 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     struct SlotW { int64_t off; float w; float pad; };
     using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
     __shared__ __align__(16) Slot s_slot[kPipeWaves][kSlots];
-    __shared__ float s_inv[kPipeWaves][kTileRows];
+    __shared__ float s_inv[kPipeWaves][kTileRows];       // row weight (1 unless W == kMean), or -1: the row is masked
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int g = l / L, f = l % L;
@@ -72,17 +76,16 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     float vv[kH];
 #pragma unroll
     for (int h = 0; h < kH; ++h) { cc[h] = 0; vv[h] = 0.f; }
-    bool simple_a = false;
+    bool ok_a = false;
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kTileRows + (l < kTileRows ? l : kTileRows);
         return rowptr[ri < n ? ri : n];                  // lanes 0..kTileRows hold the pointers; rows past the end read rowptr[n]
     };
     auto load_cols = [&](int64_t tile) {                 // from rp_a
-        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kTileRows), rp_next = __shfl_down(rp_a, 1);
-        const int64_t len = rp_next - rp_a;
-        const bool full = (tile + 1) * kTileRows <= n && tile < x_end;
-        simple_a = full && __ballot(l < kTileRows && (len > kPipeD || len >= T)) == 0;
-        const int32_t m = simple_a ? (int32_t)(t_end - begin) : 0;          // <= kSlots
+        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kTileRows);
+        // a tile takes part in the pipeline when all its rows exist and its entries fit the index registers
+        ok_a = (tile + 1) * kTileRows <= n && tile < x_end && t_end - begin <= kCap;
+        const int32_t m = ok_a ? (int32_t)(t_end - begin) : 0;
         // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
 #pragma unroll
         for (int h = 0; h < kH; ++h) {
@@ -91,8 +94,8 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
         }
     };
-    auto stage = [&]() -> bool {                         // rp_a, cc, vv -> slot table; a tile that is not simple is staged as empty
-        const int32_t rel = simple_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
+    auto stage = [&]() -> bool {                         // rp_a, cc, vv -> slot table; a tile that is not ok is staged as empty
+        const int32_t rel = ok_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
 #pragma unroll
         for (int h = 0; h < kH; ++h) {
             const int s = l + kWave * h;                 // slot s: row r, entry k
@@ -110,7 +113,8 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
                     wt = (src >> 6) == q ? wq : wt;
                 }
             }
-            const bool live = k < hi - lo;
+            const int32_t len = hi - lo;
+            const bool live = k < len && len <= kPipeD && len < T;
             if (s < kSlots) {
                 const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
                 if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
@@ -118,9 +122,9 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             }
         }
         const int32_t len = __shfl_down(rel, 1) - rel;   // all lanes take part in the exchange
-        if (W == kMean && l < kTileRows) s_inv[w][l] = row_weight<kMean>(len);
+        if (l < kTileRows) s_inv[w][l] = ok_a && len <= kPipeD && len < T ? row_weight<W == kMean ? kMean : kOnes>(len) : -1.0f;
         pipe_wave_sync();
-        return simple_a;
+        return ok_a;
     };
 
     // ---- one group: kRpg rows, one per lane group
@@ -129,10 +133,10 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
         float ws[W == kExplicit ? kPipeD : 1];
         float inv;
     };
-    Regs rr[G];
+    Regs rr[S * G];
     auto issue = [&](Regs &q, int grp) {
         const int lr = grp * kRpg + g;
-        if (W == kMean) q.inv = s_inv[w][lr];
+        q.inv = s_inv[w][lr];
 #pragma unroll
         for (int k = 0; k < kPipeD; ++k) {
             if constexpr (W == kExplicit) {
@@ -155,10 +159,66 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
         return a;
     };
 
+    char *const tbase = trash + 16 * f;
+    if constexpr (S == 2) {
+        // ---- burst form: two tiles in flight in two register sets.  A tile's G sums are stored back to back,
+        //      then the set is refilled with the G x D gathers of the tile two steps on.
+        bool ok_set[2];
+        rp_a = load_rp(t_first);
+        load_cols(t_first);
+        ok_set[0] = stage();
+#pragma unroll
+        for (int grp = 0; grp < G; ++grp) issue(rr[grp], grp);
+        rp_a = load_rp(t_first + stride);
+        load_cols(t_first + stride);
+        ok_set[1] = stage();
+#pragma unroll
+        for (int grp = 0; grp < G; ++grp) issue(rr[G + grp], grp);
+        rp_a = load_rp(t_first + 2 * stride);
+        load_cols(t_first + 2 * stride);
+        rp_b = load_rp(t_first + 3 * stride);
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
+        for (int64_t tile0 = t_first; tile0 < x_end; tile0 += 2 * stride) {
+#pragma unroll
+            for (int set = 0; set < 2; ++set) {
+                const int64_t tile = tile0 + set * stride;
+                const int64_t base = tile * kTileRows;
+                char *const ybase = Y + (base << kRowShift) + 16 * f;
+#pragma unroll
+                for (int grp = 0; grp < G; ++grp) {
+                    const v4f a = sum(rr[set * G + grp]);
+                    const int roff = (grp * kRpg + g) << kRowShift;
+                    char *const dst = rr[set * G + grp].inv >= 0.f ? ybase + roff : tbase + roff;
+                    __builtin_nontemporal_store(a, (v4f *)dst);
+                }
+                const bool ok_new = stage();             // tile + 2 stride
+#pragma unroll
+                for (int grp = 0; grp < G; ++grp) issue(rr[set * G + grp], grp);
+                rp_a = rp_b;
+                load_cols(tile + 3 * stride);
+                rp_b = load_rp(tile + 4 * stride);
+                if (!ok_set[set] && tile < x_end) {
+#pragma unroll 1
+                    for (int grp = 0; grp < G; ++grp) {
+                        const int64_t row = base + grp * kRpg + g;
+                        if (row < n) {
+                            const int64_t s = rowptr[row], e = rowptr[row + 1];
+                            if (e - s < T && e - s <= kPipeD)
+                                __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, (const v4f *)X, L, f),
+                                                            (v4f *)(Y + (row << kRowShift) + 16 * f));
+                        }
+                    }
+                }
+                ok_set[set] = ok_new;
+            }
+        }
+        return;
+    }
+
     // ---- prologue: the first tile is staged and put in flight, the CSR of the next two is on its way
     rp_a = load_rp(t_first);
     load_cols(t_first);
-    bool simple_cur = stage();
+    bool ok_cur = stage();
     rp_a = load_rp(t_first + stride);
     load_cols(t_first + stride);
     rp_b = load_rp(t_first + 2 * stride);
@@ -169,33 +229,52 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
 
     for (int64_t tile = t_first; tile < x_end; tile += stride) {
-        const bool simple_next = stage();                // CSR of the next tile -> slot table (this tile's groups are all issued)
+        const bool ok_next = stage();                    // CSR of the next tile -> slot table (this tile's groups are all issued)
         rp_a = rp_b;
         load_cols(tile + 2 * stride);
         rp_b = load_rp(tile + 3 * stride);
         const int64_t base = tile * kTileRows;
-        char *const ybase = (simple_cur ? Y + (base << kRowShift) : trash) + 16 * f;
+        char *const ybase = Y + (base << kRowShift) + 16 * f;
 #pragma unroll
         for (int grp = 0; grp < G; ++grp) {
             const v4f a = sum(rr[grp]);
-            __builtin_nontemporal_store(a, (v4f *)(ybase + ((grp * kRpg + g) << kRowShift)));
+            const int roff = (grp * kRpg + g) << kRowShift;
+            // a masked row (every row of a tile that is not ok) goes to the trash area: a select, no branch
+            char *const dst = rr[grp].inv >= 0.f ? ybase + roff : tbase + roff;
+            __builtin_nontemporal_store(a, (v4f *)dst);
             issue(rr[grp], grp);                         // the same rows of the next tile
         }
-        if (!simple_cur) {
-            // plain path: the low-degree rows of this tile straight from global memory
+        if (!ok_cur) {
+            // plain path: the rows of this tile that the pipeline serves elsewhere, straight from global memory
 #pragma unroll 1
             for (int grp = 0; grp < G; ++grp) {
                 const int64_t row = base + grp * kRpg + g;
                 if (row < n) {
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
-                    if (e - s < T)
+                    if (e - s < T && e - s <= kPipeD)
                         __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, (const v4f *)X, L, f),
                                                     (v4f *)(Y + (row << kRowShift) + 16 * f));
                 }
             }
         }
-        simple_cur = simple_next;
+        ok_cur = ok_next;
     }
+}
+
+// Low-degree rows that are longer than the pipeline's slots, by list: one lane group per row.
+template <int L, int W>
+__global__ __launch_bounds__(kBlock) void ld_rows_kernel(const int32_t *__restrict__ rows, int64_t n_rows,
+                                                         const int64_t *__restrict__ rowptr,
+                                                         const int32_t *__restrict__ col, const float *__restrict__ val,
+                                                         const v4f *__restrict__ X, v4f *__restrict__ Y, int32_t F4)
+{
+    constexpr int G = kBlock / L;
+    const int64_t k = (int64_t)blockIdx.x * G + threadIdx.x / L;
+    if (k >= n_rows) return;
+    const int64_t row = rows[k];
+    const int64_t s = rowptr[row], e = rowptr[row + 1];
+    for (int32_t ff = threadIdx.x % L; ff < F4; ff += L)
+        __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, X, F4, ff), &Y[row * F4 + ff]);
 }
 
 struct PipeArgs {
@@ -214,20 +293,20 @@ struct PipeArgs {
     hipStream_t st;
 };
 
-template <int L, int W, int G>
+template <int L, int W, int G, int D, int S>
 static void pipe_launch(const PipeArgs &a)
 {
-    ld_pipe_kernel<L, W, G><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
+    ld_pipe_kernel<L, W, G, D, S><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
         a.rowptr, a.col, a.val, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part, a.waves_per_part,
         a.parts);
 }
 
-template <int W, int G>
+template <int W, int G, int D, int S = 1>
 static void pipe_dispatch_l(int32_t F4, const PipeArgs &a)
 {
-    if (F4 == 8) pipe_launch<8, W, G>(a);
-    else if (F4 == 16) pipe_launch<16, W, G>(a);
-    else pipe_launch<32, W, G>(a);
+    if (F4 == 8) pipe_launch<8, W, G, D, S>(a);
+    else if (F4 == 16) pipe_launch<16, W, G, D, S>(a);
+    else pipe_launch<32, W, G, D, S>(a);
 }
 
 int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
@@ -236,12 +315,17 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     const int32_t F4 = F / 4;
     if (F4 != 8 && F4 != 16 && F4 != 32) return (int)hipErrorInvalidValue;
     if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
+    if (dp.pipe_depth != 6 && dp.pipe_depth != 8) return (int)hipErrorInvalidValue;
+    if (dp.n_mid_rows && !dp.mid_rows) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return (int)e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
-    const int tile_rows = kG * (kWave / F4);
+    // experiment: the burst form (two register sets) for mean weights and 6 slots
+    const int burst = (dp.pipe_depth == 6 && dp.weight_mode == kMean) ? tuning().ld_burst.load() : 0;
+    const int groups = burst == 1 ? 4 : burst == 2 ? 3 : kG;
+    const int tile_rows = groups * (kWave / F4);
     const int64_t n_tiles = (dp.n + tile_rows - 1) / tile_rows;
     // one workgroup per CU; consecutive workgroup ids land on different XCDs
     int64_t n_wg = cus / kXcds * kXcds;
@@ -255,10 +339,26 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
+    static_assert(kG * kWave * 16 <= kTrashFloats * 4, "a tile's masked sums fit the trash area");
     hipStream_t st = (hipStream_t)stream;
     const PipeArgs a{dp.rowptr, col_arg, val_arg, (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
                      dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st};
-    GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG>(F4, a)));
+    if (burst == 1) pipe_dispatch_l<kMean, 4, 6, 2>(F4, a);
+    else if (burst == 2) pipe_dispatch_l<kMean, 3, 6, 2>(F4, a);
+    else if (dp.pipe_depth == 8) { GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG, 8>(F4, a))); }
+    else { GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG, 6>(F4, a))); }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess || dp.n_mid_rows == 0) return (int)err;
+    // the low-degree rows with more entries than the pipeline has slots
+    const int64_t grid = (dp.n_mid_rows + kBlock / F4 - 1) / (kBlock / F4);
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    GROOT_DISPATCH_W(dp.weight_mode,
+                     (F4 == 8 ? ld_rows_kernel<8, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                                    dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)
+                      : F4 == 16 ? ld_rows_kernel<16, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                                       dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)
+                                 : ld_rows_kernel<32, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
+                                       dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)));
     return (int)hipGetLastError();
 }
 

@@ -658,4 +658,13 @@ int device_download(void *dst_host, const void *src_dev, size_t bytes, void *str
     return (int)(err != hipSuccess ? err : err2);
 }
 
+int device_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream)
+{
+    if (!bytes) return 0;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t err = hipMemcpyAsync(dst_dev, src_dev, bytes, hipMemcpyDeviceToDevice, st);
+    hipError_t err2 = hipStreamSynchronize(st);
+    return (int)(err != hipSuccess ? err : err2);
+}
+
 }  // namespace groot

@@ -190,6 +190,36 @@ def test_stress_graph_threshold_sweep(torch_cuda, uniform_detect, T):
     assert_close_to_oracle(Y, Y64, S, f"stress T={T}")
 
 
+@pytest.mark.parametrize("max_len,T,F,explicit", [(14, 32, 64, False), (14, 9, 32, False), (10, 4, 128, True),
+                                                   (9, 32, 64, True), (40, 16, 64, False), (8, 32, 32, False)])
+def test_mixed_row_lengths(torch_cuda, max_len, T, F, explicit):
+    """Row lengths drawn uniformly from 0..max_len (empty rows included), 20,011 rows (a ragged last tile at every
+    width): in the pipelined kernel every tile mixes rows that fit its 6 or 8 slots, longer low-degree rows (masked
+    there, computed from the row list) and high-degree rows (masked, computed by the HD kernel); with max_len = 40 a
+    tile's entries can exceed the wavefront's index registers (the whole tile takes the plain path).  Weights
+    1 / row length (recomputed in the kernels) or arbitrary (read)."""
+    n = 20011
+    rng = np.random.default_rng(1000 + max_len + T + F)
+    deg = rng.integers(0, max_len + 1, size=n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(deg, out=rowptr[1:])
+    start = rng.integers(0, n, size=n)
+    col = np.concatenate([np.sort((start[i] + 37 * np.arange(deg[i])) % n) for i in range(n)]).astype(np.int32)
+    if explicit:
+        val = rng.uniform(-1.0, 1.0, col.shape[0]).astype(np.float32)
+    else:
+        val = np.repeat((np.float32(1.0) / np.maximum(deg, 1).astype(np.float32)), deg).astype(np.float32)
+    g = G.groot_graph_from_csr(rowptr, col, val)
+    X = wl.uniform_features_numpy(44, 0, n, F)
+    Y, plan, _, _ = _run(torch_cuda, g, T, X)
+    assert G.groot_plan_query(plan, "weight_mode") == (2 if explicit else 1)
+    if G.groot_plan_query(plan, "ld_pipelined"):
+        depth = G.groot_plan_query(plan, "pipe_depth")
+        assert G.groot_plan_query(plan, "mid_rows") == int(((deg > depth) & (deg < T)).sum())
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X)
+    assert_close_to_oracle(Y, Y64, S, f"mixed rows max_len={max_len} T={T} F={F}")
+
+
 @pytest.mark.parametrize("case", ["aig", "stress"])
 def test_transposed_spmm(torch_cuda, case):
     """dX = A_hat^T dY through groot_graph_transpose + the ordinary plan/execute, against the oracle's
