@@ -371,7 +371,7 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
 
 /* What the library decided for an uploaded plan, for diagnostics and benchmarks:
  * "ld_pipelined" (0 the plain LD kernel always, 2 the pipelined one for F = 32,
- * 64 and 128), "pipe_depth" (gather slots per row of the pipelined kernel, 6 or
+ * 64 and 128), "pipe_depth" (gather slots per row of the pipelined kernel, 5 to
  * 8), "mid_rows" (low-degree rows with more entries than that, which a row-list
  * kernel computes), "hd_pieces" (launch size of the HD kernel),
  * "hd_partials" (partial-sum slots of split high-degree rows), "weight_mode"
@@ -396,10 +396,13 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
  * "sage_split" (kernel 0 only: 1 bf16 piece products, 0 fp32 matrix
  * instructions), "sage_gap" (kernel 0 only: 0..4, the pause between its matrix
  * instructions; all three read at each call of groot_sage_layer_forward)
- * and "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
- * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one when at
- * most 2 low-degree rows in 100 have more entries than its 6, or else its 8,
- * gather slots per row; read by groot_plan_upload).
+ * "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
+ * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one with the
+ * smallest number of gather slots per row, 5 to 8, that leaves at most 2
+ * low-degree rows in 100 with more entries than slots, the plain one if none
+ * does; read by groot_plan_upload) and "pipe_depth" (0, default: that rule;
+ * 5..8: this many slots whenever the pipelined kernel is used; read by
+ * groot_plan_upload).
  * Unknown names give EINVAL.  Not needed for normal use. */
 groot_status groot_set_tuning(const char *name, int64_t value);
 

@@ -480,21 +480,27 @@ groot_status to_device(T **dst, const T *src, size_t count, const char *what)
 }  // namespace
 
 namespace {
-// Which LD kernel an uploaded plan uses, from the number of low-degree rows with at most 6 and at most 8 entries
-// (n_le6, n_le8 of n_ld).  The pipelined kernel gives every row 6 or 8 gather slots; a longer low-degree row is
-// masked there and computed by a row-list kernel (one lane group per row, nothing overlapped), so it pays as
-// long as such rows are few: at most 2 in 100 with 6 slots, else at most 2 in 100 with 8 slots, else the plain
-// kernel serves the graph.  -> DevicePlan::ld_pipelined (0 / 2), and the slot count
+// Which LD kernel an uploaded plan uses.  The pipelined kernel gives every row D gather slots and always issues
+// all D (a slot past the row's end reads a row of zeros), and a gather costs the same whether it hits a cache or
+// not (it is the per-CU return path of the vector memory unit that it occupies): so D should be as small as the
+// rows allow.  A low-degree row with more than D entries is masked there and computed by a row-list kernel (one
+// lane group per row, nothing overlapped), which is fine as long as such rows are few.  Rule: the smallest D in
+// kPipeMinDepth .. kPipeMaxDepth that leaves at most 2 low-degree rows in 100 to the row list; none does: the
+// plain kernel (or D = kPipeMaxDepth when the knob insists).  at_most(d) = low-degree rows with at most d entries.
+// -> DevicePlan::ld_pipelined (0 / 2), and the slot count
 struct PipeChoice {
     int pipelined;
     int depth;
 };
-PipeChoice choose_ld_kernel(int knob, int64_t n_ld, int64_t n_le6, int64_t n_le8)
+template <class AtMost>
+PipeChoice choose_ld_kernel(int knob, int64_t n_ld, AtMost at_most)
 {
-    if (knob == 0 || n_ld <= 0) return {0, 6};
-    if ((n_ld - n_le6) * 50 <= n_ld) return {2, 6};
-    if ((n_ld - n_le8) * 50 <= n_ld) return {2, 8};
-    return {knob > 0 ? 2 : 0, 8};
+    if (knob == 0 || n_ld <= 0) return {0, kPipeMaxDepth};
+    const int forced = tuning().pipe_depth;
+    if (forced >= kPipeMinDepth && forced <= kPipeMaxDepth) return {2, forced};
+    for (int d = kPipeMinDepth; d <= kPipeMaxDepth; ++d)
+        if ((n_ld - at_most(d)) * 50 <= n_ld) return {2, d};
+    return {knob > 0 ? 2 : 0, kPipeMaxDepth};
 }
 }  // namespace
 
@@ -562,7 +568,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         const int64_t n_ld = (int64_t)plan->ld_rows.size();
         const std::vector<int64_t> &offs = plan->ld_deg_offsets;        // [d]: low-degree rows with fewer than d entries
         auto at_most = [&](int32_t len) { return offs.empty() ? 0 : offs[std::min<int32_t>(len + 1, plan->threshold)]; };
-        const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most(6), at_most(8));
+        const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most);
         d.ld_pipelined = ch.pipelined;
         d.pipe_depth = ch.depth;
         const int64_t first_mid = at_most(ch.depth);
@@ -1070,7 +1076,7 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
         d.n_partials = pl->n_partials;
         {
             auto at_most = [&](int32_t len) { return offs[std::min<int32_t>(len + 1, T)]; };
-            const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most(6), at_most(8));
+            const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most);
             d.ld_pipelined = ch.pipelined;
             d.pipe_depth = ch.depth;
             const int64_t first_mid = at_most(ch.depth);
@@ -1164,9 +1170,10 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (!name) return fail(GROOT_EINVAL, "groot_set_tuning: NULL name");
     std::string k(name);
     if (k == "xcd_remap") { tuning().xcd_remap = value ? 1 : 0; return GROOT_OK; }
-    if (k == "ld_burst") {
-        if (value < 0 || value > 2) return fail(GROOT_EINVAL, "groot_set_tuning: ld_burst must be 0, 1 or 2");
-        tuning().ld_burst = (int)value;
+    if (k == "pipe_depth") {
+        if (value != 0 && (value < kPipeMinDepth || value > kPipeMaxDepth))
+            return fail(GROOT_EINVAL, "groot_set_tuning: pipe_depth must be 0 or 5..8");
+        tuning().pipe_depth = (int)value;
         return GROOT_OK;
     }
     if (k == "ld_pipeline") {

@@ -44,7 +44,7 @@ struct Tuning {
     std::atomic<int> sage_split{1};        // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
     std::atomic<int> sage_kernel{1};       // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
     std::atomic<int> uniform_detect{1};    // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
-    std::atomic<int> ld_burst{0};          // experiment: pipelined LD kernel with two register sets (1: 4 groups, 2: 3 groups)
+    std::atomic<int> pipe_depth{0};        // gather slots per row of the pipelined LD kernel: 0 the smallest that fits, or 5..8
     std::atomic<int> ld_pipeline{-1};      // pipelined LD kernel: 1 always (where it applies), 0 never, -1 by the row lengths
 };
 Tuning &tuning();
@@ -73,11 +73,12 @@ struct DevicePlan {
     int64_t n_cols = 0;             // rows of the feature matrix the columns index: n, or the whole graph's row
                                     // count once a part's plan reads the global matrix in place
     int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
-    int pipe_depth = 6;             // slots per row of the pipelined LD kernel: 6 or 8
+    int pipe_depth = 6;             // slots per row of the pipelined LD kernel: kPipeMinDepth .. kPipeMaxDepth
     int32_t *mid_rows = nullptr;    // low-degree rows with more than pipe_depth entries (the pipelined kernel
     int64_t n_mid_rows = 0;         // masks them; a row-list kernel computes them), ordered by (length, id)
 };
 
+constexpr int kPipeMinDepth = 5, kPipeMaxDepth = 8;   // gather slots per row the pipelined LD kernel is built for
 constexpr int kZeroRowFloats = 128;
 constexpr int kTrashFloats = 2048;
 constexpr int kRowsPerLdTile = 256;   // rows of one LD block (4 wavefronts x 64 rows)

@@ -11,17 +11,17 @@
 // this access pattern) and never lets the stream of requests stop.
 //
 // What makes the pipeline work (each item was a measured dead end without it):
-//  * All address arithmetic is done once per tile, lane-parallel: lane s prepares slot s = D r + k of a
-//    wavefront-private table in LDS (byte offset of the k-th neighbour of row r) from register shuffles of
-//    the CSR, which was loaded two tiles ahead (row pointers three).  A slot past a row's end points at a
-//    row of zeros outside X: the sum of a row is the plain sum of its D slots, in CSR order.
+//  * All address arithmetic is done once per tile, lane-parallel: lane s owns slot s = D r + k of a
+//    wavefront-private table in LDS (byte offset of the k-th neighbour of row r); it fetches that entry's
+//    column index itself, two tiles ahead, from the row pointers that arrived three tiles ahead (register
+//    shuffles hand every slot its row's extent).  A slot past a row's end points at a row of zeros outside
+//    X: the sum of a row is the plain sum of its D slots, in CSR order.
 //  * The steady state has no branch and no conditional load or store, so the compiler's vmcnt waits are
 //    exact: the wait before a group's sum leaves the G-1 younger groups in flight.  A row that does not
 //    fit (more than D entries, or a high-degree row) is masked: all its slots point at the zero row and
 //    its sum is stored to a trash area instead of Y (an address select, not a branch); the high-degree
-//    kernel, or the row-list kernel below for low-degree rows longer than D, computes it.  Only a tile
-//    whose entries exceed the wavefront's index registers (a run of high-degree rows) and the ragged last
-//    tile are masked as a whole and redone by a plain, unoverlapped path.
+//    kernel, or the row-list kernel below for low-degree rows longer than D, computes it.  Only the ragged
+//    last tile is masked as a whole and redone by a plain, unoverlapped path.
 //  * No workgroup barrier anywhere: wavefronts share nothing.
 #include <type_traits>
 
@@ -30,6 +30,7 @@
 namespace groot {
 
 constexpr int kPipeWaves = 4;                // wavefronts per workgroup, one workgroup per CU
+constexpr int kPipeGroups = 5;               // lane-group sweeps (register sets) in flight per wavefront (measured best of 2..8)
 
 __device__ __forceinline__ void pipe_wave_sync()
 {
@@ -38,7 +39,7 @@ __device__ __forceinline__ void pipe_wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int L, int W, int G, int D, int S = 1>
+template <int L, int W, int G, int D>
 __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void ld_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
@@ -48,7 +49,6 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     constexpr int kTileRows = G * kRpg;
     constexpr int kPipeD = D;                            // slots per row
     constexpr int kSlots = kTileRows * kPipeD, kH = (kSlots + kWave - 1) / kWave;
-    constexpr int kCap = kH * kWave;                     // entries of a tile that the index registers hold
     constexpr int kRowShift = L == 8 ? 7 : L == 16 ? 8 : 9;   // log2 of a feature row's bytes
     static_assert(L == 8 || L == 16 || L == 32, "one float4 per lane");
     static_assert(kTileRows + 1 <= kWave, "row pointers of a tile fit one wavefront");
@@ -77,52 +77,46 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
 #pragma unroll
     for (int h = 0; h < kH; ++h) { cc[h] = 0; vv[h] = 0.f; }
     bool ok_a = false;
+    int32_t len_a = 0;                                   // lanes 0..kTileRows-1: stored length of the tile's row
+    uint32_t live_a = 0;                                 // bit h: slot l + 64 h holds an entry
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kTileRows + (l < kTileRows ? l : kTileRows);
         return rowptr[ri < n ? ri : n];                  // lanes 0..kTileRows hold the pointers; rows past the end read rowptr[n]
     };
-    auto load_cols = [&](int64_t tile) {                 // from rp_a
-        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kTileRows);
-        // a tile takes part in the pipeline when all its rows exist and its entries fit the index registers
-        ok_a = (tile + 1) * kTileRows <= n && tile < x_end && t_end - begin <= kCap;
-        const int32_t m = ok_a ? (int32_t)(t_end - begin) : 0;
-        // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
-#pragma unroll
-        for (int h = 0; h < kH; ++h) {
-            const int64_t i = l + kWave * h < m ? begin + l + kWave * h : 0;
-            cc[h] = __builtin_nontemporal_load(&col[i]);
-            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
-        }
-    };
-    auto stage = [&]() -> bool {                         // rp_a, cc, vv -> slot table; a tile that is not ok is staged as empty
-        const int32_t rel = ok_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
+    auto load_cols = [&](int64_t tile) {                 // from rp_a: every slot fetches its own entry
+        // a tile takes part in the pipeline when all its rows exist; a row that does not fit its slots (too long,
+        // or high-degree) has no live slot, whatever its length: it does not disturb the rows around it
+        ok_a = (tile + 1) * kTileRows <= n && tile < x_end;
+        const int64_t begin = __shfl(rp_a, 0);
+        const int32_t rel = ok_a ? (int32_t)(rp_a - begin) : 0;
+        len_a = __shfl_down(rel, 1) - rel;
+        live_a = 0;
+        // unconditional loads (a dead slot reads entry 0): the number of loads in flight stays known
 #pragma unroll
         for (int h = 0; h < kH; ++h) {
             const int s = l + kWave * h;                 // slot s: row r, entry k
             const int r = s / kPipeD, k = s - r * kPipeD;
-            const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
-            const int src = lo + k;
-            int32_t c = 0;
-            float wt = 0.f;
+            const int32_t lo = __shfl(rel, r), len = __shfl(rel, r + 1) - lo;
+            const bool live = s < kSlots && k < len && len <= kPipeD && len < T;
+            live_a |= (uint32_t)live << h;
+            const int64_t i = live ? begin + lo + k : 0;
+            cc[h] = __builtin_nontemporal_load(&col[i]);
+            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
+        }
+    };
+    auto stage = [&]() -> bool {                         // cc, vv, live_a, len_a -> slot table and row weights
 #pragma unroll
-            for (int q = 0; q < kH; ++q) {
-                const int32_t cq = __shfl(cc[q], src - kWave * q);
-                c = (src >> 6) == q ? cq : c;
-                if (W == kExplicit) {
-                    const float wq = __shfl(vv[q], src - kWave * q);
-                    wt = (src >> 6) == q ? wq : wt;
-                }
-            }
-            const int32_t len = hi - lo;
-            const bool live = k < len && len <= kPipeD && len < T;
+        for (int h = 0; h < kH; ++h) {
+            const int s = l + kWave * h;
+            const bool live = (live_a >> h) & 1;
             if (s < kSlots) {
-                const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
-                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
+                const int64_t off = live ? ((int64_t)cc[h] << kRowShift) : zero_off;
+                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? vv[h] : 0.f, 0.f};
                 else s_slot[w][s] = off;
             }
         }
-        const int32_t len = __shfl_down(rel, 1) - rel;   // all lanes take part in the exchange
-        if (l < kTileRows) s_inv[w][l] = ok_a && len <= kPipeD && len < T ? row_weight<W == kMean ? kMean : kOnes>(len) : -1.0f;
+        if (l < kTileRows)
+            s_inv[w][l] = ok_a && len_a <= kPipeD && len_a < T ? row_weight<W == kMean ? kMean : kOnes>(len_a) : -1.0f;
         pipe_wave_sync();
         return ok_a;
     };
@@ -133,7 +127,7 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
         float ws[W == kExplicit ? kPipeD : 1];
         float inv;
     };
-    Regs rr[S * G];
+    Regs rr[G];
     auto issue = [&](Regs &q, int grp) {
         const int lr = grp * kRpg + g;
         q.inv = s_inv[w][lr];
@@ -160,61 +154,6 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     };
 
     char *const tbase = trash + 16 * f;
-    if constexpr (S == 2) {
-        // ---- burst form: two tiles in flight in two register sets.  A tile's G sums are stored back to back,
-        //      then the set is refilled with the G x D gathers of the tile two steps on.
-        bool ok_set[2];
-        rp_a = load_rp(t_first);
-        load_cols(t_first);
-        ok_set[0] = stage();
-#pragma unroll
-        for (int grp = 0; grp < G; ++grp) issue(rr[grp], grp);
-        rp_a = load_rp(t_first + stride);
-        load_cols(t_first + stride);
-        ok_set[1] = stage();
-#pragma unroll
-        for (int grp = 0; grp < G; ++grp) issue(rr[G + grp], grp);
-        rp_a = load_rp(t_first + 2 * stride);
-        load_cols(t_first + 2 * stride);
-        rp_b = load_rp(t_first + 3 * stride);
-        __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0)
-        for (int64_t tile0 = t_first; tile0 < x_end; tile0 += 2 * stride) {
-#pragma unroll
-            for (int set = 0; set < 2; ++set) {
-                const int64_t tile = tile0 + set * stride;
-                const int64_t base = tile * kTileRows;
-                char *const ybase = Y + (base << kRowShift) + 16 * f;
-#pragma unroll
-                for (int grp = 0; grp < G; ++grp) {
-                    const v4f a = sum(rr[set * G + grp]);
-                    const int roff = (grp * kRpg + g) << kRowShift;
-                    char *const dst = rr[set * G + grp].inv >= 0.f ? ybase + roff : tbase + roff;
-                    __builtin_nontemporal_store(a, (v4f *)dst);
-                }
-                const bool ok_new = stage();             // tile + 2 stride
-#pragma unroll
-                for (int grp = 0; grp < G; ++grp) issue(rr[set * G + grp], grp);
-                rp_a = rp_b;
-                load_cols(tile + 3 * stride);
-                rp_b = load_rp(tile + 4 * stride);
-                if (!ok_set[set] && tile < x_end) {
-#pragma unroll 1
-                    for (int grp = 0; grp < G; ++grp) {
-                        const int64_t row = base + grp * kRpg + g;
-                        if (row < n) {
-                            const int64_t s = rowptr[row], e = rowptr[row + 1];
-                            if (e - s < T && e - s <= kPipeD)
-                                __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, (const v4f *)X, L, f),
-                                                            (v4f *)(Y + (row << kRowShift) + 16 * f));
-                        }
-                    }
-                }
-                ok_set[set] = ok_new;
-            }
-        }
-        return;
-    }
-
     // ---- prologue: the first tile is staged and put in flight, the CSR of the next two is on its way
     rp_a = load_rp(t_first);
     load_cols(t_first);
@@ -293,39 +232,47 @@ struct PipeArgs {
     hipStream_t st;
 };
 
-template <int L, int W, int G, int D, int S>
+template <int L, int W, int G, int D>
 static void pipe_launch(const PipeArgs &a)
 {
-    ld_pipe_kernel<L, W, G, D, S><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
+    ld_pipe_kernel<L, W, G, D><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
         a.rowptr, a.col, a.val, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part, a.waves_per_part,
         a.parts);
 }
 
-template <int W, int G, int D, int S = 1>
+template <int W, int G, int D>
 static void pipe_dispatch_l(int32_t F4, const PipeArgs &a)
 {
-    if (F4 == 8) pipe_launch<8, W, G, D, S>(a);
-    else if (F4 == 16) pipe_launch<16, W, G, D, S>(a);
-    else pipe_launch<32, W, G, D, S>(a);
+    if (F4 == 8) pipe_launch<8, W, G, D>(a);
+    else if (F4 == 16) pipe_launch<16, W, G, D>(a);
+    else pipe_launch<32, W, G, D>(a);
+}
+
+template <int W>
+static void pipe_dispatch_d(int depth, int32_t F4, const PipeArgs &a)
+{
+    constexpr int kG = kPipeGroups;
+    switch (depth) {
+    case 5: pipe_dispatch_l<W, kG, 5>(F4, a); break;
+    case 6: pipe_dispatch_l<W, kG, 6>(F4, a); break;
+    case 7: pipe_dispatch_l<W, kG, 7>(F4, a); break;
+    default: pipe_dispatch_l<W, kG, 8>(F4, a); break;
+    }
 }
 
 int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
 {
-    constexpr int kG = 5;                                // groups in flight per wavefront (13.7 / 14.0 / 13.8 ms for 5 / 6 / 7)
     const int32_t F4 = F / 4;
     if (F4 != 8 && F4 != 16 && F4 != 32) return (int)hipErrorInvalidValue;
     if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
-    if (dp.pipe_depth != 6 && dp.pipe_depth != 8) return (int)hipErrorInvalidValue;
+    if (dp.pipe_depth < kPipeMinDepth || dp.pipe_depth > kPipeMaxDepth) return (int)hipErrorInvalidValue;
     if (dp.n_mid_rows && !dp.mid_rows) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return (int)e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
-    // experiment: the burst form (two register sets) for mean weights and 6 slots
-    const int burst = (dp.pipe_depth == 6 && dp.weight_mode == kMean) ? tuning().ld_burst.load() : 0;
-    const int groups = burst == 1 ? 4 : burst == 2 ? 3 : kG;
-    const int tile_rows = groups * (kWave / F4);
+    const int tile_rows = kPipeGroups * (kWave / F4);
     const int64_t n_tiles = (dp.n + tile_rows - 1) / tile_rows;
     // one workgroup per CU; consecutive workgroup ids land on different XCDs
     int64_t n_wg = cus / kXcds * kXcds;
@@ -339,14 +286,11 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
-    static_assert(kG * kWave * 16 <= kTrashFloats * 4, "a tile's masked sums fit the trash area");
+    static_assert(kPipeGroups * kWave * 16 <= kTrashFloats * 4, "a tile's masked sums fit the trash area");
     hipStream_t st = (hipStream_t)stream;
     const PipeArgs a{dp.rowptr, col_arg, val_arg, (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
                      dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st};
-    if (burst == 1) pipe_dispatch_l<kMean, 4, 6, 2>(F4, a);
-    else if (burst == 2) pipe_dispatch_l<kMean, 3, 6, 2>(F4, a);
-    else if (dp.pipe_depth == 8) { GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG, 8>(F4, a))); }
-    else { GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_l<kW, kG, 6>(F4, a))); }
+    GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_d<kW>(dp.pipe_depth, F4, a)));
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || dp.n_mid_rows == 0) return (int)err;
     // the low-degree rows with more entries than the pipeline has slots

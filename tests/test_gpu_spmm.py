@@ -194,9 +194,9 @@ def test_stress_graph_threshold_sweep(torch_cuda, uniform_detect, T):
                                                    (9, 32, 64, True), (40, 16, 64, False), (8, 32, 32, False)])
 def test_mixed_row_lengths(torch_cuda, max_len, T, F, explicit):
     """Row lengths drawn uniformly from 0..max_len (empty rows included), 20,011 rows (a ragged last tile at every
-    width): in the pipelined kernel every tile mixes rows that fit its 6 or 8 slots, longer low-degree rows (masked
-    there, computed from the row list) and high-degree rows (masked, computed by the HD kernel); with max_len = 40 a
-    tile's entries can exceed the wavefront's index registers (the whole tile takes the plain path).  Weights
+    width): in the pipelined kernel every tile mixes rows that fit its 5 to 8 slots, longer low-degree rows (masked
+    there, computed from the row list) and high-degree rows (masked, computed by the HD kernel); with max_len = 40
+    most low-degree rows are longer than any slot count (the knob still forces the pipelined kernel).  Weights
     1 / row length (recomputed in the kernels) or arbitrary (read)."""
     n = 20011
     rng = np.random.default_rng(1000 + max_len + T + F)
