@@ -60,7 +60,7 @@ TRAFFIC = {
     ("csa1024_b16_F64", "ld_kernel"): {"bytes": 80.52e9, "read": 46.20e9, "written": 34.32e9,
                                        "sources_sha16": "unstamped (measured before stamping was introduced)"},
 }
-KERNEL_SOURCES = ("groot_device.h", "groot_internal.h", "groot_kernels.hip", "groot_ld_pipe.hip")
+KERNEL_SOURCES = ("groot_device.h", "groot_internal.h", "groot_kernels.hip", "groot_ld_pipe.hip", "groot_compress.hip")
 
 
 def kernel_sources_sha16():

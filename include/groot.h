@@ -207,22 +207,32 @@ groot_status groot_plan_use_global_columns(groot_plan *plan, const int64_t *glob
  * the graph with node features and aggregates them; the aggregation is the product
  * the paper's kernels compute).  The aggregated rows stay on chip and feed the dense
  * products on the matrix cores, so A_hat X is neither written nor re-read.
- * X_dev, H_dev (device): row-major [N,F] fp32, 16-byte aligned, not overlapping.
- * Wn_dev, Ws_dev (device): row-major [F,F] fp32 (input feature major: H = X W);
- * bias_dev: [F] fp32 or NULL.  F (input = output width) must be 64, or 32 for graphs
- * with row-uniform weights (every graph built from an AIG).  fp32 in and out,
+ * X_dev (device): row-major [N,F_in] fp32; H_dev (device): row-major [N,F_out] fp32;
+ * both 16-byte aligned, not overlapping.
+ * Wn_dev, Ws_dev (device): row-major [F_in,F_out] fp32 (input feature major: H = X W);
+ * bias_dev: [F_out] fp32 or NULL.
+ * groot_sage_layer_forward_io: F_in = 32 or 64, F_out = 16, 32 or 64 for graphs with
+ * row-uniform weights (every graph built from an AIG: a classifier that narrows or
+ * widens from layer to layer; pad a narrower input or a class count with zero
+ * columns / zero weights up to the next supported width); graphs with explicit
+ * weights: 64 -> 64 only.  groot_sage_layer_forward is the same call with
+ * F_in = F_out = F (64 or 32).  fp32 in and out,
  * fp32 sums; a dense product is formed on the matrix cores from three bf16 pieces per
  * fp32 operand (six piece products, fp32 accumulation), which keeps the relative error
  * of a product below 2^-23, as an fp32 multiplication does (the pieces have the
  * exponent range of fp32; an input above 3.38e38 in magnitude rounds to infinity in
  * its first piece and gives NaN).
- * The plan must be uploaded with max_F >= F.  Only enqueues on hip_stream; one
- * call per plan in flight.  Errors: EINVAL (NULL, alignment, unsupported F, plan not
+ * The plan must be uploaded with max_F >= F_in.  Only enqueues on hip_stream; one
+ * call per plan in flight (the aggregated high-degree rows pass through a buffer of
+ * the plan).  Errors: EINVAL (NULL, alignment, unsupported widths, plan not
  * uploaded), EHIP.
  * ------------------------------------------------------------------------- */
 groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
                                       const float *Ws_dev, const float *bias_dev, int32_t relu,
                                       float *H_dev, int32_t F, void *hip_stream);
+groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
+                                         const float *Ws_dev, const float *bias_dev, int32_t relu,
+                                         float *H_dev, int32_t F_in, int32_t F_out, void *hip_stream);
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------
@@ -373,7 +383,8 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
  * "ld_pipelined" (0 the plain LD kernel always, 2 the pipelined one for F = 32,
  * 64 and 128), "pipe_depth" (gather slots per row of the pipelined kernel, 5 to
  * 8), "mid_rows" (low-degree rows with more entries than that, which a row-list
- * kernel computes), "hd_pieces" (launch size of the HD kernel),
+ * kernel computes), "csr_compressed" (1 when the pipelined kernel reads 4-byte
+ * row pointers and 2-byte column codes instead of the 8- and 4-byte arrays), "hd_pieces" (launch size of the HD kernel),
  * "hd_partials" (partial-sum slots of split high-degree rows), "weight_mode"
  * (how the kernels take the weights: 0 all 1, 1 fl(1 / row length) recomputed
  * from the row pointer, 2 read from the weight array), "nnz_hd" (stored entries
@@ -396,6 +407,11 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
  * "sage_split" (kernel 0 only: 1 bf16 piece products, 0 fp32 matrix
  * instructions), "sage_gap" (kernel 0 only: 0..4, the pause between its matrix
  * instructions; all three read at each call of groot_sage_layer_forward)
+ * "csr_compress" (1, default: groot_plan_upload also builds a compact copy of
+ * the matrix for the pipelined LD kernel, 4-byte row pointers and 2-byte column
+ * codes, when every entry of a short row lies within 16,384 rows of its own row
+ * or names one of the first 32,768 high-degree rows, and the matrix has fewer
+ * than 2^32 entries; 0: never),
  * "ld_pipeline" (which LD kernel is used: 1 the software-pipelined one for
  * F = 32, 64, 128; 0 the plain one; -1 (default) the pipelined one with the
  * smallest number of gather slots per row, 5 to 8, that leaves at most 2

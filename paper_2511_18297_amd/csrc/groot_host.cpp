@@ -456,6 +456,8 @@ void release_device(groot_plan *pl)
     DevicePlan &d = pl->dev;
     dev_free(d.rowptr); dev_free(d.col); dev_free(d.val);
     dev_free(d.chunks); dev_free(d.split_rows); dev_free(d.partials); dev_free(d.zero_row); dev_free(d.mid_rows);
+    dev_free(d.rp32); dev_free(d.col16); dev_free(d.hot_cols);
+    dev_free(d.hd_rows); dev_free(d.hd_agg); dev_free(d.chunks_rank); dev_free(d.split_rows_rank);
     d = DevicePlan{};
     pl->resident = false;
 }
@@ -501,6 +503,37 @@ PipeChoice choose_ld_kernel(int knob, int64_t n_ld, AtMost at_most)
     for (int d = kPipeMinDepth; d <= kPipeMaxDepth; ++d)
         if ((n_ld - at_most(d)) * 50 <= n_ld) return {2, d};
     return {knob > 0 ? 2 : 0, kPipeMaxDepth};
+}
+}  // namespace
+
+namespace {
+// The fused layer's side of the high-degree rows (see DevicePlan): the HD schedule with rows renamed to their
+// place in hd_rows (ascending ids), and the buffer their aggregated features go to.  hd_rows_dev: the list on the
+// device already (a plan built there), else NULL and the host list is uploaded.
+groot_status upload_layer_hd_side(groot_plan *pl, const int32_t *hd_rows_host, int64_t n_hd, const int32_t *hd_rows_dev,
+                                  int32_t max_F, void *stream, const char *who)
+{
+    DevicePlan &d = pl->dev;
+    d.n_hd_rows = n_hd;
+    if (n_hd == 0) return GROOT_OK;
+    auto rank_of = [&](int32_t row) {
+        return (int32_t)(std::lower_bound(hd_rows_host, hd_rows_host + n_hd, row) - hd_rows_host);
+    };
+    std::vector<HdChunk> chunks(pl->chunks);
+    for (HdChunk &ch : chunks) ch.row = rank_of(ch.row);
+    std::vector<HdSplitRow> split(pl->split_rows);
+    for (HdSplitRow &sr : split) sr.row = rank_of(sr.row);
+    groot_status st;
+    if ((st = to_device(&d.chunks_rank, chunks.data(), chunks.size(), "HD schedule of the fused layer")) != GROOT_OK ||
+        (st = to_device(&d.split_rows_rank, split.data(), split.size(), "HD split rows of the fused layer")) != GROOT_OK ||
+        (st = to_device<float>(&d.hd_agg, nullptr, (size_t)n_hd * max_F, "high-degree sums of the fused layer")) != GROOT_OK ||
+        (st = to_device(&d.hd_rows, hd_rows_dev ? nullptr : hd_rows_host, (size_t)n_hd, "high-degree row list")) != GROOT_OK)
+        return st;
+    if (hd_rows_dev) {
+        int err = device_copy(d.hd_rows, hd_rows_dev, (size_t)n_hd * 4, stream);
+        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+    }
+    return GROOT_OK;
 }
 }  // namespace
 
@@ -581,6 +614,30 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
             return st;
         }
     }
+    // compact CSR for the pipelined kernel (4-byte row pointers, 2-byte column codes), when the graph allows it
+    if (d.ld_pipelined && tuning().csr_compress) {
+        int32_t *hd_dev = nullptr;
+        if ((st = to_device(&hd_dev, plan->hd_rows.data(), plan->hd_rows.size(), "high-degree row list")) != GROOT_OK) {
+            std::string keep = groot_last_error();
+            release_device(plan);
+            set_error(keep);
+            return st;
+        }
+        int err = launch_csr_compress(d, hd_dev, (int64_t)plan->hd_rows.size(), nullptr);
+        dev_free(hd_dev);
+        if (!err && d.compressed) err = pipe_compact_prepare();
+        if (err) {
+            release_device(plan);
+            return fail(GROOT_EHIP, std::string("groot_plan_upload: compact CSR: ") + hip_error_text(err));
+        }
+    }
+    if ((st = upload_layer_hd_side(plan, plan->hd_rows.data(), (int64_t)plan->hd_rows.size(), nullptr, max_F, nullptr,
+                                   "groot_plan_upload: ")) != GROOT_OK) {
+        std::string keep = groot_last_error();
+        release_device(plan);
+        set_error(keep);
+        return st;
+    }
     d.n_chunks = (int64_t)plan->chunks.size();
     d.nnz_hd = 0;
     for (const HdChunk &ch : plan->chunks) d.nnz_hd += ch.len;
@@ -646,34 +703,52 @@ extern "C" groot_status groot_spmm_execute(const groot_plan *plan, const float *
     return groot_spmm_execute_phases(plan, X_dev, Y_dev, F, GROOT_PHASE_ALL, hip_stream);
 }
 
+extern "C" groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
+                                                    const float *Ws_dev, const float *bias_dev, int32_t relu,
+                                                    float *H_dev, int32_t F_in, int32_t F_out, void *hip_stream)
+{
+    const char *who = "groot_sage_layer_forward: ";
+    if (!plan) return fail(GROOT_EINVAL, std::string(who) + "NULL plan");
+    if ((F_in != 64 && F_in != 32) || (F_out != 64 && F_out != 32 && F_out != 16))
+        return fail(GROOT_EINVAL, std::string(who) + "input width must be 32 or 64, output width 16, 32 or 64");
+    const bool wavefronts = plan->resident && tuning().sage_kernel && plan->dev.weight_mode != (int)WeightMode::Explicit;
+    if ((F_in != 64 || F_out != 64) && plan->resident && !wavefronts)
+        return fail(GROOT_EINVAL, std::string(who) + "widths other than 64 -> 64 need row-uniform weights (and the default layer kernel)");
+    groot_status st = check_features("groot_sage_layer_forward", X_dev, H_dev, F_in);
+    if (st != GROOT_OK) return st;
+    if (!Wn_dev || !Ws_dev) return fail(GROOT_EINVAL, std::string(who) + "NULL weight pointer");
+    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "plan is not on the device (call groot_plan_upload)");
+    if (F_in > plan->max_F) return fail(GROOT_EINVAL, std::string(who) + "the input width exceeds the max_F given to groot_plan_upload");
+    if (plan->dev.n_cols != plan->dev.n)
+        return fail(GROOT_EINVAL, std::string(who) + "the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
+    const char *a = (const char *)X_dev, *b = (const char *)H_dev;
+    const int64_t x_bytes = plan->dev.n * (int64_t)F_in * 4, h_bytes = plan->dev.n * (int64_t)F_out * 4;
+    if (a < b + h_bytes && b < a + x_bytes) return fail(GROOT_EINVAL, std::string(who) + "X and H overlap");
+    int err = 0;
+    if (wavefronts) {
+        // high-degree rows: their aggregation goes to the plan's side buffer, the layer kernel picks it up there
+        DevicePlan hd = plan->dev;
+        hd.chunks = plan->dev.chunks_rank;
+        hd.split_rows = plan->dev.split_rows_rank;
+        if (hd.n_chunks) err = launch_hd(hd, X_dev, hd.hd_agg, F_in, hip_stream);
+        if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F_in, hip_stream);
+        if (!err) err = launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F_in, F_out, hip_stream);
+    } else {
+        // the kernel for explicit weights (64 -> 64): high-degree sums go to H first and are picked up from there
+        if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F_in, hip_stream);
+        if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, H_dev, F_in, hip_stream);
+        if (!err) err = launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
+    }
+    if (err) return fail(GROOT_EHIP, std::string(who) + "launch failed: " + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
                                                  const float *Ws_dev, const float *bias_dev, int32_t relu,
                                                  float *H_dev, int32_t F, void *hip_stream)
 {
-    if (!plan) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL plan");
     if (F != 64 && F != 32) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F must be 64 or 32");
-    const bool wavefronts = plan->resident && tuning().sage_kernel && plan->dev.weight_mode != (int)WeightMode::Explicit;
-    if (F == 32 && plan->resident && !wavefronts)
-        return fail(GROOT_EINVAL, "groot_sage_layer_forward: F = 32 needs row-uniform weights (and the default layer kernel)");
-    groot_status st = check_features("groot_sage_layer_forward", X_dev, H_dev, F);
-    if (st != GROOT_OK) return st;
-    if (!Wn_dev || !Ws_dev) return fail(GROOT_EINVAL, "groot_sage_layer_forward: NULL weight pointer");
-    if (!plan->resident) return fail(GROOT_EINVAL, "groot_sage_layer_forward: plan is not on the device (call groot_plan_upload)");
-    if (F > plan->max_F) return fail(GROOT_EINVAL, "groot_sage_layer_forward: F exceeds the max_F given to groot_plan_upload");
-    if (plan->dev.n_cols != plan->dev.n)
-        return fail(GROOT_EINVAL, "groot_sage_layer_forward: the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
-    const char *a = (const char *)X_dev, *b = (const char *)H_dev;
-    const int64_t bytes = plan->dev.n * (int64_t)F * 4;
-    if (a < b + bytes && b < a + bytes) return fail(GROOT_EINVAL, "groot_sage_layer_forward: X and H overlap");
-    // high-degree rows: their aggregation goes to H first, the layer kernel picks it up from there
-    int err = 0;
-    if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F, hip_stream);
-    if (!err && plan->dev.n_split_rows) err = launch_hd_finish(plan->dev, H_dev, F, hip_stream);
-    if (!err)
-        err = wavefronts ? launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F, hip_stream)
-                                   : launch_sage(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, hip_stream);
-    if (err) return fail(GROOT_EHIP, std::string("groot_sage_layer_forward: launch failed: ") + hip_error_text(err));
-    return GROOT_OK;
+    return groot_sage_layer_forward_io(plan, X_dev, Wn_dev, Ws_dev, bias_dev, relu, H_dev, F, F, hip_stream);
 }
 
 extern "C" groot_status groot_plan_lists_device(const groot_plan *plan, uint8_t *row_class_dev, int32_t *hd_rows_dev,
@@ -725,6 +800,8 @@ extern "C" groot_status groot_plan_use_global_columns(groot_plan *plan, const in
     if (plan->dev.n_cols != plan->dev.n) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: the columns were renamed before");
     if (n_global < plan->dev.n) return fail(GROOT_EINVAL, "groot_plan_use_global_columns: n_global is smaller than the plan's own row count");
     if (n_global > std::numeric_limits<int32_t>::max()) return fail(GROOT_ERANGE, "groot_plan_use_global_columns: n_global does not fit int32 columns");
+    // the compact column codes name local rows: the plan goes back to the plain arrays
+    plan->dev.compressed = 0;
     int err = launch_col_map(plan->dev.col, plan->dev.nnz, global_id_dev, hip_stream);
     if (err) return fail(GROOT_EHIP, std::string("groot_plan_use_global_columns: launch failed: ") + hip_error_text(err));
     plan->dev.n_cols = n_global;
@@ -1063,6 +1140,12 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
             set_error(keep);
             return st;
         }
+        if ((st = upload_layer_hd_side(pl.get(), rows.data(), n_hd, hd_rows.as<int32_t>(), max_F, hip_stream, who)) != GROOT_OK) {
+            std::string keep = groot_last_error();
+            release_device(pl.get());
+            set_error(keep);
+            return st;
+        }
         d.n = d.n_cols = n;
         d.nnz = part->d.nnz;
         d.threshold = T;
@@ -1099,6 +1182,14 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
         part->d.col = nullptr;
         part->d.val = nullptr;
         part->csr_moved = true;
+        if (d.ld_pipelined && tuning().csr_compress) {
+            err = launch_csr_compress(d, hd_rows.as<int32_t>(), n_hd, hip_stream);
+            if (!err && d.compressed) err = pipe_compact_prepare();
+            if (err) {
+                release_device(pl.get());               // the sub-graph's arrays are the plan's by now
+                return fail(GROOT_EHIP, std::string(who) + "compact CSR: " + hip_error_text(err));
+            }
+        }
         pl->g = nullptr;
         pl->threshold = T;
         pl->max_F = max_F;
@@ -1150,14 +1241,20 @@ extern "C" groot_status groot_plan_query(const groot_plan *plan, const char *wha
     else if (k == "hd_partials") *value = plan->dev.n_partials;
     else if (k == "nnz_hd") *value = plan->dev.nnz_hd;
     else if (k == "pipe_depth") *value = plan->dev.pipe_depth;
+    else if (k == "csr_compressed") *value = plan->dev.compressed;
+    else if (k == "uncoded_rows") *value = plan->dev.n_bad_rows;
     else if (k == "mid_rows") *value = plan->dev.n_mid_rows;
     else if (k == "csr_bytes" || k == "csr_bytes_ld" || k == "csr_bytes_hd") {
         // what the kernels read of the graph per execute: every row pointer and every entry's column index, the
         // entry's weight only when the kernels take the weights from the array; the HD kernel reads its pieces'
         // descriptors instead of row pointers
         const DevicePlan &d = plan->dev;
-        const int64_t per_entry = 4 + (d.weight_mode == (int)WeightMode::Explicit ? 4 : 0);
-        const int64_t ld = 8 * (d.n + 1) + per_entry * (d.nnz - d.nnz_hd);
+        const int64_t w_bytes = d.weight_mode == (int)WeightMode::Explicit ? 4 : 0;
+        const int64_t per_entry = 4 + w_bytes;
+        // the pipelined LD kernel (feature widths 32, 64, 128) reads the compact form when the plan has one
+        const bool compact = d.ld_pipelined && d.compressed;
+        const int64_t ld = compact ? 4 * (d.n + 1) + (2 + w_bytes) * (d.nnz - d.nnz_hd)
+                                   : 8 * (d.n + 1) + per_entry * (d.nnz - d.nnz_hd);
         const int64_t hd = per_entry * d.nnz_hd + (int64_t)sizeof(HdChunk) * d.n_chunks;
         *value = k == "csr_bytes_ld" ? ld : k == "csr_bytes_hd" ? hd : ld + hd;
     }
@@ -1179,6 +1276,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (k == "ld_pipeline") {
         if (value < -1 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: ld_pipeline must be -1, 0 or 1");
         tuning().ld_pipeline = (int)value;
+        return GROOT_OK;
+    }
+    if (k == "csr_compress") {
+        if (value < 0 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: csr_compress must be 0 or 1");
+        tuning().csr_compress = (int)value;
         return GROOT_OK;
     }
     if (k == "sage_split" || k == "sage_kernel" || k == "uniform_detect") {

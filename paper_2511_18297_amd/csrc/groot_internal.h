@@ -44,6 +44,7 @@ struct Tuning {
     std::atomic<int> sage_split{1};        // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
     std::atomic<int> sage_kernel{1};       // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
     std::atomic<int> uniform_detect{1};    // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
+    std::atomic<int> csr_compress{1};      // groot_plan_upload builds the compact CSR for the pipelined LD kernel when it can
     std::atomic<int> pipe_depth{0};        // gather slots per row of the pipelined LD kernel: 0 the smallest that fits, or 5..8
     std::atomic<int> ld_pipeline{-1};      // pipelined LD kernel: 1 always (where it applies), 0 never, -1 by the row lengths
 };
@@ -70,6 +71,21 @@ struct DevicePlan {
     int xcd_remap = 1;
     float *zero_row = nullptr;      // kZeroRowFloats zeros (the gather target of unused slots in the pipelined
                                     // kernels), followed by kTrashFloats that those kernels may overwrite
+    // the fused layer's view of the high-degree rows: their ids (ascending), a buffer that takes their aggregated
+    // features, one row per high-degree row in that order, and the HD schedule with every row named by its place
+    // in the list instead of its id (so that the HD kernels write into the buffer)
+    int32_t *hd_rows = nullptr;     // [n_hd_rows]
+    int64_t n_hd_rows = 0;
+    float *hd_agg = nullptr;        // [n_hd_rows, max_F]
+    HdChunk *chunks_rank = nullptr; // [n_chunks]
+    HdSplitRow *split_rows_rank = nullptr;   // [n_split_rows]
+    // compact CSR for the pipelined LD kernel (groot_compress.hip); all NULL / 0 unless compressed
+    uint32_t *rp32 = nullptr;       // [n+1] low 32 bits of rowptr (nnz < 2^32)
+    uint16_t *col16 = nullptr;      // [nnz] column codes of the rows the pipelined kernel serves
+    int32_t *hot_cols = nullptr;    // [n_hot] the high-degree rows that a code can name, ascending
+    int32_t n_hot = 0;
+    int64_t n_bad_rows = 0;         // rows with an entry that no code expresses (they are part of mid_rows)
+    int compressed = 0;
     int64_t n_cols = 0;             // rows of the feature matrix the columns index: n, or the whole graph's row
                                     // count once a part's plan reads the global matrix in place
     int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
@@ -78,6 +94,10 @@ struct DevicePlan {
     int64_t n_mid_rows = 0;         // masks them; a row-list kernel computes them), ordered by (length, id)
 };
 
+constexpr int kCodeNear = 0x4000;     // column codes below kCodeHot: row + code - kCodeNear
+constexpr int kCodeHot = 0x8000;      // codes from here on: index into the hot list
+constexpr int kCodeBad = 0xFFFF;      // an entry that no code can express: its row is not served in compact form
+constexpr int kCodeMaxHot = 0x7FFF;
 constexpr int kPipeMinDepth = 5, kPipeMaxDepth = 8;   // gather slots per row the pipelined LD kernel is built for
 constexpr int kZeroRowFloats = 128;
 constexpr int kTrashFloats = 2048;
@@ -98,7 +118,10 @@ int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, co
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t F, void *stream);   // F = 64 or 32, row-uniform weights
+                     int relu, int32_t F_in, int32_t F_out, void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform weights
+// Compact CSR for the pipelined LD kernel, built on the device (groot_compress.hip); synchronises the stream.
+int launch_csr_compress(DevicePlan &dp, const int32_t *hd_rows_dev, int64_t n_hd, void *stream);
+int pipe_compact_prepare();   // once per process, before the first launch with a compact CSR; hipError_t as int
 // col[p] = ids[col[p]] for p < nnz, in place (a part's local columns -> rows of the whole graph's feature matrix)
 int launch_col_map(int32_t *col, int64_t nnz, const int64_t *ids, void *stream);
 int launch_rows_gather(const int64_t *ids, int64_t n, const float *X, float *out, int32_t F, void *stream);

@@ -39,10 +39,20 @@ __device__ __forceinline__ void pipe_wave_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int L, int W, int G, int D>
+// The compact form of the CSR (C = true: 4-byte row pointers, 2-byte column codes, the list of high-degree
+// rows that a code can name; see groot_compress.hip) replaces the loads of the pipeline; the plain path and the
+// row-list kernel keep reading the full arrays.
+struct CompactCsr {
+    const uint32_t *rp32;
+    const uint16_t *col16;
+    const int32_t *hot;
+    int32_t n_hot;
+};
+
+template <int L, int W, int G, int D, bool C>
 __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void ld_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
-    const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
+    const CompactCsr cz, const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
     int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
 {
     constexpr int kRpg = kWave / L;                      // rows per lane group sweep
@@ -67,6 +77,12 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     const int64_t x_begin = part * tiles_per_part;
     const int64_t x_end = x_begin + tiles_per_part < n_tiles ? x_begin + tiles_per_part : n_tiles;
     const int64_t t_first = x_begin + j, stride = waves_per_part;
+    extern __shared__ int32_t s_hot[];                   // C: the hot list (at least one element)
+    if constexpr (C) {
+        for (int i = threadIdx.x; i < cz.n_hot; i += kPipeWaves * kWave) s_hot[i] = cz.hot[i];
+        if (threadIdx.x == 0 && cz.n_hot == 0) s_hot[0] = 0;
+        __syncthreads();                                 // every wavefront gets here: none has left, nothing is in flight
+    }
     if (t_first >= x_end) return;
     const char *Xf = X + 16 * f;
 
@@ -79,14 +95,18 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     bool ok_a = false;
     int32_t len_a = 0;                                   // lanes 0..kTileRows-1: stored length of the tile's row
     uint32_t live_a = 0;                                 // bit h: slot l + 64 h holds an entry
+    int32_t base_a = 0;                                  // C: first row of the tile that cc belongs to
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kTileRows + (l < kTileRows ? l : kTileRows);
-        return rowptr[ri < n ? ri : n];                  // lanes 0..kTileRows hold the pointers; rows past the end read rowptr[n]
+        // lanes 0..kTileRows hold the pointers; rows past the end read rowptr[n]
+        if constexpr (C) return (int64_t)cz.rp32[ri < n ? ri : n];       // all of them below 2^32
+        else return rowptr[ri < n ? ri : n];
     };
     auto load_cols = [&](int64_t tile) {                 // from rp_a: every slot fetches its own entry
         // a tile takes part in the pipeline when all its rows exist; a row that does not fit its slots (too long,
         // or high-degree) has no live slot, whatever its length: it does not disturb the rows around it
         ok_a = (tile + 1) * kTileRows <= n && tile < x_end;
+        base_a = ok_a ? (int32_t)(tile * kTileRows) : 0;
         const int64_t begin = __shfl(rp_a, 0);
         const int32_t rel = ok_a ? (int32_t)(rp_a - begin) : 0;
         len_a = __shfl_down(rel, 1) - rel;
@@ -100,23 +120,44 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             const bool live = s < kSlots && k < len && len <= kPipeD && len < T;
             live_a |= (uint32_t)live << h;
             const int64_t i = live ? begin + lo + k : 0;
-            cc[h] = __builtin_nontemporal_load(&col[i]);
+            if constexpr (C) cc[h] = __builtin_nontemporal_load(&cz.col16[i]);
+            else cc[h] = __builtin_nontemporal_load(&col[i]);
             if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
         }
     };
     auto stage = [&]() -> bool {                         // cc, vv, live_a, len_a -> slot table and row weights
+        uint64_t badm[kH];                               // C: slots whose entry no code expresses
 #pragma unroll
         for (int h = 0; h < kH; ++h) {
             const int s = l + kWave * h;
-            const bool live = (live_a >> h) & 1;
+            bool live = (live_a >> h) & 1;
+            int32_t c = cc[h];
+            if constexpr (C) {                           // code -> column: near the row, or one of the hot rows
+                const bool bad = live && c == kCodeBad;
+                badm[h] = __ballot(bad);
+                live = live && !bad;
+                const int32_t hot_c = s_hot[live && c >= kCodeHot ? c - kCodeHot : 0];
+                c = c >= kCodeHot ? hot_c : base_a + s / kPipeD + c - kCodeNear;
+            }
             if (s < kSlots) {
-                const int64_t off = live ? ((int64_t)cc[h] << kRowShift) : zero_off;
+                const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
                 if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? vv[h] : 0.f, 0.f};
                 else s_slot[w][s] = off;
             }
         }
-        if (l < kTileRows)
-            s_inv[w][l] = ok_a && len_a <= kPipeD && len_a < T ? row_weight<W == kMean ? kMean : kOnes>(len_a) : -1.0f;
+        bool row_ok = ok_a && len_a <= kPipeD && len_a < T;
+        if constexpr (C) {                               // a row with a bad slot is masked as a whole: slots l D .. l D + D - 1
+            const int sb = l * kPipeD, sh = sb & 63;
+            uint64_t w0 = 0, w1 = 0;
+#pragma unroll
+            for (int q = 0; q < kH; ++q) {
+                w0 = (sb >> 6) == q ? badm[q] : w0;
+                w1 = (sb >> 6) + 1 == q ? badm[q] : w1;
+            }
+            const uint64_t bits = (w0 >> sh) | (sh ? w1 << (64 - sh) : 0);
+            row_ok = row_ok && (bits & ((1u << kPipeD) - 1)) == 0;
+        }
+        if (l < kTileRows) s_inv[w][l] = row_ok ? row_weight<W == kMean ? kMean : kOnes>(len_a) : -1.0f;
         pipe_wave_sync();
         return ok_a;
     };
@@ -220,6 +261,8 @@ struct PipeArgs {
     const int64_t *rowptr;
     const int32_t *col;
     const float *val;
+    CompactCsr cz;
+    bool compact;
     const char *X;
     char *Y;
     int64_t zero_off;                        // byte distance from X to the plan's row of zeros
@@ -235,9 +278,16 @@ struct PipeArgs {
 template <int L, int W, int G, int D>
 static void pipe_launch(const PipeArgs &a)
 {
-    ld_pipe_kernel<L, W, G, D><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
-        a.rowptr, a.col, a.val, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part, a.waves_per_part,
-        a.parts);
+    if (a.compact) {
+        const size_t lds = (size_t)(a.cz.n_hot ? a.cz.n_hot : 1) * sizeof(int32_t);
+        ld_pipe_kernel<L, W, G, D, true><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), lds, a.st>>>(
+            a.rowptr, a.col, a.val, a.cz, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part,
+            a.waves_per_part, a.parts);
+    } else {
+        ld_pipe_kernel<L, W, G, D, false><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
+            a.rowptr, a.col, a.val, a.cz, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part,
+            a.waves_per_part, a.parts);
+    }
 }
 
 template <int W, int G, int D>
@@ -258,6 +308,44 @@ static void pipe_dispatch_d(int depth, int32_t F4, const PipeArgs &a)
     case 7: pipe_dispatch_l<W, kG, 7>(F4, a); break;
     default: pipe_dispatch_l<W, kG, 8>(F4, a); break;
     }
+}
+
+// The compact form keeps the hot list in dynamic LDS, up to 128 KB: the runtime wants to be told once per
+// kernel that more than its default limit may be asked for.  Called when a plan gets its compact CSR (not at
+// launch, which may be under stream capture).
+template <int L, int W, int D>
+static int pipe_allow_lds()
+{
+    return (int)hipFuncSetAttribute((const void *)&ld_pipe_kernel<L, W, kPipeGroups, D, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kCodeMaxHot * (int)sizeof(int32_t));
+}
+template <int W, int D>
+static int pipe_allow_lds_l()
+{
+    int err = pipe_allow_lds<8, W, D>();
+    if (!err) err = pipe_allow_lds<16, W, D>();
+    if (!err) err = pipe_allow_lds<32, W, D>();
+    return err;
+}
+template <int W>
+static int pipe_allow_lds_d()
+{
+    int err = pipe_allow_lds_l<W, 5>();
+    if (!err) err = pipe_allow_lds_l<W, 6>();
+    if (!err) err = pipe_allow_lds_l<W, 7>();
+    if (!err) err = pipe_allow_lds_l<W, 8>();
+    return err;
+}
+int pipe_compact_prepare()
+{
+    static std::atomic<int> state{-1};                   // -1 not tried, else the result
+    int s = state.load();
+    if (s >= 0) return s;
+    int err = pipe_allow_lds_d<kOnes>();
+    if (!err) err = pipe_allow_lds_d<kMean>();
+    if (!err) err = pipe_allow_lds_d<kExplicit>();
+    state.store(err);
+    return err;
 }
 
 int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
@@ -288,7 +376,9 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     static_assert(kPipeGroups * kWave * 16 <= kTrashFloats * 4, "a tile's masked sums fit the trash area");
     hipStream_t st = (hipStream_t)stream;
-    const PipeArgs a{dp.rowptr, col_arg, val_arg, (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
+    const bool compact = dp.compressed && dp.rp32 && dp.col16 && dp.hot_cols;
+    const PipeArgs a{dp.rowptr, col_arg, val_arg, CompactCsr{dp.rp32, dp.col16, dp.hot_cols, dp.n_hot}, compact,
+                     (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
                      dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st};
     GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_d<kW>(dp.pipe_depth, F4, a)));
     hipError_t err = hipGetLastError();

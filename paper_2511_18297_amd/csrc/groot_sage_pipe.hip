@@ -1,5 +1,6 @@
 // Fused GraphSAGE-mean layer for gfx950, self-contained wavefronts (two per SIMD):
-//     H = act((A_hat X) Wn + X Ws + b),   F_in = F_out = F, F = 64 or 32.
+//     H = act((A_hat X) Wn + X Ws + b),   X [N, FI], Wn and Ws [FI, FO], H [N, FO], FI = 32 or 64, FO = 16, 32 or 64
+//     (described below for FI = FO = 64).
 //
 // The aggregation is the software-pipelined LD kernel's (a persistent workgroup per CU, every wavefront walks
 // its own tiles and keeps a whole tile of gathers in flight; slot table in LDS, zero row for dead slots, no
@@ -19,8 +20,10 @@
 // instruction's accumulator.  The weights are cut once per workgroup into LDS, in the operand layout of the
 // instruction (48 KB, one 16-byte read per lane and operand); the tile is cut when it is parked.
 //
-// High-degree rows are aggregated beforehand by the HD kernel into H itself; a tile that contains one (or a
-// row with more than kSpD entries, or the ragged end) is redone by a plain path that picks those sums up.
+// High-degree rows are aggregated beforehand by the HD kernel into a side buffer of the plan, one row per
+// high-degree row in ascending order of their ids; a tile that contains one (or a row with more than kSpD entries,
+// or the ragged end) is redone by a plain path that picks those sums up (the row's place in the buffer by binary
+// search in the list of high-degree rows).
 #include <type_traits>
 
 #include "groot_device.h"
@@ -33,21 +36,26 @@ constexpr int kSpSlots = kSpRows * kSpD;     // 96
 constexpr int kSpH = (kSpSlots + kWave - 1) / kWave;
 static_assert(kSpRows * 64 <= kTrashFloats, "rows past the end of the matrix are stored to the trash area");
 
-// Shapes for F input = F output features (64 or 32) and NW wavefronts per workgroup (one workgroup per CU).
-template <int F, int NW>
+// Shapes for FI input and FO output features and NW wavefronts per workgroup (one workgroup per CU).
+template <int FI, int FO, int NW>
 struct SpCfg {
     static constexpr int kWaves = NW;
-    static constexpr int kL = F / 4;                 // lanes per row, one float4 each
-    static constexpr int kRpg = kWave / kL;          // rows per lane-group sweep
+    static constexpr int kL = FI / 4;                // lanes per input row, one float4 each
+    static constexpr int kRpg = kWave / kL;          // input rows per lane-group sweep
     static constexpr int kG = kSpRows / kRpg;        // sweeps per tile
-    static constexpr int kRowShift = F == 64 ? 8 : 7;   // log2 of a feature row's bytes
-    static constexpr int kK = 2 * F;                 // contraction length: [agg | self]
+    static constexpr int kRowShift = FI == 64 ? 8 : 7;   // log2 of an input row's bytes
+    static constexpr int kK = 2 * FI;                // contraction length: [agg | self]
     static constexpr int kKs = kK / 32;              // k blocks of a matrix instruction
-    static constexpr int kNb = F / 16;               // blocks of 16 output columns
+    static constexpr int kNb = FO / 16;              // blocks of 16 output columns
     static constexpr int kBRow = kK * 2 + 16;        // bytes per LDS row of one bf16 plane (16 B of padding: conflict-free)
     static constexpr int kPlane = kSpRows * kBRow;
-    static constexpr int kOStride = F + 4;           // floats per LDS row of the result tile
-    static_assert(F == 64 || F == 32, "feature width");
+    static constexpr int kOStride = FO + 4;          // floats per LDS row of the result tile
+    static constexpr int kLo = FO / 4;               // lanes per output row
+    static constexpr int kRo = kWave / kLo;          // output rows per store instruction
+    static constexpr int kGo = kSpRows / kRo;        // store sweeps per tile
+    static constexpr int kORowShift = FO == 64 ? 8 : FO == 32 ? 7 : 6;   // log2 of an output row's bytes
+    static_assert(FI == 64 || FI == 32, "input width");
+    static_assert(FO == 64 || FO == 32 || FO == 16, "output width");
     static_assert(kSpRows * kOStride * 4 <= 3 * kPlane, "the result tile fits the parked tile's space");
 };
 
@@ -95,14 +103,16 @@ __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
     *(sp_u2 *)(p + 2 * kPlane) = (sp_u2){l0, l1};
 }
 
-template <int W, int F, int NW>   // W: kOnes or kMean
+template <int W, int FI, int FO, int NW>   // W: kOnes or kMean
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *H, int64_t zero_off, char *trash,
     const float *__restrict__ Wn, const float *__restrict__ Ws, const float *__restrict__ bias, int relu, int64_t n,
-    int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
+    int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts,
+    const int32_t *__restrict__ hd_rows, int32_t n_hd, const char *__restrict__ hd_agg)
 {
-    using C = SpCfg<F, NW>;
+    using C = SpCfg<FI, FO, NW>;
+    constexpr int F = FI;
     constexpr int kSpWaves = C::kWaves, kSpL = C::kL, kSpRpg = C::kRpg, kSpG = C::kG, kRowShift = C::kRowShift;
     constexpr int kKs = C::kKs, kNb = C::kNb, kSpBRow = C::kBRow, kSpPlane = C::kPlane, kSpOStride = C::kOStride;
     struct SlotW { int64_t off; float w; float pad; };
@@ -111,7 +121,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     __shared__ float s_inv[kSpWaves][kSpRows];
     __shared__ __align__(16) char s_A[kSpWaves][3 * kSpPlane];           // F = 64: 13,056 B per wavefront; the result tile reuses it
     __shared__ __align__(16) sp_u4 s_W[kNb][kKs][3][kWave];              // F = 64: 49,152 B: [nb][ks][piece][lane] B operands
-    __shared__ float s_bias[F];
+    __shared__ float s_bias[FO];
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int g = l / kSpL, f = l % kSpL;
@@ -132,8 +142,8 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
                 const int k = 32 * ks + 8 * kq + e;
-                const float w0 = k < F ? Wn[k * F + jcol] : Ws[(k - F) * F + jcol];
-                const float w1 = k + 1 < F ? Wn[(k + 1) * F + jcol] : Ws[(k + 1 - F) * F + jcol];
+                const float w0 = k < F ? Wn[k * FO + jcol] : Ws[(k - F) * FO + jcol];
+                const float w1 = k + 1 < F ? Wn[(k + 1) * FO + jcol] : Ws[(k + 1 - F) * FO + jcol];
                 unsigned h, m, lo_;
                 sp_split3(w0, w1, h, m, lo_);
                 pc[0][e / 2] = h;
@@ -144,7 +154,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             for (int q = 0; q < 3; ++q) s_W[nb][ks][q][l] = pc[q];
         }
     }
-    if (threadIdx.x < F) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
+    if (threadIdx.x < FO) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
     __syncthreads();
     if (t_first >= x_end) return;
 
@@ -276,8 +286,16 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
                 if (row < n) {
                     self = *(const v4f *)(Xf + (row << kRowShift));
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
-                    if (e - s >= T) a = *(const v4f *)(H + (row << kRowShift) + 16 * f);
-                    else a = ld_row_sum<W, false, kSpD>(s, e, col, val, (const v4f *)X, kSpL, f);
+                    if (e - s >= T) {
+                        int32_t lo = 0, hi = n_hd;       // the row's place in the list of high-degree rows
+                        while (lo < hi) {
+                            const int32_t mid = (lo + hi) / 2;
+                            if (hd_rows[mid] < row) lo = mid + 1; else hi = mid;
+                        }
+                        a = *(const v4f *)(hd_agg + ((int64_t)lo << kRowShift) + 16 * f);
+                    } else {
+                        a = ld_row_sum<W, false, kSpD>(s, e, col, val, (const v4f *)X, kSpL, f);
+                    }
                 }
                 sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
                 sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, self);
@@ -337,12 +355,12 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             }
         sp_wave_sync();
 #pragma unroll
-        for (int grp = 0; grp < kSpG; ++grp) {
-            const int lr = grp * kSpRpg + g;
+        for (int go = 0; go < C::kGo; ++go) {
+            const int lr = go * C::kRo + l / C::kLo, fo = l % C::kLo;
             const int64_t row = base + lr;
-            const v4f v = *(const v4f *)&o_tile[lr * kSpOStride + 4 * f];
-            char *dst = row < n ? H + (row << kRowShift) : trash + (lr << kRowShift);
-            __builtin_nontemporal_store(v, (v4f *)(dst + 16 * f));
+            const v4f v = *(const v4f *)&o_tile[lr * kSpOStride + 4 * fo];
+            char *dst = row < n ? H + (row << C::kORowShift) : trash + (lr << C::kORowShift);
+            __builtin_nontemporal_store(v, (v4f *)(dst + 16 * fo));
         }
         sp_wave_sync();                                  // the tiles in LDS are free for the next round
         simple_cur = simple_next;
@@ -350,11 +368,13 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
 }
 
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t F, void *stream)
+                     int relu, int32_t FI, int32_t FO, void *stream)
 {
-    if (!weights_ok(dp) || !dp.zero_row || (F != 64 && F != 32)) return (int)hipErrorInvalidValue;
+    if (!weights_ok(dp) || !dp.zero_row || (FI != 64 && FI != 32) || (FO != 64 && FO != 32 && FO != 16))
+        return (int)hipErrorInvalidValue;
     // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
     if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
+    if (dp.n_hd_rows && (!dp.hd_rows || !dp.hd_agg)) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return (int)e;
@@ -376,17 +396,23 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
-#define GROOT_SAGE_PIPE_LAUNCH(WM, FF, NW)                                                                            \
-    sage_pipe_kernel<WM, FF, NW><<<dim3((unsigned)n_wg), dim3(NW * kWave), 0, st>>>(                                  \
+#define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO)                                                                           \
+    sage_pipe_kernel<WM, FFI, FFO, kNwRun><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(                     \
         dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, byte_distance(X, dp.zero_row), trash, Wn, Ws, bias, relu, \
-        dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts)
-    if (F == 64) {
-        if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean, 64, 8);
-        else GROOT_SAGE_PIPE_LAUNCH(kOnes, 64, 8);
+        dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows,         \
+        (const char *)dp.hd_agg)
+#define GROOT_SAGE_PIPE_FO(WM, FFI)                          \
+    if (FO == 64) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 64);       \
+    else if (FO == 32) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 32);  \
+    else GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 16)
+    if (FI == 64) {
+        if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 64); }
+        else { GROOT_SAGE_PIPE_FO(kOnes, 64); }
     } else {
-        if (dp.weight_mode == kMean) GROOT_SAGE_PIPE_LAUNCH(kMean, 32, 8);
-        else GROOT_SAGE_PIPE_LAUNCH(kOnes, 32, 8);
+        if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 32); }
+        else { GROOT_SAGE_PIPE_FO(kOnes, 32); }
     }
+#undef GROOT_SAGE_PIPE_FO
 #undef GROOT_SAGE_PIPE_LAUNCH
     return (int)hipGetLastError();
 }

@@ -112,6 +112,12 @@ def test_config2_256bit(torch_cuda):
     X = wl.uniform_features_numpy(1, 0, aig.num_nodes, 64)
     Y, plan, Xd, Yd = _run(torch_cuda, g, 32, X)
     assert G.groot_plan_view(plan)["n_hd"] == 512
+    # the pipelined kernel runs with 5 slots per row (only 256 rows have 6 entries) on the compact matrix
+    # (2-byte column codes; the 498 rows they cannot express -- primary outputs more than 16,384 rows behind their
+    # drivers, and those drivers -- join the 256 long rows on the row list)
+    if G.groot_plan_query(plan, "ld_pipelined"):
+        assert G.groot_plan_query(plan, "pipe_depth") == 5 and G.groot_plan_query(plan, "csr_compressed") == 1
+        assert G.groot_plan_query(plan, "uncoded_rows") == 498 and G.groot_plan_query(plan, "mid_rows") == 256 + 498
     Y64, S = oracle.spmm_f64(rowptr, col, val, X)
     assert_close_to_oracle(Y, Y64, S, "config 2")
     # no atomics anywhere: a second run is bitwise identical
@@ -215,7 +221,20 @@ def test_mixed_row_lengths(torch_cuda, max_len, T, F, explicit):
     assert G.groot_plan_query(plan, "weight_mode") == (2 if explicit else 1)
     if G.groot_plan_query(plan, "ld_pipelined"):
         depth = G.groot_plan_query(plan, "pipe_depth")
-        assert G.groot_plan_query(plan, "mid_rows") == int(((deg > depth) & (deg < T)).sum())
+        # rows near the end wrap around to columns near 0: farther than a 2-byte code reaches, and such a column
+        # is a named high-degree row only by chance -> those rows are left to the row list
+        rows = np.repeat(np.arange(n), deg)
+        short = (deg <= depth) & (deg < T)
+        delta = col.astype(np.int64) - rows
+        hot_mask = np.zeros(n, dtype=bool)
+        hot_mask[np.nonzero(deg >= T)[0][:32767]] = True
+        uncoded = np.unique(rows[short[rows] & ~((delta >= -16384) & (delta < 16384)) & ~hot_mask[col]])
+        if uncoded.shape[0] * 50 <= n:
+            assert G.groot_plan_query(plan, "csr_compressed") == 1
+            assert G.groot_plan_query(plan, "uncoded_rows") == uncoded.shape[0]
+            assert G.groot_plan_query(plan, "mid_rows") == int(((deg > depth) & (deg < T)).sum()) + uncoded.shape[0]
+        else:
+            assert G.groot_plan_query(plan, "csr_compressed") == 0
     Y64, S = oracle.spmm_f64(rowptr, col, val, X)
     assert_close_to_oracle(Y, Y64, S, f"mixed rows max_len={max_len} T={T} F={F}")
 
@@ -272,22 +291,27 @@ def layer_tolerance(S, scale, absWn, floor=1e-6):
     return (1e-5 * S + floor) @ absWn + 1e-5 * scale + floor
 
 
-def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64):
+def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64, F_out=None):
+    """F_out None: the square call (F -> F); else the call with separate input and output widths."""
     rng = np.random.default_rng(seed)
     X = wl.uniform_features_numpy(seed, 0, n, F)
     if row_scale is not None:
         X = (X * row_scale[:, None]).astype(np.float32)
-    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
-    b = rng.uniform(-0.125, 0.125, F).astype(np.float32) if with_bias else None
+    FO = F if F_out is None else F_out
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, FO)).astype(np.float32) for _ in range(2))
+    b = rng.uniform(-0.125, 0.125, FO).astype(np.float32) if with_bias else None
     plan = G.groot_spmm_plan(g, T)
     G.groot_plan_upload(plan, F)
     dev = lambda a: torch.from_numpy(a).cuda()
     guard = 2
-    buf = torch.full((n + 2 * guard, F), float("nan"), dtype=torch.float32, device="cuda")
+    buf = torch.full((n + 2 * guard, FO), float("nan"), dtype=torch.float32, device="cuda")
     buf[:guard] = 777.0
     buf[n + guard:] = 777.0
     H = buf[guard:n + guard]
-    G.groot_sage_layer_forward(plan, dev(X), dev(Wn), dev(Ws), None if b is None else dev(b), relu, H, F)
+    if F_out is None:
+        G.groot_sage_layer_forward(plan, dev(X), dev(Wn), dev(Ws), None if b is None else dev(b), relu, H, F)
+    else:
+        G.groot_sage_layer_forward_io(plan, dev(X), dev(Wn), dev(Ws), None if b is None else dev(b), relu, H, F, FO)
     torch.cuda.synchronize()
     out = buf.cpu().numpy()
     assert (out[:guard] == 777.0).all() and (out[n + guard:] == 777.0).all(), "wrote outside H"
@@ -320,6 +344,40 @@ def test_fused_sage_layer_width_32(torch_cuda, n_bits, batch, T, relu, with_bias
     aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
     _sage_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 300 + n_bits, relu, with_bias,
                 f"sage F=32 {n_bits}x{batch} T={T}", F=32)
+
+
+@pytest.mark.parametrize("F_in,F_out", [(32, 16), (32, 64), (64, 32), (64, 16), (32, 32), (64, 64)])
+@pytest.mark.parametrize("n_bits,batch,T,relu,with_bias", [(48, 2, 32, True, True), (17, 3, 5, False, False),
+                                                            (40, 1, 1, True, False)])
+def test_fused_sage_layer_input_and_output_widths(torch_cuda, F_in, F_out, n_bits, batch, T, relu, with_bias):
+    """A layer that narrows or widens (X [N, F_in] -> H [N, F_out]): every supported pair of widths, with
+    high-degree rows (their sums pass through the plan's side buffer), low thresholds, and every row
+    high-degree."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    _sage_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 500 + n_bits + F_in + F_out, relu, with_bias,
+                f"sage {F_in}->{F_out} {n_bits}x{batch} T={T}", F=F_in, F_out=F_out)
+
+
+def test_fused_sage_layer_widths_on_booth_and_stress_shapes(torch_cuda):
+    """High-degree rows scattered through the graph (Booth recoding signals; heavy rows of a polarized graph,
+    some of them split into pieces): every tile that holds one takes the path that looks its sum up."""
+    aig = wl.booth_multiplier_aig(32)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 2)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 2)
+    _sage_check(torch_cuda, g, rowptr, col, val, 16, 2 * aig.num_nodes, 61, True, True, "sage booth 64->32", F=64, F_out=32)
+    s = wl.stress_graph(12, 1 << 14, window=512, dmin=64, dmax=2048)
+    gs = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    _sage_check(torch_cuda, gs, s.rowptr, s.col, s.val, 32, s.n, 62, False, True, "sage stress 32->16", F=32, F_out=16)
+    plan = G.groot_spmm_plan(g, 16)
+    G.groot_plan_upload(plan, 64)
+    z = lambda *shape: torch_cuda.zeros(shape, device="cuda")
+    n = 2 * aig.num_nodes
+    with pytest.raises(G.GrootError):                       # output width 48 is not built
+        G.groot_sage_layer_forward_io(plan, z(n, 64), z(64, 48), z(64, 48), None, True, z(n, 48), 64, 48)
+    with pytest.raises(G.GrootError):                       # input width 16 is not built
+        G.groot_sage_layer_forward_io(plan, z(n, 16), z(16, 32), z(16, 32), None, True, z(n, 32), 16, 32)
+    with pytest.raises(ValueError):                         # the binding: weights too small for 64 -> 32
+        G.groot_sage_layer_forward_io(plan, z(n, 64), z(32, 32), z(64, 32), None, True, z(n, 32), 64, 32)
 
 
 def test_fused_sage_layer_bf16_pieces_keep_fp32_accuracy(torch_cuda):
@@ -408,9 +466,22 @@ def test_tuning_knobs_do_not_change_results(torch_cuda):
                 G.groot_set_tuning("hd_chunk", chunk)
                 Y, _, _, _ = _run(torch_cuda, g, 12, X)
                 assert_close_to_oracle(Y, Y64, S, f"remap={remap} chunk={chunk}")
+        G.groot_set_tuning("xcd_remap", 1)
+        G.groot_set_tuning("hd_chunk", 512)
+        for compress in (0, 1):
+            for depth in (0, 5, 6, 7, 8):
+                G.groot_set_tuning("csr_compress", compress)
+                G.groot_set_tuning("pipe_depth", depth)
+                Y, plan, _, _ = _run(torch_cuda, g, 12, X)
+                if G.groot_plan_query(plan, "ld_pipelined"):
+                    assert G.groot_plan_query(plan, "csr_compressed") == compress
+                    assert G.groot_plan_query(plan, "pipe_depth") == (depth or 5)
+                assert_close_to_oracle(Y, Y64, S, f"compress={compress} depth={depth}")
     finally:
         G.groot_set_tuning("xcd_remap", 1)
         G.groot_set_tuning("hd_chunk", 512)
+        G.groot_set_tuning("csr_compress", 1)
+        G.groot_set_tuning("pipe_depth", 0)
 
 
 def test_phases_cover_disjoint_rows(torch_cuda):
