@@ -30,6 +30,8 @@ EXPORTS = [
     "groot_set_tuning", "groot_last_error",
 ]
 
+# an alternative build of the library (same ABI), for experiments
+LIB_PATH = os.environ.get("GROOT_LIBRARY", LIB_PATH)
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_18297_amd.build` "
                       "(or __graft_entry__.build()); there is no fallback path")

@@ -604,6 +604,9 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
         const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most);
         d.ld_pipelined = ch.pipelined;
         d.pipe_depth = ch.depth;
+        // the fused layer kernel completes a longer row inside the tile's turn, unoverlapped: 5 slots only when
+        // at most one low-degree row in 2000 has 6 entries or more
+        d.sage_depth = (n_ld - at_most(5)) * 2000 <= n_ld ? 5 : 6;
         const int64_t first_mid = at_most(ch.depth);
         d.n_mid_rows = ch.pipelined ? n_ld - first_mid : 0;
         if (d.n_mid_rows &&
@@ -1162,6 +1165,7 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
             const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most);
             d.ld_pipelined = ch.pipelined;
             d.pipe_depth = ch.depth;
+            d.sage_depth = (n_ld - at_most(5)) * 2000 <= n_ld ? 5 : 6;
             const int64_t first_mid = at_most(ch.depth);
             d.n_mid_rows = ch.pipelined ? n_ld - first_mid : 0;
             if (d.n_mid_rows) {             // the tail of the degree-sorted list, which is on the device already

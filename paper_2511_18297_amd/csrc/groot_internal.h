@@ -89,6 +89,7 @@ struct DevicePlan {
     int64_t n_cols = 0;             // rows of the feature matrix the columns index: n, or the whole graph's row
                                     // count once a part's plan reads the global matrix in place
     int ld_pipelined = 0;           // pipelined LD kernel: 0 never, 1 for F = 64 and 128, 2 for F = 32 as well
+    int sage_depth = 6;             // gather slots per row of the fused layer kernel: 5 when rows of 6 entries are rare, else 6
     int pipe_depth = 6;             // slots per row of the pipelined LD kernel: kPipeMinDepth .. kPipeMaxDepth
     int32_t *mid_rows = nullptr;    // low-degree rows with more than pipe_depth entries (the pipelined kernel
     int64_t n_mid_rows = 0;         // masks them; a row-list kernel computes them), ordered by (length, id)

@@ -120,9 +120,11 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             const bool live = s < kSlots && k < len && len <= kPipeD && len < T;
             live_a |= (uint32_t)live << h;
             const int64_t i = live ? begin + lo + k : 0;
-            if constexpr (C) cc[h] = __builtin_nontemporal_load(&cz.col16[i]);
-            else cc[h] = __builtin_nontemporal_load(&col[i]);
-            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
+            // (plain loads, no streaming hint: the cache line a tile's entries end in is the one the next tile's
+            // begin in, and that tile belongs to another wavefront of the same XCD, a moment later; 1.7 % of a step)
+            if constexpr (C) cc[h] = cz.col16[i];
+            else cc[h] = col[i];
+            if (W == kExplicit) vv[h] = val[i];
         }
     };
     auto stage = [&]() -> bool {                         // cc, vv, live_a, len_a -> slot table and row weights

@@ -30,10 +30,7 @@
 
 namespace groot {
 
-constexpr int kSpD = 6;                      // slots per row on the pipelined path
 constexpr int kSpRows = 16;                  // rows per tile: the height of a matrix instruction
-constexpr int kSpSlots = kSpRows * kSpD;     // 96
-constexpr int kSpH = (kSpSlots + kWave - 1) / kWave;
 static_assert(kSpRows * 64 <= kTrashFloats, "rows past the end of the matrix are stored to the trash area");
 
 // Shapes for FI input and FO output features and NW wavefronts per workgroup (one workgroup per CU).
@@ -103,7 +100,7 @@ __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
     *(sp_u2 *)(p + 2 * kPlane) = (sp_u2){l0, l1};
 }
 
-template <int W, int FI, int FO, int NW>   // W: kOnes or kMean
+template <int W, int FI, int FO, int NW, int D>   // W: kOnes or kMean; D: gather slots per row on the pipelined path
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *H, int64_t zero_off, char *trash,
@@ -113,6 +110,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
 {
     using C = SpCfg<FI, FO, NW>;
     constexpr int F = FI;
+    constexpr int kSpD = D, kSpSlots = kSpRows * kSpD, kSpH = (kSpSlots + kWave - 1) / kWave;
     constexpr int kSpWaves = C::kWaves, kSpL = C::kL, kSpRpg = C::kRpg, kSpG = C::kG, kRowShift = C::kRowShift;
     constexpr int kKs = C::kKs, kNb = C::kNb, kSpBRow = C::kBRow, kSpPlane = C::kPlane, kSpOStride = C::kOStride;
     struct SlotW { int64_t off; float w; float pad; };
@@ -164,55 +162,49 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     float vv[kSpH];
 #pragma unroll
     for (int h = 0; h < kSpH; ++h) { cc[h] = 0; vv[h] = 0.f; }
-    bool simple_a = false;
+    bool fix_a = true;                                   // the tile has rows that the slots do not serve (or is ragged)
+    int32_t len_a = 0;                                   // lanes 0..kSpRows-1: stored length of the tile's row
+    uint32_t live_a = 0;                                 // bit h: slot l + 64 h holds an entry
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kSpRows + (l < kSpRows ? l : kSpRows);
         return rowptr[ri < n ? ri : n];                  // lanes 0..kSpRows hold the pointers; rows past the end read rowptr[n]
     };
-    auto load_cols = [&](int64_t tile) {                 // from rp_a
-        const int64_t begin = __shfl(rp_a, 0), t_end = __shfl(rp_a, kSpRows), rp_next = __shfl_down(rp_a, 1);
-        const int64_t len = rp_next - rp_a;
+    auto load_cols = [&](int64_t tile) {                 // from rp_a: every slot fetches its own entry
         const bool full = (tile + 1) * kSpRows <= n && tile < x_end;
-        simple_a = full && __ballot(l < kSpRows && (len > kSpD || len >= T)) == 0;
-        const int32_t m = simple_a ? (int32_t)(t_end - begin) : 0;          // <= kSpSlots
-        // unconditional loads (lanes past the end read entry 0): the number of loads in flight stays known
-#pragma unroll
-        for (int h = 0; h < kSpH; ++h) {
-            const int64_t i = l + kWave * h < m ? begin + l + kWave * h : 0;
-            cc[h] = __builtin_nontemporal_load(&col[i]);
-            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
-        }
-    };
-    auto stage = [&]() -> bool {                         // rp_a, cc, vv -> slot table; a tile that is not simple is staged as empty
-        const int32_t rel = simple_a ? (int32_t)(rp_a - __shfl(rp_a, 0)) : 0;
+        const int64_t begin = __shfl(rp_a, 0);
+        const int32_t rel = full ? (int32_t)(rp_a - begin) : 0;
+        len_a = __shfl_down(rel, 1) - rel;
+        // a row with more entries than slots, or a high-degree row, has no live slot: the tile is completed by the
+        // plain path below, row by row
+        fix_a = !full || __ballot(l < kSpRows && (len_a > kSpD || len_a >= T)) != 0;
+        live_a = 0;
+        // unconditional loads (a dead slot reads entry 0): the number of loads in flight stays known
 #pragma unroll
         for (int h = 0; h < kSpH; ++h) {
             const int s = l + kWave * h;                 // slot s: row r, entry k
             const int r = s / kSpD, k = s - r * kSpD;
-            const int32_t lo = __shfl(rel, r), hi = __shfl(rel, r + 1);
-            const int src = lo + k;
-            int32_t c = 0;
-            float wt = 0.f;
+            const int32_t lo = __shfl(rel, r), len = __shfl(rel, r + 1) - lo;
+            const bool live = s < kSpSlots && k < len && len <= kSpD && len < T;
+            live_a |= (uint32_t)live << h;
+            const int64_t i = live ? begin + lo + k : 0;
+            cc[h] = __builtin_nontemporal_load(&col[i]);
+            if (W == kExplicit) vv[h] = __builtin_nontemporal_load(&val[i]);
+        }
+    };
+    auto stage = [&]() -> bool {                         // cc, vv, live_a, len_a -> slot table and row weights; -> fix_a
 #pragma unroll
-            for (int q = 0; q < kSpH; ++q) {
-                const int32_t cq = __shfl(cc[q], src - kWave * q);
-                c = (src >> 6) == q ? cq : c;
-                if (W == kExplicit) {
-                    const float wq = __shfl(vv[q], src - kWave * q);
-                    wt = (src >> 6) == q ? wq : wt;
-                }
-            }
-            const bool live = k < hi - lo;
+        for (int h = 0; h < kSpH; ++h) {
+            const int s = l + kWave * h;
+            const bool live = (live_a >> h) & 1;
             if (s < kSpSlots) {
-                const int64_t off = live ? ((int64_t)c << kRowShift) : zero_off;
-                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? wt : 0.f, 0.f};
+                const int64_t off = live ? ((int64_t)cc[h] << kRowShift) : zero_off;
+                if constexpr (W == kExplicit) s_slot[w][s] = SlotW{off, live ? vv[h] : 0.f, 0.f};
                 else s_slot[w][s] = off;
             }
         }
-        const int32_t len = __shfl_down(rel, 1) - rel;   // all lanes take part in the exchange
-        if (W == kMean && l < kSpRows) s_inv[w][l] = row_weight<kMean>(len);
+        if (W == kMean && l < kSpRows) s_inv[w][l] = row_weight<kMean>(len_a);
         sp_wave_sync();
-        return simple_a;
+        return fix_a;
     };
 
     // ---- one group: kSpRpg rows, one per lane group: the row's own features and its kSpD slots
@@ -253,7 +245,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     // ---- prologue: the first tile is staged and put in flight, the CSR of the next two is on its way
     rp_a = load_rp(t_first);
     load_cols(t_first);
-    bool simple_cur = stage();
+    bool fix_cur = stage();
     rp_a = load_rp(t_first + stride);
     load_cols(t_first + stride);
     rp_b = load_rp(t_first + 2 * stride);
@@ -264,7 +256,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     char *const a_tile = s_A[w];
     float *const o_tile = (float *)s_A[w];               // after the products the parked tile is dead
     for (int64_t tile = t_first; tile < x_end; tile += stride) {
-        const bool simple_next = stage();                // CSR of the next tile -> slot table (this tile's groups are all issued)
+        const bool fix_next = stage();                   // CSR of the next tile -> slot table (this tile's groups are all issued)
         rp_a = rp_b;
         load_cols(tile + 2 * stride);
         rp_b = load_rp(tile + 3 * stride);
@@ -277,15 +269,18 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, rr[grp].self);
             issue(rr[grp], tile + stride, grp);
         }
-        if (!simple_cur) {
-            // plain path: the rows of this tile straight from global memory, high-degree sums from H
+        if (fix_cur) {
+            // plain path: the rows of this tile that had no live slots (more entries than slots, high-degree, or
+            // every row of the ragged last tile), straight from global memory; high-degree sums from the side buffer
 #pragma unroll 1
             for (int grp = 0; grp < kSpG; ++grp) {
                 const int64_t row = base + grp * kSpRpg + g;
-                v4f a = {0.f, 0.f, 0.f, 0.f}, self = {0.f, 0.f, 0.f, 0.f};
+                const bool full = base + kSpRows <= n;
+                v4f a = {0.f, 0.f, 0.f, 0.f};
+                bool redo = false;
                 if (row < n) {
-                    self = *(const v4f *)(Xf + (row << kRowShift));
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
+                    redo = !full || e - s > kSpD || e - s >= T;
                     if (e - s >= T) {
                         int32_t lo = 0, hi = n_hd;       // the row's place in the list of high-degree rows
                         while (lo < hi) {
@@ -293,12 +288,11 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
                             if (hd_rows[mid] < row) lo = mid + 1; else hi = mid;
                         }
                         a = *(const v4f *)(hd_agg + ((int64_t)lo << kRowShift) + 16 * f);
-                    } else {
-                        a = ld_row_sum<W, false, kSpD>(s, e, col, val, (const v4f *)X, kSpL, f);
+                    } else if (redo) {
+                        a = ld_row_sum<W, false, 8>(s, e, col, val, (const v4f *)X, kSpL, f);
                     }
                 }
-                sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
-                sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, self);
+                if (redo) sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
             }
         }
         sp_wave_sync();
@@ -363,7 +357,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             __builtin_nontemporal_store(v, (v4f *)(dst + 16 * fo));
         }
         sp_wave_sync();                                  // the tiles in LDS are free for the next round
-        simple_cur = simple_next;
+        fix_cur = fix_next;
     }
 }
 
@@ -396,15 +390,18 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
-#define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO)                                                                           \
-    sage_pipe_kernel<WM, FFI, FFO, kNwRun><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(                     \
+#define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD)                                                                       \
+    sage_pipe_kernel<WM, FFI, FFO, kNwRun, DD><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(                 \
         dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, byte_distance(X, dp.zero_row), trash, Wn, Ws, bias, relu, \
         dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows,         \
         (const char *)dp.hd_agg)
-#define GROOT_SAGE_PIPE_FO(WM, FFI)                          \
-    if (FO == 64) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 64);       \
-    else if (FO == 32) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 32);  \
-    else GROOT_SAGE_PIPE_LAUNCH(WM, FFI, 16)
+#define GROOT_SAGE_PIPE_D(WM, FFI, FFO)                                   \
+    if (dp.sage_depth == 5) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, 5);      \
+    else GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, 6)
+#define GROOT_SAGE_PIPE_FO(WM, FFI)                            \
+    if (FO == 64) { GROOT_SAGE_PIPE_D(WM, FFI, 64); }          \
+    else if (FO == 32) { GROOT_SAGE_PIPE_D(WM, FFI, 32); }     \
+    else { GROOT_SAGE_PIPE_D(WM, FFI, 16); }
     if (FI == 64) {
         if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 64); }
         else { GROOT_SAGE_PIPE_FO(kOnes, 64); }
@@ -412,6 +409,7 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
         if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 32); }
         else { GROOT_SAGE_PIPE_FO(kOnes, 32); }
     }
+#undef GROOT_SAGE_PIPE_D
 #undef GROOT_SAGE_PIPE_FO
 #undef GROOT_SAGE_PIPE_LAUNCH
     return (int)hipGetLastError();
