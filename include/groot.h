@@ -395,6 +395,18 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
  * Errors: EINVAL (NULL, unknown name, plan not uploaded). */
 groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t *value);
 
+/* The HD kernel's launch list of an uploaded plan, in launch order, copied to
+ * host arrays of `capacity` entries each (any of them may be NULL = not
+ * wanted): piece c covers stored entries [begin[c], begin[c] + len[c]) of row
+ * row[c]; slot[c] is its partial-sum slot, or -1 when the row has one piece.
+ * Paper: Section "Kernel Design - GROOT-GPU" (static split of a high-degree
+ * row's non-zeros).  For tests and diagnostics: a plan made on the device
+ * (groot_dev_part_plan) carries the same list, bit for bit, as a host plan of
+ * the same sub-graph.  Synchronous.  Errors: EINVAL (NULL plan, plan not
+ * uploaded, capacity below "hd_pieces"), EHIP. */
+groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t capacity, int64_t *begin_host,
+                                  int32_t *len_host, int32_t *row_host, int32_t *slot_host);
+
 /* Launch-shape knobs for experiments: "xcd_remap" (0/1, read by
  * groot_plan_upload), "hd_chunk" (largest piece of a high-degree row,
  * 64..4096 non-zeros, read by groot_spmm_plan), "uniform_detect" (1, default:

@@ -507,11 +507,9 @@ PipeChoice choose_ld_kernel(int knob, int64_t n_ld, AtMost at_most)
 }  // namespace
 
 namespace {
-// The fused layer's side of the high-degree rows (see DevicePlan): the HD schedule with rows renamed to their
-// place in hd_rows (ascending ids), and the buffer their aggregated features go to.  hd_rows_dev: the list on the
-// device already (a plan built there), else NULL and the host list is uploaded.
-groot_status upload_layer_hd_side(groot_plan *pl, const int32_t *hd_rows_host, int64_t n_hd, const int32_t *hd_rows_dev,
-                                  int32_t max_F, void *stream, const char *who)
+// The fused layer's side of the high-degree rows (see DevicePlan) for a plan made on the host: the HD schedule
+// with rows renamed to their place in hd_rows (ascending ids), and the buffer their aggregated features go to.
+groot_status upload_layer_hd_side(groot_plan *pl, const int32_t *hd_rows_host, int64_t n_hd, int32_t max_F)
 {
     DevicePlan &d = pl->dev;
     d.n_hd_rows = n_hd;
@@ -527,12 +525,8 @@ groot_status upload_layer_hd_side(groot_plan *pl, const int32_t *hd_rows_host, i
     if ((st = to_device(&d.chunks_rank, chunks.data(), chunks.size(), "HD schedule of the fused layer")) != GROOT_OK ||
         (st = to_device(&d.split_rows_rank, split.data(), split.size(), "HD split rows of the fused layer")) != GROOT_OK ||
         (st = to_device<float>(&d.hd_agg, nullptr, (size_t)n_hd * max_F, "high-degree sums of the fused layer")) != GROOT_OK ||
-        (st = to_device(&d.hd_rows, hd_rows_dev ? nullptr : hd_rows_host, (size_t)n_hd, "high-degree row list")) != GROOT_OK)
+        (st = to_device(&d.hd_rows, hd_rows_host, (size_t)n_hd, "high-degree row list")) != GROOT_OK)
         return st;
-    if (hd_rows_dev) {
-        int err = device_copy(d.hd_rows, hd_rows_dev, (size_t)n_hd * 4, stream);
-        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
-    }
     return GROOT_OK;
 }
 }  // namespace
@@ -634,8 +628,7 @@ extern "C" groot_status groot_plan_upload(groot_plan *plan, int32_t max_F)
             return fail(GROOT_EHIP, std::string("groot_plan_upload: compact CSR: ") + hip_error_text(err));
         }
     }
-    if ((st = upload_layer_hd_side(plan, plan->hd_rows.data(), (int64_t)plan->hd_rows.size(), nullptr, max_F, nullptr,
-                                   "groot_plan_upload: ")) != GROOT_OK) {
+    if ((st = upload_layer_hd_side(plan, plan->hd_rows.data(), (int64_t)plan->hd_rows.size(), max_F)) != GROOT_OK) {
         std::string keep = groot_last_error();
         release_device(plan);
         set_error(keep);
@@ -1106,60 +1099,45 @@ extern "C" groot_status groot_dev_part_plan(groot_dev_part *part, int32_t degree
             return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
         const int64_t n_hd = h_counts[0], n_ld = h_counts[1];
         if (n_hd < 0 || n_ld < 0 || n_hd + n_ld != n) return fail(GROOT_EHIP, std::string(who) + "inconsistent row counts from the device");
-        std::vector<int32_t> rows(n_hd);
-        std::vector<int64_t> begin(n_hd), end(n_hd);
-        if ((err = device_download(rows.data(), hd_rows.p, (size_t)n_hd * 4, hip_stream)) ||
-            (err = device_row_extents(part->d.rowptr, hd_rows.as<int32_t>(), n_hd, begin.data(), end.data(), hip_stream))) {
-            if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "scratch allocation failed");
-            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
-        }
-        for (int64_t k = 0; k < n_hd; ++k)
-            if (rows[k] < 0 || rows[k] >= n || begin[k] < 0 || end[k] < begin[k] || end[k] > part->d.nnz)
-                return fail(GROOT_EHIP, std::string(who) + "row extents from the device are out of range");
-        groot_status hs = hd_schedule(n_hd, rows.data(), [&](int64_t k) { return begin[k]; },
-                                      [&](int64_t k) { return end[k] - begin[k]; }, pl->chunks, pl->split_rows,
-                                      pl->n_partials);
-        if (hs != GROOT_OK) return hs;
-        std::vector<int64_t> idx(pl->chunks.size());
-        std::vector<int32_t> key(pl->chunks.size());
-        for (size_t c = 0; c < idx.size(); ++c) idx[c] = pl->chunks[c].len > 0 ? pl->chunks[c].begin : 0;
-        if ((err = device_gather_col(part->d.col, idx.data(), (int64_t)idx.size(), key.data(), hip_stream))) {
-            if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "scratch allocation failed");
-            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
-        }
-        for (size_t c = 0; c < key.size(); ++c)
-            if (pl->chunks[c].len <= 0) key[c] = std::numeric_limits<int32_t>::max();
-        sort_hd_schedule(pl->chunks, key);
-
+        // the schedule of the high-degree rows, cut and ordered on the device too: only four sizes come back
+        DeviceHdSchedule sched;
+        err = launch_hd_schedule_device(part->d.rowptr, part->d.col, hd_rows.as<int32_t>(), n_hd, tuning().hd_chunk,
+                                        hip_stream, &sched);
+        if (err == kErrOutOfDeviceMemory) return fail(GROOT_ENOMEM, std::string(who) + "device allocation of the HD schedule failed");
+        if (err == kErrTooManyPieces) return fail(GROOT_ERANGE, std::string(who) + "too many high-degree pieces");
+        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
         DevicePlan &d = pl->dev;
+        d.chunks = sched.chunks;                         // the plan owns them from here on (release_device)
+        d.chunks_rank = sched.chunks_rank;
+        d.split_rows = sched.split_rows;
+        d.split_rows_rank = sched.split_rows_rank;
+        pl->n_partials = sched.n_partials;
         const std::vector<float> zeros(kZeroRowFloats + kTrashFloats, 0.0f);
         groot_status st;
         if ((st = to_device(&d.zero_row, zeros.data(), zeros.size(), "zero row")) != GROOT_OK ||
-            (st = to_device(&d.chunks, pl->chunks.data(), pl->chunks.size(), "HD schedule")) != GROOT_OK ||
-            (st = to_device(&d.split_rows, pl->split_rows.data(), pl->split_rows.size(), "HD split rows")) != GROOT_OK ||
-            (st = to_device<float>(&d.partials, nullptr, (size_t)pl->n_partials * max_F, "HD partial sums")) != GROOT_OK) {
+            (st = to_device<float>(&d.partials, nullptr, (size_t)sched.n_partials * max_F, "HD partial sums")) != GROOT_OK ||
+            (st = to_device<float>(&d.hd_agg, nullptr, (size_t)n_hd * max_F, "high-degree sums of the fused layer")) != GROOT_OK ||
+            (st = to_device<int32_t>(&d.hd_rows, nullptr, (size_t)n_hd, "high-degree row list")) != GROOT_OK) {
             std::string keep = groot_last_error();
             release_device(pl.get());
             set_error(keep);
             return st;
         }
-        if ((st = upload_layer_hd_side(pl.get(), rows.data(), n_hd, hd_rows.as<int32_t>(), max_F, hip_stream, who)) != GROOT_OK) {
-            std::string keep = groot_last_error();
+        if (n_hd && (err = device_copy(d.hd_rows, hd_rows.p, (size_t)n_hd * 4, hip_stream))) {
             release_device(pl.get());
-            set_error(keep);
-            return st;
+            return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
         }
+        d.n_hd_rows = n_hd;
         d.n = d.n_cols = n;
         d.nnz = part->d.nnz;
         d.threshold = T;
         d.xcd_remap = tuning().xcd_remap;
         d.weight_mode = d.graph_weight_mode = (int)part->weight_mode;
         d.n_tiles = (n + kRowsPerLdTile - 1) / kRowsPerLdTile;
-        d.n_chunks = (int64_t)pl->chunks.size();
-        d.nnz_hd = 0;
-        for (const HdChunk &ch : pl->chunks) d.nnz_hd += ch.len;
-        d.n_split_rows = (int64_t)pl->split_rows.size();
-        d.n_partials = pl->n_partials;
+        d.n_chunks = sched.n_chunks;
+        d.nnz_hd = sched.nnz_hd;
+        d.n_split_rows = sched.n_split_rows;
+        d.n_partials = sched.n_partials;
         {
             auto at_most = [&](int32_t len) { return offs[std::min<int32_t>(len + 1, T)]; };
             const PipeChoice ch = choose_ld_kernel(tuning().ld_pipeline, n_ld, at_most);
@@ -1231,6 +1209,31 @@ extern "C" groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, co
     if (st != GROOT_OK) return st;
     int err = launch_rows_scatter(ids_dev, n, in_dev, Y_dev, F, hip_stream);
     if (err) return fail(GROOT_EHIP, std::string("groot_rows_scatter: launch failed: ") + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t capacity, int64_t *begin_host,
+                                             int32_t *len_host, int32_t *row_host, int32_t *slot_host)
+{
+    const char *who = "groot_plan_hd_pieces: ";
+    if (!plan) return fail(GROOT_EINVAL, std::string(who) + "NULL plan");
+    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "the plan is not uploaded");
+    const int64_t n = plan->dev.n_chunks;
+    if (capacity < n) return fail(GROOT_EINVAL, std::string(who) + "capacity below the number of pieces");
+    if (n == 0) return GROOT_OK;
+    try {
+        std::vector<HdChunk> chunks((size_t)n);
+        const int err = device_download(chunks.data(), plan->dev.chunks, (size_t)n * sizeof(HdChunk), nullptr);
+        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        for (int64_t c = 0; c < n; ++c) {
+            if (begin_host) begin_host[c] = chunks[c].begin;
+            if (len_host) len_host[c] = chunks[c].len;
+            if (row_host) row_host[c] = chunks[c].row;
+            if (slot_host) slot_host[c] = chunks[c].slot;
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(GROOT_ENOMEM, std::string(who) + "out of host memory");
+    }
     return GROOT_OK;
 }
 

@@ -120,6 +120,17 @@ int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                      int relu, int32_t F_in, int32_t F_out, void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform weights
+// Schedule of the high-degree rows built on the device (groot_hd_sched_device.hip): the pieces in execution order,
+// once with rows named by id and once by their place in the list of high-degree rows, and the split rows likewise.
+struct DeviceHdSchedule {
+    HdChunk *chunks = nullptr, *chunks_rank = nullptr;
+    HdSplitRow *split_rows = nullptr, *split_rows_rank = nullptr;
+    int64_t n_chunks = 0, n_split_rows = 0, n_partials = 0, nnz_hd = 0;
+};
+constexpr int kErrTooManyPieces = -3;
+int launch_hd_schedule_device(const int64_t *rowptr_dev, const int32_t *col_dev, const int32_t *hd_rows_dev, int64_t n_hd,
+                              int32_t hd_chunk, void *stream, DeviceHdSchedule *out);   // synchronises the stream
+void free_device_hd_schedule(DeviceHdSchedule &s);
 // Compact CSR for the pipelined LD kernel, built on the device (groot_compress.hip); synchronises the stream.
 int launch_csr_compress(DevicePlan &dp, const int32_t *hd_rows_dev, int64_t n_hd, void *stream);
 int pipe_compact_prepare();   // once per process, before the first launch with a compact CSR; hipError_t as int

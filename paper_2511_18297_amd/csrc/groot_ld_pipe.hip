@@ -30,7 +30,10 @@
 namespace groot {
 
 constexpr int kPipeWaves = 4;                // wavefronts per workgroup, one workgroup per CU
-constexpr int kPipeGroups = 5;               // lane-group sweeps (register sets) in flight per wavefront (measured best of 2..8)
+// lane-group sweeps (register sets) in flight per wavefront, by lanes per row.  Measured on the headline graph:
+// 16 lanes (F = 64): 16.9 / 14.4 / 14.2 / 13.7 / 14.0 / 13.8 / 13.9 ms for 2..8; 8 lanes (F = 32): 7.8 / 7.0 / 7.6 ms
+// for 4 / 5 / 6; 32 lanes (F = 128): 31.0 / 30.5 / 31.3 ms for 5 / 7 / 8
+constexpr int pipe_groups(int L) { return L == 32 ? 7 : 5; }
 
 __device__ __forceinline__ void pipe_wave_sync()
 {
@@ -292,23 +295,22 @@ static void pipe_launch(const PipeArgs &a)
     }
 }
 
-template <int W, int G, int D>
+template <int W, int D>
 static void pipe_dispatch_l(int32_t F4, const PipeArgs &a)
 {
-    if (F4 == 8) pipe_launch<8, W, G, D>(a);
-    else if (F4 == 16) pipe_launch<16, W, G, D>(a);
-    else pipe_launch<32, W, G, D>(a);
+    if (F4 == 8) pipe_launch<8, W, pipe_groups(8), D>(a);
+    else if (F4 == 16) pipe_launch<16, W, pipe_groups(16), D>(a);
+    else pipe_launch<32, W, pipe_groups(32), D>(a);
 }
 
 template <int W>
 static void pipe_dispatch_d(int depth, int32_t F4, const PipeArgs &a)
 {
-    constexpr int kG = kPipeGroups;
     switch (depth) {
-    case 5: pipe_dispatch_l<W, kG, 5>(F4, a); break;
-    case 6: pipe_dispatch_l<W, kG, 6>(F4, a); break;
-    case 7: pipe_dispatch_l<W, kG, 7>(F4, a); break;
-    default: pipe_dispatch_l<W, kG, 8>(F4, a); break;
+    case 5: pipe_dispatch_l<W, 5>(F4, a); break;
+    case 6: pipe_dispatch_l<W, 6>(F4, a); break;
+    case 7: pipe_dispatch_l<W, 7>(F4, a); break;
+    default: pipe_dispatch_l<W, 8>(F4, a); break;
     }
 }
 
@@ -318,7 +320,7 @@ static void pipe_dispatch_d(int depth, int32_t F4, const PipeArgs &a)
 template <int L, int W, int D>
 static int pipe_allow_lds()
 {
-    return (int)hipFuncSetAttribute((const void *)&ld_pipe_kernel<L, W, kPipeGroups, D, true>,
+    return (int)hipFuncSetAttribute((const void *)&ld_pipe_kernel<L, W, pipe_groups(L), D, true>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kCodeMaxHot * (int)sizeof(int32_t));
 }
 template <int W, int D>
@@ -362,7 +364,7 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     if (e != hipSuccess) return (int)e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
-    const int tile_rows = kPipeGroups * (kWave / F4);
+    const int tile_rows = pipe_groups(F4) * (kWave / F4);
     const int64_t n_tiles = (dp.n + tile_rows - 1) / tile_rows;
     // one workgroup per CU; consecutive workgroup ids land on different XCDs
     int64_t n_wg = cus / kXcds * kXcds;
@@ -376,7 +378,8 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
-    static_assert(kPipeGroups * kWave * 16 <= kTrashFloats * 4, "a tile's masked sums fit the trash area");
+    static_assert(pipe_groups(8) <= 8 && pipe_groups(16) <= 8 && pipe_groups(32) <= 8 && 8 * kWave * 16 <= kTrashFloats * 4,
+                  "a tile's masked sums fit the trash area");
     hipStream_t st = (hipStream_t)stream;
     const bool compact = dp.compressed && dp.rp32 && dp.col16 && dp.hot_cols;
     const PipeArgs a{dp.rowptr, col_arg, val_arg, CompactCsr{dp.rp32, dp.col16, dp.hot_cols, dp.n_hot}, compact,

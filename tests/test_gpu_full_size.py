@@ -284,7 +284,7 @@ def _progress(msg):
         pass
 
 
-def _stress_case(torch, log2n, thresholds):
+def _stress_case(torch, log2n, thresholds, every_element_at=None):
     import time
 
     n, Fw = 1 << log2n, 128
@@ -317,6 +317,12 @@ def _stress_case(torch, log2n, thresholds):
         torch.cuda.synchronize()
         assert not bool(torch.isnan(Y).any())
         assert_close_to_oracle(Y[rows_dev].cpu().numpy(), Y64, S, f"stress 2^{log2n} T={T_sweep}")
+        if T_sweep == every_element_at:          # the whole result against the oracle on the whole graph
+            t0 = time.time()
+            full64, fullS = oracle.spmm_f64(s.rowptr, s.col, s.val, X.cpu().numpy())
+            _progress(f"  T={T_sweep}: oracle over all {n} rows in {time.time() - t0:.0f} s")
+            assert_close_to_oracle(Y.cpu().numpy(), full64, fullS, f"stress 2^{log2n} T={T_sweep}, every element")
+            del full64, fullS
         if log2n >= 24:          # the full-size instance also reports its time
             start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             start.record()
@@ -335,8 +341,9 @@ def _stress_case(torch, log2n, thresholds):
 def test_config5_stress_graph_long_rows(torch_cuda):
     """Polarized stress workload at 2^20 rows with the full degree law (Zipf(1.2) draws clipped to
     [64, 262144], F = 128): rows of up to ~230k stored entries are cut into hundreds of pieces.
-    Sampled rows (every class, the longest rows) against the oracle; threshold sweep as in the workload."""
-    _stress_case(torch_cuda, 20, (16, 32, 64, 128))
+    Sampled rows (every class, the longest rows) against the oracle at every threshold of the sweep, and every
+    element of the result at T = 32."""
+    _stress_case(torch_cuda, 20, (16, 32, 64, 128), every_element_at=32)
 
 
 def _huge_case_fits(torch):

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import assert_close_to_oracle, ensure_built
+from util import assert_close_to_oracle, ensure_built, layer_tolerance
 
 pytestmark = pytest.mark.gpu
 
@@ -238,6 +238,64 @@ def test_device_built_plan_with_split_high_degree_rows_and_nested_partition(torc
     for p in range(3):
         _check_part(torch, plan, want["rowptr"], want["col"], want["val"], sub_part_of, 3, p, G.GROOT_REGROW, 2,
                     True, "nested")
+
+
+@pytest.mark.parametrize("T,hd_chunk", [(32, 512), (16, 64), (200, 300)])
+def test_device_built_schedule_of_high_degree_rows_is_the_host_plans(torch_cuda, T, hd_chunk):
+    """The launch list of the HD kernel that groot_dev_part_plan cuts and orders on the device, against the list
+    a host plan makes from the oracle's copy of the same sub-graph: piece by piece, bit for bit (rows of one and
+    of many pieces, piece sizes 64, 300 and 512).  The fused layer on the device-built plan (its high-degree sums
+    go through the schedule that names rows by rank) against the fp64 layer."""
+    torch = torch_cuda
+    rng = np.random.default_rng(5)
+    s = wl.stress_graph(6, 1 << 14, window=64, dmin=64, dmax=4096)
+    w = rng.random(len(s.col)).astype(np.float32)
+    g = G.groot_graph_from_csr(s.rowptr, s.col, w)
+    full = _resident_plan(g, 32, 64)
+    part_of = oracle.part_of_default(s.n, s.n, 2)
+    want = oracle.regrow_part(s.rowptr, s.col, w, part_of, 0, G.GROOT_REGROW, 2)
+    n_loc = want["n_owned"] + want["n_halo"]
+    G.groot_set_tuning("hd_chunk", hd_chunk)
+    try:
+        print(f"device HD schedule: T={T} hd_chunk={hd_chunk} rows={n_loc}", flush=True)
+        part = G.groot_partition_regrow_device(full, 2, 0)
+        dev_plan = G.groot_dev_part_plan(part, T, 64)
+        sub = G.groot_graph_from_csr(want["rowptr"], want["col"], want["val"])
+        host_plan = G.groot_spmm_plan(sub, T)
+        G.groot_plan_upload(host_plan, 64)
+    finally:
+        G.groot_set_tuning("hd_chunk", 512)
+    got, ref = G.groot_plan_hd_pieces(dev_plan), G.groot_plan_hd_pieces(host_plan)
+    deg = np.diff(want["rowptr"])
+    hd = deg[deg >= T]
+    pieces = np.maximum(1, -(-hd // hd_chunk))
+    assert len(ref["row"]) == int(pieces.sum()) and (pieces > 1).any() and (pieces == 1).any()
+    for k in ("begin", "len", "row", "slot"):
+        assert np.array_equal(got[k], ref[k]), (k, T, hd_chunk)
+    for k in ("hd_pieces", "hd_partials", "nnz_hd"):
+        assert G.groot_plan_query(dev_plan, k) == G.groot_plan_query(host_plan, k), k
+    assert G.groot_plan_query(dev_plan, "nnz_hd") == int(hd.sum())
+    # every entry of every high-degree row is in exactly one piece
+    covered = np.zeros(len(want["col"]), np.int32)
+    for b, ln in zip(got["begin"], got["len"]):
+        covered[b:b + ln] += 1
+    is_hd = np.repeat(deg >= T, deg)
+    assert np.array_equal(covered, is_hd.astype(np.int32))
+    # fused layer on the device-built plan
+    F = 64
+    X = wl.uniform_features_numpy(9, 0, n_loc, F)
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
+    b = rng.uniform(-0.125, 0.125, F).astype(np.float32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    H = torch.full((n_loc, F), float("nan"), device="cuda")
+    G.groot_sage_layer_forward(dev_plan, dev(X), dev(Wn), dev(Ws), dev(b), True, H, F)
+    torch.cuda.synchronize()
+    ref_H, A, S = oracle.sage_layer_f64(want["rowptr"], want["col"], want["val"], X, Wn, Ws, b, True)
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale = np.abs(A) @ a64(Wn) + a64(X) @ a64(Ws) + a64(b)
+    err = np.abs(H.cpu().numpy().astype(np.float64) - ref_H)
+    tol = layer_tolerance(S, scale, a64(Wn))
+    assert np.isfinite(err).all() and (err <= tol).all(), float(np.max(err / tol))
 
 
 def test_error_paths(torch_cuda):

@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import assert_close_to_oracle, ensure_built
+from util import assert_close_to_oracle, ensure_built, layer_tolerance
 
 pytestmark = pytest.mark.gpu
 
@@ -279,16 +279,6 @@ def sage_variant(request):
     yield request.param
     G.groot_set_tuning("sage_kernel", 1)
     G.groot_set_tuning("sage_split", 1)
-
-
-def layer_tolerance(S, scale, absWn, floor=1e-6):
-    """Accepted deviation of the fused layer from the fp64 layer, element by element.  The aggregation's own
-    bar, 1e-5 * sum|a_ij x_jk| + 1e-6 per element of A_hat X, reaches the output through |Wn|; the dense part
-    is an fp32 sum of 2F + 1 <= 129 terms (two products per input feature and the bias) whose rounding error
-    is at most (2F + 2) * 2^-24 <= 7.8e-6 of the sum of their magnitudes in any order of summation, each
-    product being exact to 2^-23 of itself: together below 1e-5 * scale, scale = |A_hat X| |Wn| + |X| |Ws| + |b|,
-    the same coefficient as the aggregation's bar."""
-    return (1e-5 * S + floor) @ absWn + 1e-5 * scale + floor
 
 
 def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64, F_out=None):

@@ -29,3 +29,13 @@ def assert_close_to_oracle(Y_gpu, Y64, S, what=""):
         raise AssertionError(f"{what}: {bad.sum()} elements out of tolerance, first at row {i} col {k}: "
                              f"gpu {Y_gpu[i, k]!r} oracle {Y64[i, k]!r} tol {tol[i, k]!r}")
     return float(np.max(err / tol))
+
+
+def layer_tolerance(S, scale, absWn, floor=1e-6):
+    """Accepted deviation of the fused layer from the fp64 layer, element by element.  The aggregation's own
+    bar, 1e-5 * sum|a_ij x_jk| + 1e-6 per element of A_hat X, reaches the output through |Wn|; the dense part
+    is an fp32 sum of 2F + 1 <= 129 terms (two products per input feature and the bias) whose rounding error
+    is at most (2F + 2) * 2^-24 <= 7.8e-6 of the sum of their magnitudes in any order of summation, each
+    product being exact to 2^-23 of itself: together below 1e-5 * scale, scale = |A_hat X| |Wn| + |X| |Ws| + |b|,
+    the same coefficient as the aggregation's bar."""
+    return (1e-5 * S + floor) @ absWn + 1e-5 * scale + floor
