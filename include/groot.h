@@ -402,8 +402,11 @@ groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t 
  * Paper: Section "Kernel Design - GROOT-GPU" (static split of a high-degree
  * row's non-zeros).  For tests and diagnostics: a plan made on the device
  * (groot_dev_part_plan) carries the same list, bit for bit, as a host plan of
- * the same sub-graph.  Synchronous.  Errors: EINVAL (NULL plan, plan not
- * uploaded, capacity below "hd_pieces"), EHIP. */
+ * the same sub-graph.  A plan made by groot_spmm_plan answers before its
+ * upload too, from the host copy of the list that the upload will send (so do
+ * "hd_pieces" and "hd_partials" of groot_plan_query).  Synchronous.  Errors:
+ * EINVAL (NULL plan, a device-built plan that is gone from the device,
+ * capacity below "hd_pieces"), EHIP. */
 groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t capacity, int64_t *begin_host,
                                   int32_t *len_host, int32_t *row_host, int32_t *slot_host);
 

@@ -1217,14 +1217,18 @@ extern "C" groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t cap
 {
     const char *who = "groot_plan_hd_pieces: ";
     if (!plan) return fail(GROOT_EINVAL, std::string(who) + "NULL plan");
-    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "the plan is not uploaded");
-    const int64_t n = plan->dev.n_chunks;
+    if (!plan->resident && !plan->g) return fail(GROOT_EINVAL, std::string(who) + "the plan is not uploaded");
+    const int64_t n = plan->resident ? plan->dev.n_chunks : (int64_t)plan->chunks.size();
     if (capacity < n) return fail(GROOT_EINVAL, std::string(who) + "capacity below the number of pieces");
     if (n == 0) return GROOT_OK;
     try {
         std::vector<HdChunk> chunks((size_t)n);
-        const int err = device_download(chunks.data(), plan->dev.chunks, (size_t)n * sizeof(HdChunk), nullptr);
-        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        if (plan->resident) {
+            const int err = device_download(chunks.data(), plan->dev.chunks, (size_t)n * sizeof(HdChunk), nullptr);
+            if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        } else {
+            chunks = plan->chunks;                      // a host plan before its upload: the list it will upload
+        }
         for (int64_t c = 0; c < n; ++c) {
             if (begin_host) begin_host[c] = chunks[c].begin;
             if (len_host) len_host[c] = chunks[c].len;
@@ -1240,8 +1244,12 @@ extern "C" groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t cap
 extern "C" groot_status groot_plan_query(const groot_plan *plan, const char *what, int64_t *value)
 {
     if (!plan || !what || !value) return fail(GROOT_EINVAL, "groot_plan_query: NULL argument");
-    if (!plan->resident) return fail(GROOT_EINVAL, "groot_plan_query: plan is not on the device (call groot_plan_upload)");
     const std::string k(what);
+    if (!plan->resident && plan->g && (k == "hd_pieces" || k == "hd_partials")) {
+        *value = k == "hd_pieces" ? (int64_t)plan->chunks.size() : plan->n_partials;
+        return GROOT_OK;                                  // the schedule of a host plan, before its upload
+    }
+    if (!plan->resident) return fail(GROOT_EINVAL, "groot_plan_query: plan is not on the device (call groot_plan_upload)");
     if (k == "ld_pipelined") *value = plan->dev.ld_pipelined;
     else if (k == "weight_mode") *value = plan->dev.weight_mode;
     else if (k == "hd_pieces") *value = plan->dev.n_chunks;

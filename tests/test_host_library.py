@@ -157,6 +157,47 @@ def test_plan_bit_exact_on_stress_graph(T):
         assert np.array_equal(pv[k], w), k
 
 
+@pytest.mark.parametrize("T,hd_chunk", [(16, 512), (32, 64), (128, 300)])
+def test_schedule_of_the_high_degree_rows(T, hd_chunk):
+    """The HD kernel's launch list of a host plan (Section "Kernel Design - GROOT-GPU": the non-zeros of a
+    high-degree row are split statically): every stored entry of every high-degree row lies in exactly one piece,
+    a row of d entries has ceil(d / hd_chunk) balanced pieces, the partial-sum slots of a split row are one run,
+    and the pieces run in the order of their first column (ties in row order)."""
+    g0 = wl.stress_graph(4, 1 << 15, window=256, dmin=64, dmax=4096)
+    g = G.groot_graph_from_csr(g0.rowptr, g0.col, g0.val)
+    G.groot_set_tuning("hd_chunk", hd_chunk)
+    try:
+        plan = G.groot_spmm_plan(g, T)
+    finally:
+        G.groot_set_tuning("hd_chunk", 512)
+    pc = G.groot_plan_hd_pieces(plan)                    # before any upload: the host copy
+    deg = np.diff(g0.rowptr)
+    hd_rows = np.flatnonzero(deg >= T)
+    pieces_of = np.maximum(1, -(-deg[hd_rows] // hd_chunk))
+    assert len(pc["row"]) == int(pieces_of.sum()) == G.groot_plan_query(plan, "hd_pieces")
+    assert G.groot_plan_query(plan, "hd_partials") == int(pieces_of[pieces_of > 1].sum())
+    covered = np.zeros(len(g0.col), np.int32)
+    for b, ln, r in zip(pc["begin"], pc["len"], pc["row"]):
+        assert g0.rowptr[r] <= b and b + ln <= g0.rowptr[r + 1] and 0 < ln <= hd_chunk
+        covered[b:b + ln] += 1
+    assert np.array_equal(covered, np.repeat(deg >= T, deg).astype(np.int32))
+    first_col = g0.col[pc["begin"]]
+    assert (np.diff(first_col) >= 0).all()
+    ties = np.flatnonzero(np.diff(first_col) == 0)
+    assert ((pc["row"][ties] < pc["row"][ties + 1]) |
+            ((pc["row"][ties] == pc["row"][ties + 1]) & (pc["begin"][ties] < pc["begin"][ties + 1]))).all()
+    for r, count in zip(hd_rows, pieces_of):
+        mine = np.flatnonzero(pc["row"] == r)
+        assert len(mine) == count
+        lens = pc["len"][mine]
+        assert lens.max() - lens.min() <= -(-deg[r] // count) - deg[r] // count + (count - 1)   # balanced
+        slots = np.sort(pc["slot"][mine])
+        if count == 1:
+            assert slots[0] == -1
+        else:
+            assert slots[0] >= 0 and np.array_equal(slots, slots[0] + np.arange(count))
+
+
 def _compare_parts(g, rowptr, col, val, part_of, P, flags, weight_mode):
     parts = G.groot_partition_regrow(g, P, part_of, flags)
     assert G.groot_parts_count(parts) == P
