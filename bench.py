@@ -57,19 +57,24 @@ STRESS_THRESHOLDS = (16, 32, 64, 128)
 TRAFFIC = {
     # FETCH_SIZE 26,674,394 KiB x 2.000 (scale of the 34.33 GB device copy in the same run), WRITE_SIZE 33,512,882 KiB x 1.000
     ("csa1024_b16_F64", "ld_pipe_kernel"): {"bytes": 88.95e9, "read": 54.63e9, "written": 34.32e9,
-                                            "sources_sha16": "86f794266c0650b4"},
+                                            "sources_sha16": "a37aa27e4c7bf7b3"},
 }
 KERNEL_SOURCES = ("groot_device.h", "groot_kernels.hip", "groot_ld_pipe.hip", "groot_compress.hip")
 
 
 def kernel_sources_sha16():
-    """Hash of the sources of the aggregation kernels (the files a traffic measurement depends on)."""
+    """Hash of the code of the aggregation kernels (the files a traffic measurement depends on), comments and
+    white space left out: a reworded comment does not make a measurement stale, a changed statement does."""
     import hashlib
+    import re
 
     h = hashlib.sha256()
     for name in KERNEL_SOURCES:
-        with open(os.path.join(ROOT, "paper_2511_18297_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2511_18297_amd", "csrc", name), "r") as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", " ", text, flags=re.S)         # none of these sources holds "//" or "/*" in a string
+        text = re.sub(r"//[^\n]*", " ", text)
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()[:16]
 
 

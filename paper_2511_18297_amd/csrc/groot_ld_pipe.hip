@@ -3,7 +3,7 @@
 //
 // One persistent workgroup of four wavefronts per CU, i.e. one wavefront per SIMD.  Every wavefront walks
 // its own tiles of G lane groups x (64 / L) rows (L = F / 4 lanes per row) and keeps a whole tile in
-// flight: G register sets of D gathered float4 each (D = 6 or 8 slots per row, chosen per plan).  Right
+// flight: G register sets of D gathered float4 each (D = 5 to 8 slots per row, chosen per plan).  Right
 // after the rows of a group of tile t have been summed and stored, the same register set is loaded with
 // the group's rows of tile t+1, so the wavefront never waits with nothing in flight.  Compared with the
 // plain LD kernel (32 wavefronts per CU, four rows in flight each, all of them drained at every tile) this
@@ -22,7 +22,8 @@
 //    its sum is stored to a trash area instead of Y (an address select, not a branch); the high-degree
 //    kernel, or the row-list kernel below for low-degree rows longer than D, computes it.  Only the ragged
 //    last tile is masked as a whole and redone by a plain, unoverlapped path.
-//  * No workgroup barrier anywhere: wavefronts share nothing.
+//  * No workgroup barrier after the start (the list of hot rows is copied to LDS once): wavefronts share
+//    nothing else.
 #include <type_traits>
 
 #include "groot_device.h"
