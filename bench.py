@@ -282,11 +282,15 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name
 
 
 def choose_placement(G, torch, plan, X, Y, F, tries):
-    """Where the driver puts a multi-gigabyte buffer changes the step time by up to 7 % on this machine (the same
-    kernels on the same data: 14.3 to 15.3 ms on the headline graph from one allocation to the next, unchanged by
-    offsets inside an allocation, so it is a property of the physical pages an allocation receives; neither the
-    address nor a larger alignment predicts it).  Before anything is timed, a few more allocations of Y, then of X,
-    are tried with three steps each and the fastest pair is kept; the others are released.  -> X, Y, log"""
+    """Where the feature matrices lie in device memory changes the step time by up to 7 % on this machine, the same
+    kernels on the same data: the memory behaves as (at least) two regions of tens of gigabytes, and a step whose X
+    and Y lie in the same region is slower than one that reads from one region and writes to the other (LD kernel
+    13.9-14.1 ms against 12.9-13.2 ms on the headline graph; slots of one 206 GB allocation fall into the classes
+    {0, 1, 4} and {2, 3, 5}; shifts of less than the region size change nothing).  The region of an address is not
+    visible to a program, so before anything is timed `tries` more buffers of the size of X are allocated, every
+    ordered pair of buffers (X in one, Y in the other) runs three steps, and the fastest pair is kept; the rest
+    is released.  A caller that reuses its feature buffers over many layers and epochs can do the same once.
+    -> X, Y, log"""
     def quick(Xc, Yc):
         G.groot_spmm_execute(plan, Xc, Yc, F)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -298,32 +302,37 @@ def choose_placement(G, torch, plan, X, Y, F, tries):
         return a.elapsed_time(b) / 3
 
     size = X.numel() * X.element_size()
-    log = {"y_ms": [round(quick(X, Y), 3)], "x_ms": []}
-    best = log["y_ms"][0]
-    for which in ("y", "x"):
-        free, _ = torch.cuda.mem_get_info()
-        n_try = max(0, min(tries, int(free // size) - 1))
-        losers = []
-        for _ in range(n_try):
-            cand = torch.empty_like(X)
-            if which == "x":
-                cand.copy_(X)
-            ms = quick(X, cand) if which == "y" else quick(cand, Y)
-            log[which + "_ms"].append(round(ms, 3))
-            if ms < best:
-                best = ms
-                if which == "y":
-                    losers.append(Y)
-                    Y = cand
-                else:
-                    losers.append(X)
-                    X = cand
-            else:
-                losers.append(cand)
-        del losers
-        torch.cuda.empty_cache()
-    log["kept_ms"] = round(best, 3)
-    return X, Y, log
+    free, _ = torch.cuda.mem_get_info()
+    n_more = max(0, min(tries, int(free // size) - 1))
+    bufs = [X, Y] + [torch.empty_like(X) for _ in range(n_more)]
+    ms = [[None] * len(bufs) for _ in bufs]
+    clean = {0}                                          # buffers that hold the features (a buffer used as Y loses them)
+
+    def pair(i, j):
+        if i not in clean:                               # X of the pair must hold the features
+            src = next(c for c in clean)
+            bufs[i].copy_(bufs[src])
+            clean.add(i)
+        t = quick(bufs[i], bufs[j])
+        clean.discard(j)
+        ms[i][j] = round(t, 3)
+        return t
+
+    best = (pair(0, 1), 0, 1)
+    for i in range(len(bufs)):
+        for j in range(len(bufs)):
+            if i == j or (i, j) == (0, 1):
+                continue
+            t = pair(i, j)
+            if t < best[0]:
+                best = (t, i, j)
+    _, i, j = best
+    if i not in clean:
+        bufs[i].copy_(bufs[next(c for c in clean)])
+    Xk, Yk = bufs[i], bufs[j]
+    del bufs
+    torch.cuda.empty_cache()
+    return Xk, Yk, {"buffers": 2 + n_more, "pair_ms_x_row_y_column": ms, "kept_x_y": [i, j], "kept_ms": round(best[0], 3)}
 
 
 def stress_bench(args, G, torch, np, wl, name, props):
