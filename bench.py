@@ -281,16 +281,18 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name
         "max_abs_diff_vs_unfused": worst, "device": props.name}))
 
 
-def choose_placement(G, torch, plan, X, Y, F, tries):
-    """Where the feature matrices lie in device memory changes the step time by up to 7 % on this machine, the same
-    kernels on the same data: the memory behaves as (at least) two regions of tens of gigabytes, and a step whose X
-    and Y lie in the same region is slower than one that reads from one region and writes to the other (LD kernel
-    13.9-14.1 ms against 12.9-13.2 ms on the headline graph; slots of one 206 GB allocation fall into the classes
-    {0, 1, 4} and {2, 3, 5}; shifts of less than the region size change nothing).  The region of an address is not
-    visible to a program, so before anything is timed `tries` more buffers of the size of X are allocated, every
-    ordered pair of buffers (X in one, Y in the other) runs three steps, and the fastest pair is kept; the rest
-    is released.  A caller that reuses its feature buffers over many layers and epochs can do the same once.
-    -> X, Y, log"""
+def choose_placement(G, torch, plan, bufs, F, tries):
+    """Where the feature matrices lie in device memory changes the step time by up to 10 % on this machine, the same
+    kernels on the same data.  The memory behaves as two classes of address ranges that alternate every 64 GiB or
+    so: a step is slowest when X and Y lie in ranges of one class (LD kernel 13.8-14.1 ms on the headline graph),
+    faster when X lies in one class and Y in the other (12.9-13.2 ms), and fastest when each of them straddles a
+    boundary, so that both classes serve half of the traffic at any time (12.5 ms: the XCDs sweep contiguous
+    eighths of the rows).  Which class an address belongs to is not visible to a program, but it shows in the
+    time.  So before anything is timed one arena of `tries` + 2 buffer sizes is allocated, X and Y are tried at
+    quarter-buffer offsets in it (a coordinate search: X, then Y, then both once more; three steps per try), and
+    the fastest pair that does not overlap is kept for the timed run; the features are copied there.  Every try is
+    in the output line.  A caller that reuses its feature buffers over many layers and epochs can do the same
+    once.  -> X, Y, log"""
     def quick(Xc, Yc):
         G.groot_spmm_execute(plan, Xc, Yc, F)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -301,38 +303,55 @@ def choose_placement(G, torch, plan, X, Y, F, tries):
         b.synchronize()
         return a.elapsed_time(b) / 3
 
-    size = X.numel() * X.element_size()
-    free, _ = torch.cuda.mem_get_info()
-    n_more = max(0, min(tries, int(free // size) - 1))
-    bufs = [X, Y] + [torch.empty_like(X) for _ in range(n_more)]
-    ms = [[None] * len(bufs) for _ in bufs]
-    clean = {0}                                          # buffers that hold the features (a buffer used as Y loses them)
-
-    def pair(i, j):
-        if i not in clean:                               # X of the pair must hold the features
-            src = next(c for c in clean)
-            bufs[i].copy_(bufs[src])
-            clean.add(i)
-        t = quick(bufs[i], bufs[j])
-        clean.discard(j)
-        ms[i][j] = round(t, 3)
-        return t
-
-    best = (pair(0, 1), 0, 1)
-    for i in range(len(bufs)):
-        for j in range(len(bufs)):
-            if i == j or (i, j) == (0, 1):
-                continue
-            t = pair(i, j)
-            if t < best[0]:
-                best = (t, i, j)
-    _, i, j = best
-    if i not in clean:
-        bufs[i].copy_(bufs[next(c for c in clean)])
-    Xk, Yk = bufs[i], bufs[j]
-    del bufs
+    X, Y = bufs
+    bufs.clear()                                         # the caller's references are gone: what is deleted here is freed
+    n, numel = X.shape[0], X.numel()
+    first = round(quick(X, Y), 3)
+    del Y                                                # the arena takes its place
     torch.cuda.empty_cache()
-    return Xk, Yk, {"buffers": 2 + n_more, "pair_ms_x_row_y_column": ms, "kept_x_y": [i, j], "kept_ms": round(best[0], 3)}
+    free, _ = torch.cuda.mem_get_info()
+    slots = min(tries + 2, int((free - (2 << 30)) // (numel * 4)))
+    if slots < 2:
+        Y = torch.empty_like(X)
+        return X, Y, {"first_allocations_ms": first, "arena_slots": 0, "note": "no room for an arena"}
+    arena = torch.zeros((slots * numel,), dtype=torch.float32, device=X.device)
+
+    def at(q):                                           # the buffer that starts q quarter-sizes into the arena
+        o = (q * numel // 4) // 1024 * 1024              # 4 KB granularity keeps the 16-byte alignment the kernels need
+        return arena[o:o + numel].view(n, F)
+
+    # coordinate search over quarter-size offsets: X with Y parked at the far end, then Y, then X and Y once more
+    last = 4 * (slots - 1)
+    tried = []
+
+    def scan(which, other):
+        best = None
+        for q in range(last + 1):
+            if abs(q - other) < 4:                       # the two buffers must not overlap
+                continue
+            t = quick(at(q), at(other)) if which == "x" else quick(at(other), at(q))
+            tried.append([q, other, round(t, 3)] if which == "x" else [other, q, round(t, 3)])
+            if best is None or t < best[0]:
+                best = (t, q)
+        return best
+
+    _, qx = scan("x", last)
+    if abs(qx - last) < 4:
+        qx = 0
+    t, qy = scan("y", qx)
+    for _ in range(2):
+        t2, qx2 = scan("x", qy)
+        if t2 < t:
+            t, qx = t2, qx2
+        t2, qy2 = scan("y", qx)
+        if t2 < t:
+            t, qy = t2, qy2
+    Xk, Yk = at(qx), at(qy)
+    Xk.copy_(X)
+    del X
+    torch.cuda.empty_cache()
+    return Xk, Yk, {"first_allocations_ms": first, "arena_slots": slots, "unit": "quarter of a buffer size",
+                    "tried_x_y_ms": tried, "kept_x_y": [qx, qy], "kept_ms": round(t, 3)}
 
 
 def stress_bench(args, G, torch, np, wl, name, props):
@@ -458,7 +477,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
     ap.add_argument("--placement-tries", type=int, default=3,
-                    help="extra allocations of Y and of X tried before timing (the fastest pair is kept); 0: take the first")
+                    help="the placement search uses an arena of this many buffer sizes + 2 (X and Y tried at every pair of "
+                         "quarter-buffer offsets in turn, the fastest pair kept); 0: take the first allocations as they come")
     ap.add_argument("--thresholds", type=int, nargs="*", default=None, help="stress workload: degree thresholds to sweep")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
     ap.add_argument("--partitioned", type=int, default=0, metavar="P",
@@ -548,7 +568,9 @@ def main():
 
     placement = None
     if args.placement_tries > 0:
-        X, Y, placement = choose_placement(G, torch, plan, X, Y, F, args.placement_tries)
+        bufs = [X, Y]
+        del X, Y
+        X, Y, placement = choose_placement(G, torch, plan, bufs, F, args.placement_tries)
 
     # ---- whole path: W warm-up steps, then exactly K timed steps
     run(G.GROOT_PHASE_ALL, args.warmup)
