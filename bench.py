@@ -223,13 +223,14 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
         "device": props.name}))
 
 
-def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props):
-    """Fused layer against the unfused form (library SpMM, then torch for the dense part)."""
+def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name, props, placement):
+    """Fused layer (X -> H, the pair of buffers the placement search kept) against the unfused form (library SpMM
+    into a buffer of its own, then torch for the dense part)."""
     assert F in (32, 64), "the fused layer is built for F = 64 and F = 32"
     gen = torch.Generator(device="cuda").manual_seed(2)
     Wn, Ws = ((torch.rand((F, F), generator=gen, device="cuda") - 0.5) * 0.25 for _ in range(2))
     b = (torch.rand(F, generator=gen, device="cuda") - 0.5) * 0.25
-    H = torch.empty_like(X)
+    Y = torch.empty_like(X)
 
     def fused():
         G.groot_sage_layer_forward(plan, X, Wn, Ws, b, True, H, F)
@@ -278,7 +279,7 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name
                      "algorithmic_bytes": bytes_layer},
         "fp32_equivalent_tflops": round(tflops, 2), "fp32_mfma_peak_tflops": 157.3,
         "unfused_ms_per_step": round(ms_unfused, 4), "speedup_vs_unfused": round(ms_unfused / ms_fused, 3),
-        "max_abs_diff_vs_unfused": worst, "device": props.name}))
+        "max_abs_diff_vs_unfused": worst, "placement": placement, "device": props.name}))
 
 
 def choose_placement(G, torch, plan, bufs, F, tries):
@@ -563,7 +564,12 @@ def main():
         partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props)
         return
     if args.sage_layer:
-        sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props)
+        placement = None
+        if args.placement_tries > 0:                     # X and the layer's output where the aggregation runs fastest
+            bufs = [X, Y]
+            del X, Y
+            X, Y, placement = choose_placement(G, torch, plan, bufs, F, min(args.placement_tries, 2))
+        sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props, placement)
         return
 
     placement = None
