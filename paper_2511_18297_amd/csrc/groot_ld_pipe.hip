@@ -32,9 +32,11 @@ namespace groot {
 
 constexpr int kPipeWaves = 4;                // wavefronts per workgroup, one workgroup per CU
 // lane-group sweeps (register sets) in flight per wavefront, by lanes per row.  Measured on the headline graph:
-// 16 lanes (F = 64): 16.9 / 14.4 / 14.2 / 13.7 / 14.0 / 13.8 / 13.9 ms for 2..8; 8 lanes (F = 32): 7.8 / 7.0 / 7.6 ms
-// for 4 / 5 / 6; 32 lanes (F = 128): 31.0 / 30.5 / 31.3 ms for 5 / 7 / 8
-constexpr int pipe_groups(int L) { return L == 32 ? 7 : 5; }
+// 16 lanes (F = 64), LD kernels with X and Y where they run fastest: 13.08 / 12.75 / 12.94 / 12.63 / 12.75 ms for
+// 4 / 5 / 6 / 7 / 8 (with both matrices in one class of address ranges 5 was the best: 16.9 / 14.4 / 14.2 / 13.7 /
+// 14.0 / 13.8 / 13.9 ms for 2..8); 8 lanes (F = 32): 6.46 / 6.36 ms for 5 / 7; 32 lanes (F = 128): 31.0 / 30.5 /
+// 31.3 ms per step for 5 / 7 / 8
+constexpr int pipe_groups(int) { return 7; }
 
 __device__ __forceinline__ void pipe_wave_sync()
 {
