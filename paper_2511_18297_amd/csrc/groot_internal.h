@@ -165,10 +165,7 @@ constexpr int kErrBadPartId = -2;   // a caller-supplied part id outside [0, P)
 int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int32_t *part_of_dev, int32_t p,
                          int regrow, void *stream, DevicePart *out);
 void free_device_part(DevicePart &part);
-// Small synchronous device reads for the high-degree schedule of a plan built from device arrays.
-int device_row_extents(const int64_t *rowptr_dev, const int32_t *rows_dev, int64_t n_rows, int64_t *begin_host,
-                       int64_t *end_host, void *stream);
-int device_gather_col(const int32_t *col_dev, const int64_t *idx_host, int64_t n_idx, int32_t *out_host, void *stream);
+// Small synchronous device reads and copies (sizes and lists of a plan built from device arrays).
 int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream);
 int device_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream);   // device to device, synchronous
 const char *hip_error_text(int err);

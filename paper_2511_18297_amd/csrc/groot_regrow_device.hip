@@ -470,27 +470,6 @@ __global__ __launch_bounds__(kBlock) void rg_fill_long(RgGraph g, const int32_t 
     }
 }
 
-// begin[k] = rowptr[rows[k]], end[k] = rowptr[rows[k] + 1]
-__global__ __launch_bounds__(kBlock) void rg_row_extents(const int64_t *__restrict__ rowptr,
-                                                         const int32_t *__restrict__ rows, int64_t n_rows,
-                                                         int64_t *__restrict__ begin, int64_t *__restrict__ end)
-{
-    const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (k < n_rows) {
-        const int32_t r = rows[k];
-        begin[k] = rowptr[r];
-        end[k] = rowptr[r + 1];
-    }
-}
-
-// out[k] = col[idx[k]]
-__global__ __launch_bounds__(kBlock) void rg_gather_col(const int32_t *__restrict__ col, const int64_t *__restrict__ idx,
-                                                        int64_t n_idx, int32_t *__restrict__ out)
-{
-    const int64_t k = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (k < n_idx) out[k] = col[idx[k]];
-}
-
 namespace {
 
 inline unsigned rg_grid(int64_t items, int per_block) { return (unsigned)((items + per_block - 1) / per_block); }
@@ -611,42 +590,6 @@ int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int3
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return done((int)e);   // the scratch is freed on return
     *out = part;
     return 0;
-}
-
-// begin/end (host, n_rows each) of the rows listed in rows_dev
-int device_row_extents(const int64_t *rowptr_dev, const int32_t *rows_dev, int64_t n_rows, int64_t *begin_host,
-                       int64_t *end_host, void *stream)
-{
-    if (n_rows <= 0) return 0;
-    hipStream_t st = (hipStream_t)stream;
-    Scratch scratch;
-    int64_t *b = nullptr, *e = nullptr;
-    if (!scratch.get(&b, (size_t)n_rows) || !scratch.get(&e, (size_t)n_rows)) return kErrOutOfDeviceMemory;
-    rg_row_extents<<<dim3(rg_grid(n_rows, kBlock)), dim3(kBlock), 0, st>>>(rowptr_dev, rows_dev, n_rows, b, e);
-    hipError_t err = hipGetLastError();
-    if (err == hipSuccess) err = hipMemcpyAsync(begin_host, b, (size_t)n_rows * sizeof(int64_t), hipMemcpyDeviceToHost, st);
-    if (err == hipSuccess) err = hipMemcpyAsync(end_host, e, (size_t)n_rows * sizeof(int64_t), hipMemcpyDeviceToHost, st);
-    hipError_t err2 = hipStreamSynchronize(st);
-    return (int)(err != hipSuccess ? err : err2);
-}
-
-// out_host[k] = col_dev[idx_host[k]]; every index must lie inside col_dev (the caller checks)
-int device_gather_col(const int32_t *col_dev, const int64_t *idx_host, int64_t n_idx, int32_t *out_host, void *stream)
-{
-    if (n_idx <= 0) return 0;
-    hipStream_t st = (hipStream_t)stream;
-    Scratch scratch;
-    int64_t *idx = nullptr;
-    int32_t *o = nullptr;
-    if (!scratch.get(&idx, (size_t)n_idx) || !scratch.get(&o, (size_t)n_idx)) return kErrOutOfDeviceMemory;
-    hipError_t err = hipMemcpyAsync(idx, idx_host, (size_t)n_idx * sizeof(int64_t), hipMemcpyHostToDevice, st);
-    if (err == hipSuccess) {
-        rg_gather_col<<<dim3(rg_grid(n_idx, kBlock)), dim3(kBlock), 0, st>>>(col_dev, idx, n_idx, o);
-        err = hipGetLastError();
-    }
-    if (err == hipSuccess) err = hipMemcpyAsync(out_host, o, (size_t)n_idx * sizeof(int32_t), hipMemcpyDeviceToHost, st);
-    hipError_t err2 = hipStreamSynchronize(st);
-    return (int)(err != hipSuccess ? err : err2);
 }
 
 int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream)
