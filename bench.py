@@ -312,10 +312,16 @@ def choose_placement(G, torch, plan, bufs, F, tries):
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     slots = min(tries + 2, int((free - (2 << 30)) // (numel * 4)))
-    if slots < 2:
+    arena = None
+    while slots >= 2 and arena is None:
+        try:
+            arena = torch.zeros((slots * numel,), dtype=torch.float32, device=X.device)
+        except RuntimeError:                             # out of memory after all: a smaller arena
+            torch.cuda.empty_cache()
+            slots -= 1
+    if arena is None:
         Y = torch.empty_like(X)
         return X, Y, {"first_allocations_ms": first, "arena_slots": 0, "note": "no room for an arena"}
-    arena = torch.zeros((slots * numel,), dtype=torch.float32, device=X.device)
 
     def at(q):                                           # the buffer that starts q quarter-sizes into the arena
         o = (q * numel // 4) // 1024 * 1024              # 4 KB granularity keeps the 16-byte alignment the kernels need
