@@ -337,3 +337,27 @@ def test_build_module_is_importable_without_loading_the_library():
             "assert 'paper_2511_18297_amd.binding' not in sys.modules; print('ok')")
     out = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True)
     assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr
+
+
+def test_traffic_stamp_of_the_bench_ignores_comments_only(tmp_path, monkeypatch):
+    """bench.py ties its measured-traffic figure to a hash of the kernel code: rewording a comment must keep it,
+    changing a statement must not."""
+    import importlib.util
+    import shutil
+
+    spec = importlib.util.spec_from_file_location("bench_for_test", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    stamp = bench.kernel_sources_sha16()
+    csrc = tmp_path / "paper_2511_18297_amd" / "csrc"
+    csrc.mkdir(parents=True)
+    for name in bench.KERNEL_SOURCES:
+        shutil.copy(os.path.join(ROOT, "paper_2511_18297_amd", "csrc", name), csrc / name)
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    assert bench.kernel_sources_sha16() == stamp
+    path = csrc / "groot_ld_pipe.hip"
+    text = path.read_text()
+    path.write_text("// another comment\n" + text.replace("// ----", "//   ----", 1) + "\n   /* and a block\n comment */\n")
+    assert bench.kernel_sources_sha16() == stamp
+    path.write_text(text.replace("constexpr int kPipeWaves = 4;", "constexpr int kPipeWaves = 8;", 1))
+    assert bench.kernel_sources_sha16() != stamp
