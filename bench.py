@@ -284,36 +284,21 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
 
 def choose_placement(G, torch, plan, bufs, F, tries):
     """Where the feature matrices lie in device memory changes the step time by up to 10 % on this machine, the same
-    kernels on the same data.  The memory behaves as two classes of address ranges that alternate every 64 GiB or
-    so: a step is slowest when X and Y lie in ranges of one class (LD kernel 13.8-14.1 ms on the headline graph),
-    faster when X lies in one class and Y in the other (12.9-13.2 ms), and fastest when each of them straddles a
-    boundary, so that both classes serve half of the traffic at any time (12.5 ms: the XCDs sweep contiguous
-    eighths of the rows).  Which class an address belongs to is not visible to a program, but it shows in the
-    time.  So before anything is timed one arena of `tries` + 2 buffer sizes is allocated, X and Y are tried at
-    quarter-buffer offsets in it (a coordinate search: X, then Y, then both once more; three steps per try), and
-    the fastest pair that does not overlap is kept for the timed run; the features are copied there.  Every try is
-    in the output line.  A caller that reuses its feature buffers over many layers and epochs can do the same
-    once.  -> X, Y, log"""
-    def quick(Xc, Yc):
-        G.groot_spmm_execute(plan, Xc, Yc, F)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(3):
-            G.groot_spmm_execute(plan, Xc, Yc, F)
-        b.record()
-        b.synchronize()
-        return a.elapsed_time(b) / 3
-
+    kernels on the same data: slowest when X and Y lie in address ranges of the same one of two classes that
+    alternate every 64 GiB or so (the first two allocations of a process), fastest when each of them straddles a
+    boundary between the classes (measurement section).  The library has a call that finds a good place
+    by measuring, `groot_feature_placement`; a caller that reuses its feature buffers over many layers and epochs
+    makes it once.  Here: Y is released, one arena of `tries` + 2 matrix sizes is allocated, the call picks the
+    offsets of X and Y in it, and the features are copied to the X it picked.  -> X, Y, log"""
     X, Y = bufs
     bufs.clear()                                         # the caller's references are gone: what is deleted here is freed
     n, numel = X.shape[0], X.numel()
-    first = round(quick(X, Y), 3)
     del Y                                                # the arena takes its place
     torch.cuda.empty_cache()
     free, _ = torch.cuda.mem_get_info()
     slots = min(tries + 2, int((free - (2 << 30)) // (numel * 4)))
     arena = None
-    while slots >= 2 and arena is None:
+    while slots >= 3 and arena is None:
         try:
             arena = torch.zeros((slots * numel,), dtype=torch.float32, device=X.device)
         except RuntimeError:                             # out of memory after all: a smaller arena
@@ -321,44 +306,18 @@ def choose_placement(G, torch, plan, bufs, F, tries):
             slots -= 1
     if arena is None:
         Y = torch.empty_like(X)
-        return X, Y, {"first_allocations_ms": first, "arena_slots": 0, "note": "no room for an arena"}
-
-    def at(q):                                           # the buffer that starts q quarter-sizes into the arena
-        o = (q * numel // 4) // 1024 * 1024              # 4 KB granularity keeps the 16-byte alignment the kernels need
-        return arena[o:o + numel].view(n, F)
-
-    # coordinate search over quarter-size offsets: X with Y parked at the far end, then Y, then X and Y once more
-    last = 4 * (slots - 1)
-    tried = []
-
-    def scan(which, other):
-        best = None
-        for q in range(last + 1):
-            if abs(q - other) < 4:                       # the two buffers must not overlap
-                continue
-            t = quick(at(q), at(other)) if which == "x" else quick(at(other), at(q))
-            tried.append([q, other, round(t, 3)] if which == "x" else [other, q, round(t, 3)])
-            if best is None or t < best[0]:
-                best = (t, q)
-        return best
-
-    _, qx = scan("x", last)
-    if abs(qx - last) < 4:
-        qx = 0
-    t, qy = scan("y", qx)
-    for _ in range(2):
-        t2, qx2 = scan("x", qy)
-        if t2 < t:
-            t, qx = t2, qx2
-        t2, qy2 = scan("y", qx)
-        if t2 < t:
-            t, qy = t2, qy2
-    Xk, Yk = at(qx), at(qy)
+        return X, Y, {"arena_matrices": 0, "note": "no room for an arena: X and Y as first allocated"}
+    t0 = time.perf_counter()
+    place = G.groot_feature_placement(plan, arena, F)
+    seconds = time.perf_counter() - t0
+    ox, oy = place["x_offset"] // 4, place["y_offset"] // 4
+    Xk, Yk = arena[ox:ox + numel].view(n, F), arena[oy:oy + numel].view(n, F)
     Xk.copy_(X)
     del X
     torch.cuda.empty_cache()
-    return Xk, Yk, {"first_allocations_ms": first, "arena_slots": slots, "unit": "quarter of a buffer size",
-                    "tried_x_y_ms": tried, "kept_x_y": [qx, qy], "kept_ms": round(t, 3)}
+    return Xk, Yk, {"arena_matrices": slots, "x_offset_bytes": place["x_offset"], "y_offset_bytes": place["y_offset"],
+                    "back_to_back_ms": round(place["first_ms"], 3), "kept_ms": round(place["best_ms"], 3),
+                    "search_seconds": round(seconds, 2)}
 
 
 def stress_bench(args, G, torch, np, wl, name, props):
@@ -484,8 +443,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
     ap.add_argument("--placement-tries", type=int, default=3,
-                    help="the placement search uses an arena of this many buffer sizes + 2 (X and Y tried at every pair of "
-                         "quarter-buffer offsets in turn, the fastest pair kept); 0: take the first allocations as they come")
+                    help="groot_feature_placement looks for a good place for X and Y in an arena of this many matrix sizes + 2; "
+                         "0: take the first allocations as they come")
     ap.add_argument("--thresholds", type=int, nargs="*", default=None, help="stress workload: degree thresholds to sweep")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
     ap.add_argument("--partitioned", type=int, default=0, metavar="P",

@@ -26,6 +26,7 @@
 #ifndef GROOT_H
 #define GROOT_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -378,6 +379,30 @@ groot_status groot_rows_gather(const int64_t *ids_dev, int64_t n, const float *X
                                float *out_dev, int32_t F, void *hip_stream);
 groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *in_dev,
                                 float *Y_dev, int32_t F, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * groot_feature_placement -- where in an arena of device memory X and Y should
+ * lie.  Not in the paper: a property of this machine.  The same kernels on the
+ * same data take up to 10 % longer when the two feature matrices lie in
+ * address ranges of the same one of two classes that alternate every 64 GiB or
+ * so than when each of them straddles a boundary between the classes (the first
+ * two allocations of a process are the slow case).  The class of an address is
+ * not visible to a program, but it shows in the time, so this call measures:
+ * it runs groot_spmm_execute (three times per try, timed with events on
+ * hip_stream, which it synchronises) with X and Y at offsets in the arena that
+ * are multiples of a quarter matrix (in whole 4 KB units), X first against Y at
+ * the far end, then Y, then each twice more against the other, and returns the
+ * byte offsets of the fastest pair that does not overlap, its time per step,
+ * and the time with the two matrices back to back at the start of the arena.
+ * arena_dev (device, 16-byte aligned, owned by the caller, contents are
+ * overwritten): at least 2.25 matrices of max(rows, feature rows) x F fp32;
+ * five matrices give the search room.  A caller that reuses its feature
+ * buffers over many layers and epochs does this once.  Errors: EINVAL (NULL,
+ * plan not uploaded, F, alignment, arena too small), EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_feature_placement(const groot_plan *plan, void *arena_dev, size_t arena_bytes,
+                                     int32_t F, void *hip_stream, size_t *x_offset,
+                                     size_t *y_offset, float *best_ms, float *first_ms);
 
 /* What the library decided for an uploaded plan, for diagnostics and benchmarks:
  * "ld_pipelined" (0 the plain LD kernel always, 2 the pipelined one for F = 32,

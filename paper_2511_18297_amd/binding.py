@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_feature_placement", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
     "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
@@ -68,6 +68,9 @@ _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_lists_device_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
 _lib.groot_plan_hd_pieces.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp]
+_lib.groot_feature_placement.argtypes = [_vp, _vp, ctypes.c_size_t, _i32, _vp, ctypes.POINTER(ctypes.c_size_t),
+                                         ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_float),
+                                         ctypes.POINTER(ctypes.c_float)]
 _lib.groot_plan_free.argtypes = [_vp]
 _lib.groot_plan_free.restype = None
 _lib.groot_partition_regrow.argtypes = [_vp, _i32, _vp, _u32, _pp]
@@ -383,6 +386,20 @@ def groot_plan_hd_pieces(pl: Plan) -> dict:
            "slot": np.empty(n, np.int32)}
     _check(_lib.groot_plan_hd_pieces(pl.handle, n, *(out[k].ctypes.data for k in ("begin", "len", "row", "slot"))))
     return out
+
+
+def groot_feature_placement(pl: Plan, arena, F: int, stream=None) -> dict:
+    """arena: a contiguous float32 CUDA tensor (its contents are overwritten) -> byte offsets of X and Y in it"""
+    import torch
+
+    ptr = _dev_ptr(arena, "arena")
+    if arena.dtype != torch.float32:
+        raise TypeError("arena must be float32")
+    x, y = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    best, first = ctypes.c_float(0), ctypes.c_float(0)
+    _check(_lib.groot_feature_placement(pl.handle, ptr, arena.numel() * 4, F, _stream_handle(stream), ctypes.byref(x),
+                                        ctypes.byref(y), ctypes.byref(best), ctypes.byref(first)))
+    return {"x_offset": x.value, "y_offset": y.value, "best_ms": best.value, "first_ms": first.value}
 
 
 def groot_partition_regrow(g: Graph, num_parts: int, part_of=None, flags: int = GROOT_REGROW) -> Parts:

@@ -3,6 +3,7 @@
 // here; device work goes through the launchers in groot_kernels.hip.
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <limits>
@@ -697,6 +698,85 @@ extern "C" groot_status groot_spmm_execute(const groot_plan *plan, const float *
                                            int32_t F, void *hip_stream)
 {
     return groot_spmm_execute_phases(plan, X_dev, Y_dev, F, GROOT_PHASE_ALL, hip_stream);
+}
+
+namespace {
+struct PlacementTry {
+    const groot_plan *plan;
+    const float *X;
+    float *Y;
+    int32_t F;
+    void *stream;
+    groot_status status;
+};
+int placement_step(void *ctx)
+{
+    PlacementTry *t = (PlacementTry *)ctx;
+    t->status = groot_spmm_execute(t->plan, t->X, t->Y, t->F, t->stream);
+    return t->status == GROOT_OK ? 0 : -1;
+}
+}  // namespace
+
+extern "C" groot_status groot_feature_placement(const groot_plan *plan, void *arena_dev, size_t arena_bytes, int32_t F,
+                                                void *hip_stream, size_t *x_offset, size_t *y_offset, float *best_ms,
+                                                float *first_ms)
+{
+    const char *who = "groot_feature_placement: ";
+    if (!plan || !arena_dev || !x_offset || !y_offset) return fail(GROOT_EINVAL, std::string(who) + "NULL argument");
+    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "plan is not on the device (call groot_plan_upload)");
+    if (F < 4 || F > 512 || F % 4) return fail(GROOT_EINVAL, std::string(who) + "F must be a multiple of 4 in [4,512]");
+    if (((uintptr_t)arena_dev & 15) != 0) return fail(GROOT_EINVAL, std::string(who) + "the arena must be 16-byte aligned");
+    const size_t rows = (size_t)std::max(plan->dev.n, plan->dev.n_cols);
+    const size_t size = rows * (size_t)F * 4;                 // one matrix
+    const size_t step = std::max<size_t>(4096, size / 4 / 4096 * 4096);   // a quarter of it, in whole 4 KB units
+    const int64_t apart = (int64_t)((size + step - 1) / step);      // steps between two matrices that do not overlap
+    if (arena_bytes < size + (size_t)apart * step)
+        return fail(GROOT_EINVAL, std::string(who) + "the arena must hold two matrices (the second starts at a multiple of a quarter matrix, in whole 4 KB units)");
+    const int64_t last = (int64_t)((arena_bytes - size) / step);   // offsets 0 .. last steps
+    char *base = (char *)arena_dev;
+    PlacementTry t{plan, nullptr, nullptr, F, hip_stream, GROOT_OK};
+    auto time_pair = [&](int64_t qx, int64_t qy, float *ms) -> groot_status {
+        t.X = (const float *)(base + (size_t)qx * step);
+        t.Y = (float *)(base + (size_t)qy * step);
+        const int err = device_time_ms(hip_stream, 3, placement_step, &t, ms);
+        if (err < 0) return t.status;                          // groot_spmm_execute has set the error text
+        if (err) return fail(GROOT_EHIP, std::string(who) + hip_error_text(err));
+        return GROOT_OK;
+    };
+    groot_status st;
+    float first = 0.f;
+    if ((st = time_pair(0, apart, &first)) != GROOT_OK) return st;   // the two matrices back to back, as first allocated
+    float best = first;
+    int64_t bx = 0, by = apart;
+    // X against Y parked at the far end, then Y against that X, then each once more against the other
+    auto scan = [&](bool moving_x, int64_t other, float *t_best, int64_t *q_best) -> groot_status {
+        for (int64_t q = 0; q <= last; ++q) {
+            if (std::llabs(q - other) < apart) continue;
+            float ms = 0.f;
+            groot_status s2 = moving_x ? time_pair(q, other, &ms) : time_pair(other, q, &ms);
+            if (s2 != GROOT_OK) return s2;
+            if (ms < *t_best) { *t_best = ms; *q_best = q; }
+        }
+        return GROOT_OK;
+    };
+    if (last >= apart) {
+        float tx = std::numeric_limits<float>::max();
+        int64_t qx = 0, qy = last;
+        if ((st = scan(true, last, &tx, &qx)) != GROOT_OK) return st;
+        for (int round = 0; round < 3; ++round) {
+            float ty = std::numeric_limits<float>::max(), tx2 = std::numeric_limits<float>::max();
+            if ((st = scan(false, qx, &ty, &qy)) != GROOT_OK) return st;
+            if (ty < best) { best = ty; bx = qx; by = qy; }
+            if (round == 2) break;
+            if ((st = scan(true, qy, &tx2, &qx)) != GROOT_OK) return st;
+            if (tx2 < best) { best = tx2; bx = qx; by = qy; }
+        }
+    }
+    *x_offset = (size_t)bx * step;
+    *y_offset = (size_t)by * step;
+    if (best_ms) *best_ms = best;
+    if (first_ms) *first_ms = first;
+    return GROOT_OK;
 }
 
 extern "C" groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_dev, const float *Wn_dev,

@@ -166,6 +166,7 @@ int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int3
                          int regrow, void *stream, DevicePart *out);
 void free_device_part(DevicePart &part);
 // Small synchronous device reads and copies (sizes and lists of a plan built from device arrays).
+int device_time_ms(void *stream, int reps, int (*fn)(void *ctx), void *ctx, float *ms);
 int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream);
 int device_copy(void *dst_dev, const void *src_dev, size_t bytes, void *stream);   // device to device, synchronous
 const char *hip_error_text(int err);

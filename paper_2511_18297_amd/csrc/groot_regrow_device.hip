@@ -592,6 +592,29 @@ int launch_regrow_device(const DevicePlan &dp, int64_t n1, int32_t P, const int3
     return 0;
 }
 
+// Milliseconds per call of fn(ctx), which enqueues work on the stream: one untimed call, then `reps` calls between two
+// events.  Synchronises the stream.  0, or the first HIP error (fn returns 0 or an error of its own).
+int device_time_ms(void *stream, int reps, int (*fn)(void *ctx), void *ctx, float *ms)
+{
+    hipStream_t st = (hipStream_t)stream;
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    int err = (int)e;
+    if (!err) err = fn(ctx);
+    if (!err) err = (int)hipEventRecord(a, st);
+    for (int r = 0; r < reps && !err; ++r) err = fn(ctx);
+    if (!err) err = (int)hipEventRecord(b, st);
+    if (!err) err = (int)hipEventSynchronize(b);
+    float t = 0.f;
+    if (!err) err = (int)hipEventElapsedTime(&t, a, b);
+    if (a) (void)hipEventDestroy(a);
+    if (b) (void)hipEventDestroy(b);
+    if (err) (void)hipStreamSynchronize(st);
+    *ms = reps > 0 ? t / (float)reps : 0.f;
+    return err;
+}
+
 int device_download(void *dst_host, const void *src_dev, size_t bytes, void *stream)
 {
     if (!bytes) return 0;

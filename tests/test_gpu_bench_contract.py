@@ -39,7 +39,7 @@ def test_bench_line_on_a_small_workload(workload, tries):
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["sample"]
     assert d["parity_max_err_over_tol"] <= 1.0           # the timed output, element by element against the oracle
     if tries:
-        assert d["placement"]["arena_slots"] >= 2 and d["placement"]["kept_ms"] > 0
+        assert d["placement"]["arena_matrices"] >= 3 and d["placement"]["kept_ms"] > 0
     else:
         assert d["placement"] is None
 

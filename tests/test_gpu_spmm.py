@@ -654,3 +654,36 @@ def test_partitioned_mode_scatters_back_to_full_result(torch_cuda, n, batch, P, 
     if regrow:
         Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
     assert_close_to_oracle(Y.cpu().numpy(), Y64, S, "partitioned")
+
+
+@pytest.mark.parametrize("matrices,F", [(5.0, 64), (2.25, 32), (3.5, 20)])
+def test_feature_placement_returns_a_usable_pair(torch_cuda, matrices, F):
+    """groot_feature_placement measures; whatever pair of offsets it returns must be inside the arena, aligned, not
+    overlapping, and the aggregation computed there must match the oracle (the arena's contents are not kept)."""
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(48, 2)
+    n = 2 * aig.num_nodes
+    plan = G.groot_spmm_plan(g, 32)
+    G.groot_plan_upload(plan, 64)
+    size = n * F * 4
+    quarter = max(4096, size // 4 // 4096 * 4096)
+    arena_floats = int(matrices * n * F) + 4 * quarter // 4
+    arena = torch.full((arena_floats,), float("nan"), dtype=torch.float32, device="cuda")
+    place = G.groot_feature_placement(plan, arena, F)
+    ox, oy = place["x_offset"], place["y_offset"]
+    assert ox % quarter == 0 and oy % quarter == 0 and abs(ox - oy) >= size
+    assert max(ox, oy) + size <= arena.numel() * 4
+    assert place["best_ms"] > 0 and place["first_ms"] >= place["best_ms"]
+    X_np = wl.uniform_features_numpy(33, 0, n, F)
+    X = arena[ox // 4:ox // 4 + n * F].view(n, F)
+    Y = arena[oy // 4:oy // 4 + n * F].view(n, F)
+    X.copy_(torch.from_numpy(X_np))
+    G.groot_spmm_execute(plan, X, Y, F)
+    torch.cuda.synchronize()
+    Y64, S = oracle.spmm_f64(rowptr, col, val, X_np)
+    assert_close_to_oracle(Y.cpu().numpy(), Y64, S, f"placed at {ox}, {oy}")
+    # errors: an arena that does not hold two matrices, a plan that is not uploaded
+    with pytest.raises(G.GrootError):
+        G.groot_feature_placement(plan, arena[: n * F + n * F // 2], F)
+    with pytest.raises(G.GrootError):
+        G.groot_feature_placement(G.groot_spmm_plan(g, 32), arena, F)
