@@ -113,7 +113,8 @@ struct RowOut {
 
 // Kernel launchers (groot_kernels.hip).  Return hipError_t as int (0 = success).
 int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
-int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream);   // F = 32, 64, 128
+int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream,
+                        const RowOut *out = nullptr);   // F = 32, 64, 128
 int launch_hd(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
 int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, const RowOut *out = nullptr);
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,

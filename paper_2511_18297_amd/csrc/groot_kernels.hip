@@ -237,8 +237,8 @@ int launch_ld(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *s
     const int64_t *out_ids = out ? out->ids : nullptr;
     const int64_t n_out = out ? out->n_out : dp.n;
     // the pipelined kernel serves whole graphs at F = 32, 64 and 128 (ld_pipelined: 2 all three widths, 1 only the two wider)
-    if (!out && dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
-        return launch_ld_pipelined(dp, X, Y, F, stream);
+    if (dp.zero_row && ((dp.ld_pipelined == 2 && F4 == 8) || (dp.ld_pipelined && (F4 == 16 || F4 == 32))))
+        return launch_ld_pipelined(dp, X, Y, F, stream, out);
     const int64_t n_tiles = (n_out + kRowsPerLdTile - 1) / kRowsPerLdTile;
     if (n_tiles == 0) return 0;
     const int64_t per_xcd = (n_tiles + kXcds - 1) / kXcds;

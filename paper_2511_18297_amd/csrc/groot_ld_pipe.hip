@@ -55,12 +55,16 @@ struct CompactCsr {
     int32_t n_hot;
 };
 
-template <int L, int W, int G, int D, bool C>
+// M: the sum of row r goes to row out_ids[r] of Y (the owned rows of a part written into place in the matrix of
+// the whole graph); n is then the number of leading rows that are wanted.  Only without the compact matrix.
+template <int L, int W, int G, int D, bool C, bool M = false>
 __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 2))) void ld_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const CompactCsr cz, const char *__restrict__ X, char *__restrict__ Y, int64_t zero_off, char *trash, int64_t n,
-    int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts)
+    int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts,
+    const int64_t *__restrict__ out_ids)
 {
+    static_assert(!(C && M), "the row-mapped form reads the plain arrays");
     constexpr int kRpg = kWave / L;                      // rows per lane group sweep
     constexpr int kTileRows = G * kRpg;
     constexpr int kPipeD = D;                            // slots per row
@@ -74,6 +78,7 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
     __shared__ __align__(16) Slot s_slot[kPipeWaves][kSlots];
     __shared__ float s_inv[kPipeWaves][kTileRows];       // row weight (1 unless W == kMean), or -1: the row is masked
+    __shared__ int64_t s_oid[M ? kPipeWaves : 1][M ? kTileRows : 1];   // M: byte offset of the row's place in Y
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int g = l / L, f = l % L;
@@ -102,6 +107,12 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     int32_t len_a = 0;                                   // lanes 0..kTileRows-1: stored length of the tile's row
     uint32_t live_a = 0;                                 // bit h: slot l + 64 h holds an entry
     int32_t base_a = 0;                                  // C: first row of the tile that cc belongs to
+    int64_t oid_a = 0, oid_b = 0;                        // M: out_ids of the rows that rp_a / rp_b belong to
+    auto load_oid = [&](int64_t tile) -> int64_t {
+        if constexpr (!M) return 0;
+        const int64_t ri = tile * kTileRows + (l < kTileRows ? l : 0);
+        return out_ids[ri < n ? ri : 0];                 // rows past the end: any valid entry, never used
+    };
     auto load_rp = [&](int64_t tile) -> int64_t {
         const int64_t ri = tile * kTileRows + (l < kTileRows ? l : kTileRows);
         // lanes 0..kTileRows hold the pointers; rows past the end read rowptr[n]
@@ -166,6 +177,9 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             row_ok = row_ok && (bits & ((1u << kPipeD) - 1)) == 0;
         }
         if (l < kTileRows) s_inv[w][l] = row_ok ? row_weight<W == kMean ? kMean : kOnes>(len_a) : -1.0f;
+        if constexpr (M) {
+            if (l < kTileRows) s_oid[w][l] = oid_a << kRowShift;
+        }
         pipe_wave_sync();
         return ok_a;
     };
@@ -175,11 +189,13 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
         v4f xs[kPipeD];
         float ws[W == kExplicit ? kPipeD : 1];
         float inv;
+        int64_t oid;                                     // M: where the row's sum goes
     };
     Regs rr[G];
     auto issue = [&](Regs &q, int grp) {
         const int lr = grp * kRpg + g;
         q.inv = s_inv[w][lr];
+        if constexpr (M) q.oid = s_oid[w][lr];
 #pragma unroll
         for (int k = 0; k < kPipeD; ++k) {
             if constexpr (W == kExplicit) {
@@ -205,11 +221,14 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     char *const tbase = trash + 16 * f;
     // ---- prologue: the first tile is staged and put in flight, the CSR of the next two is on its way
     rp_a = load_rp(t_first);
+    oid_a = load_oid(t_first);
     load_cols(t_first);
     bool ok_cur = stage();
     rp_a = load_rp(t_first + stride);
+    oid_a = load_oid(t_first + stride);
     load_cols(t_first + stride);
     rp_b = load_rp(t_first + 2 * stride);
+    oid_b = load_oid(t_first + 2 * stride);
 #pragma unroll
     for (int grp = 0; grp < G; ++grp) issue(rr[grp], grp);
     // Everything above has arrived before the loop starts: the loop's own order of loads is then the
@@ -219,8 +238,10 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
     for (int64_t tile = t_first; tile < x_end; tile += stride) {
         const bool ok_next = stage();                    // CSR of the next tile -> slot table (this tile's groups are all issued)
         rp_a = rp_b;
+        oid_a = oid_b;
         load_cols(tile + 2 * stride);
         rp_b = load_rp(tile + 3 * stride);
+        oid_b = load_oid(tile + 3 * stride);
         const int64_t base = tile * kTileRows;
         char *const ybase = Y + (base << kRowShift) + 16 * f;
 #pragma unroll
@@ -228,7 +249,8 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
             const v4f a = sum(rr[grp]);
             const int roff = (grp * kRpg + g) << kRowShift;
             // a masked row (every row of a tile that is not ok) goes to the trash area: a select, no branch
-            char *const dst = rr[grp].inv >= 0.f ? ybase + roff : tbase + roff;
+            char *const yrow = M ? Y + rr[grp].oid + 16 * f : ybase + roff;
+            char *const dst = rr[grp].inv >= 0.f ? yrow : tbase + roff;
             __builtin_nontemporal_store(a, (v4f *)dst);
             issue(rr[grp], grp);                         // the same rows of the next tile
         }
@@ -241,7 +263,7 @@ __global__ __launch_bounds__(kPipeWaves * kWave) __attribute__((amdgpu_waves_per
                     const int64_t s = rowptr[row], e = rowptr[row + 1];
                     if (e - s < T && e - s <= kPipeD)
                         __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, (const v4f *)X, L, f),
-                                                    (v4f *)(Y + (row << kRowShift) + 16 * f));
+                                                    (v4f *)(Y + ((M ? out_ids[row] : row) << kRowShift) + 16 * f));
                 }
             }
         }
@@ -254,15 +276,18 @@ template <int L, int W>
 __global__ __launch_bounds__(kBlock) void ld_rows_kernel(const int32_t *__restrict__ rows, int64_t n_rows,
                                                          const int64_t *__restrict__ rowptr,
                                                          const int32_t *__restrict__ col, const float *__restrict__ val,
-                                                         const v4f *__restrict__ X, v4f *__restrict__ Y, int32_t F4)
+                                                         const v4f *__restrict__ X, v4f *__restrict__ Y, int32_t F4,
+                                                         const int64_t *__restrict__ out_ids, int64_t n_out)
 {
     constexpr int G = kBlock / L;
     const int64_t k = (int64_t)blockIdx.x * G + threadIdx.x / L;
     if (k >= n_rows) return;
     const int64_t row = rows[k];
+    if (row >= n_out) return;                            // a row that is not wanted (row-mapped calls: boundary rows)
     const int64_t s = rowptr[row], e = rowptr[row + 1];
+    const int64_t orow = out_ids ? out_ids[row] : row;
     for (int32_t ff = threadIdx.x % L; ff < F4; ff += L)
-        __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, X, F4, ff), &Y[row * F4 + ff]);
+        __builtin_nontemporal_store(ld_row_sum<W, false>(s, e, col, val, X, F4, ff), &Y[orow * F4 + ff]);
 }
 
 struct PipeArgs {
@@ -281,20 +306,25 @@ struct PipeArgs {
     int32_t parts;
     int64_t n_wg;
     hipStream_t st;
+    const int64_t *out_ids;                  // row-mapped form, else NULL
 };
 
 template <int L, int W, int G, int D>
 static void pipe_launch(const PipeArgs &a)
 {
-    if (a.compact) {
+    if (a.out_ids) {
+        ld_pipe_kernel<L, W, G, D, false, true><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
+            a.rowptr, a.col, a.val, a.cz, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part,
+            a.waves_per_part, a.parts, a.out_ids);
+    } else if (a.compact) {
         const size_t lds = (size_t)(a.cz.n_hot ? a.cz.n_hot : 1) * sizeof(int32_t);
         ld_pipe_kernel<L, W, G, D, true><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), lds, a.st>>>(
             a.rowptr, a.col, a.val, a.cz, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part,
-            a.waves_per_part, a.parts);
+            a.waves_per_part, a.parts, nullptr);
     } else {
         ld_pipe_kernel<L, W, G, D, false><<<dim3((unsigned)a.n_wg), dim3(kPipeWaves * kWave), 0, a.st>>>(
             a.rowptr, a.col, a.val, a.cz, a.X, a.Y, a.zero_off, a.trash, a.n, a.T, a.n_tiles, a.tiles_per_part,
-            a.waves_per_part, a.parts);
+            a.waves_per_part, a.parts, nullptr);
     }
 }
 
@@ -355,8 +385,13 @@ int pipe_compact_prepare()
     return err;
 }
 
-int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream)
+// out: the leading out->n_out rows only, row r written to row out->ids[r] of Y (ids NULL: to row r)
+int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t F, void *stream, const RowOut *out)
 {
+    const int64_t n_rows = out ? out->n_out : dp.n;
+    const int64_t *out_ids = out ? out->ids : nullptr;
+    if (n_rows < 0 || n_rows > dp.n) return (int)hipErrorInvalidValue;
+    if (n_rows == 0) return 0;
     const int32_t F4 = F / 4;
     if (F4 != 8 && F4 != 16 && F4 != 32) return (int)hipErrorInvalidValue;
     if (!weights_ok(dp) || !dp.zero_row) return (int)hipErrorInvalidValue;
@@ -368,7 +403,7 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return (int)e;
     const int tile_rows = pipe_groups(F4) * (kWave / F4);
-    const int64_t n_tiles = (dp.n + tile_rows - 1) / tile_rows;
+    const int64_t n_tiles = (n_rows + tile_rows - 1) / tile_rows;
     // one workgroup per CU; consecutive workgroup ids land on different XCDs
     int64_t n_wg = cus / kXcds * kXcds;
     if (n_wg < kXcds) n_wg = kXcds;
@@ -384,23 +419,26 @@ int launch_ld_pipelined(const DevicePlan &dp, const float *X, float *Y, int32_t 
     static_assert(pipe_groups(8) <= 8 && pipe_groups(16) <= 8 && pipe_groups(32) <= 8 && 8 * kWave * 16 <= kTrashFloats * 4,
                   "a tile's masked sums fit the trash area");
     hipStream_t st = (hipStream_t)stream;
-    const bool compact = dp.compressed && dp.rp32 && dp.col16 && dp.hot_cols;
+    // the compact matrix codes rows that the row list serves as uncoded, which only holds for whole-graph calls
+    const bool compact = !out && dp.compressed && dp.rp32 && dp.col16 && dp.hot_cols;
     const PipeArgs a{dp.rowptr, col_arg, val_arg, CompactCsr{dp.rp32, dp.col16, dp.hot_cols, dp.n_hot}, compact,
-                     (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, dp.n,
-                     dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st};
+                     (const char *)X, (char *)Y, byte_distance(X, dp.zero_row), trash, n_rows,
+                     dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, n_wg, st, out_ids};
     GROOT_DISPATCH_W(dp.weight_mode, (pipe_dispatch_d<kW>(dp.pipe_depth, F4, a)));
     hipError_t err = hipGetLastError();
-    if (err != hipSuccess || dp.n_mid_rows == 0) return (int)err;
-    // the low-degree rows with more entries than the pipeline has slots
-    const int64_t grid = (dp.n_mid_rows + kBlock / F4 - 1) / (kBlock / F4);
+    // the low-degree rows with more entries than the pipeline has slots; the rows that the compact matrix cannot
+    // code stand at the end of the list and are the pipeline's own whenever it reads the plain arrays
+    const int64_t n_mid = compact ? dp.n_mid_rows : dp.n_mid_rows - dp.n_bad_rows;
+    if (err != hipSuccess || n_mid <= 0) return (int)err;
+    const int64_t grid = (n_mid + kBlock / F4 - 1) / (kBlock / F4);
     if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
     GROOT_DISPATCH_W(dp.weight_mode,
                      (F4 == 8 ? ld_rows_kernel<8, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                                    dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)
+                                    dp.mid_rows, n_mid, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4, out_ids, n_rows)
                       : F4 == 16 ? ld_rows_kernel<16, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                                       dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)
+                                       dp.mid_rows, n_mid, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4, out_ids, n_rows)
                                  : ld_rows_kernel<32, kW><<<dim3((unsigned)grid), dim3(kBlock), 0, st>>>(
-                                       dp.mid_rows, dp.n_mid_rows, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4)));
+                                       dp.mid_rows, n_mid, dp.rowptr, col_arg, val_arg, (const v4f *)X, (v4f *)Y, F4, out_ids, n_rows)));
     return (int)hipGetLastError();
 }
 
