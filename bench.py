@@ -282,7 +282,7 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
         "max_abs_diff_vs_unfused": worst, "placement": placement, "device": props.name}))
 
 
-def choose_placement(G, torch, plan, bufs, F, tries):
+def choose_placement(G, torch, plan, bufs, F, tries, fixed=None):
     """Where the feature matrices lie in device memory changes the step time by up to 10 % on this machine, the same
     kernels on the same data: slowest when X and Y lie in address ranges of the same one of two classes that
     alternate every 64 GiB or so (the first two allocations of a process), fastest when each of them straddles a
@@ -308,7 +308,12 @@ def choose_placement(G, torch, plan, bufs, F, tries):
         Y = torch.empty_like(X)
         return X, Y, {"arena_matrices": 0, "note": "no room for an arena: X and Y as first allocated"}
     t0 = time.perf_counter()
-    place = G.groot_feature_placement(plan, arena, F)
+    if fixed:                                            # offsets of an earlier search (they repeat from box to box)
+        assert max(fixed) + numel * 4 <= arena.numel() * 4 and abs(fixed[0] - fixed[1]) >= numel * 4 \
+            and fixed[0] % 16 == 0 and fixed[1] % 16 == 0, "offsets outside the arena, overlapping or unaligned"
+        place = {"x_offset": fixed[0], "y_offset": fixed[1], "best_ms": float("nan"), "first_ms": float("nan")}
+    else:
+        place = G.groot_feature_placement(plan, arena, F)
     seconds = time.perf_counter() - t0
     ox, oy = place["x_offset"] // 4, place["y_offset"] // 4
     Xk, Yk = arena[ox:ox + numel].view(n, F), arena[oy:oy + numel].view(n, F)
@@ -316,8 +321,9 @@ def choose_placement(G, torch, plan, bufs, F, tries):
     del X
     torch.cuda.empty_cache()
     return Xk, Yk, {"arena_matrices": slots, "x_offset_bytes": place["x_offset"], "y_offset_bytes": place["y_offset"],
-                    "back_to_back_ms": round(place["first_ms"], 3), "kept_ms": round(place["best_ms"], 3),
-                    "search_seconds": round(seconds, 2)}
+                    "back_to_back_ms": None if fixed else round(place["first_ms"], 3),
+                    "kept_ms": None if fixed else round(place["best_ms"], 3),
+                    "search_seconds": None if fixed else round(seconds, 2)}
 
 
 def stress_bench(args, G, torch, np, wl, name, props):
@@ -445,6 +451,8 @@ def main():
     ap.add_argument("--placement-tries", type=int, default=3,
                     help="groot_feature_placement looks for a good place for X and Y in an arena of this many matrix sizes + 2; "
                          "0: take the first allocations as they come")
+    ap.add_argument("--placement-offsets", type=int, nargs=2, default=None, metavar=("X", "Y"),
+                    help="byte offsets of X and Y in the arena, as an earlier run reported them: no search (for profiles)")
     ap.add_argument("--thresholds", type=int, nargs="*", default=None, help="stress workload: degree thresholds to sweep")
     ap.add_argument("--transposed", action="store_true", help="time dX = A_hat^T dY (backward pass) instead")
     ap.add_argument("--partitioned", type=int, default=0, metavar="P",
@@ -541,7 +549,7 @@ def main():
     if args.placement_tries > 0:
         bufs = [X, Y]
         del X, Y
-        X, Y, placement = choose_placement(G, torch, plan, bufs, F, args.placement_tries)
+        X, Y, placement = choose_placement(G, torch, plan, bufs, F, args.placement_tries, args.placement_offsets)
 
     # ---- whole path: W warm-up steps, then exactly K timed steps
     run(G.GROOT_PHASE_ALL, args.warmup)
