@@ -282,31 +282,29 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
         "max_abs_diff_vs_unfused": worst, "placement": placement, "device": props.name}))
 
 
-def choose_placement(G, torch, plan, bufs, F, tries, fixed=None):
+def place_features(G, torch, wl, plan, seed, n, F, tries, fixed=None):
     """Where the feature matrices lie in device memory changes the step time by up to 10 % on this machine, the same
     kernels on the same data: slowest when X and Y lie in address ranges of the same one of two classes that
     alternate every 64 GiB or so (the first two allocations of a process), fastest when each of them straddles a
     boundary between the classes (measurement section).  The library has a call that finds a good place
     by measuring, `groot_feature_placement`; a caller that reuses its feature buffers over many layers and epochs
-    makes it once.  Here: Y is released, one arena of `tries` + 2 matrix sizes is allocated, the call picks the
-    offsets of X and Y in it, and the features are copied to the X it picked.  -> X, Y, log"""
-    X, Y = bufs
-    bufs.clear()                                         # the caller's references are gone: what is deleted here is freed
-    n, numel = X.shape[0], X.numel()
-    del Y                                                # the arena takes its place
-    torch.cuda.empty_cache()
-    free, _ = torch.cuda.mem_get_info()
-    slots = min(tries + 2, int((free - (2 << 30)) // (numel * 4)))
-    arena = None
+    makes it once.  Here, before any feature matrix exists: one arena of `tries` + 3 matrix sizes is allocated, the
+    call picks the offsets of X and Y in it, and the features are generated into the X it picked.  With `tries` = 0
+    X and Y are plain allocations, one after the other.  -> X, Y, log"""
+    numel = n * F
+    slots, arena = 0, None
+    if tries > 0:
+        free, _ = torch.cuda.mem_get_info()
+        slots = min(tries + 3, int(0.75 * free // (numel * 4)))      # a quarter of the memory stays free for the rest
     while slots >= 3 and arena is None:
         try:
-            arena = torch.zeros((slots * numel,), dtype=torch.float32, device=X.device)
+            arena = torch.zeros((slots * numel,), dtype=torch.float32, device="cuda")
         except RuntimeError:                             # out of memory after all: a smaller arena
             torch.cuda.empty_cache()
             slots -= 1
     if arena is None:
-        Y = torch.empty_like(X)
-        return X, Y, {"arena_matrices": 0, "note": "no room for an arena: X and Y as first allocated"}
+        X = wl.uniform_features(seed, 0, n, F, device="cuda")
+        return X, torch.empty_like(X), (None if tries <= 0 else {"arena_matrices": 0, "note": "no room for an arena"})
     t0 = time.perf_counter()
     if fixed:                                            # offsets of an earlier search (they repeat from box to box)
         assert max(fixed) + numel * 4 <= arena.numel() * 4 and abs(fixed[0] - fixed[1]) >= numel * 4 \
@@ -316,14 +314,12 @@ def choose_placement(G, torch, plan, bufs, F, tries, fixed=None):
         place = G.groot_feature_placement(plan, arena, F)
     seconds = time.perf_counter() - t0
     ox, oy = place["x_offset"] // 4, place["y_offset"] // 4
-    Xk, Yk = arena[ox:ox + numel].view(n, F), arena[oy:oy + numel].view(n, F)
-    Xk.copy_(X)
-    del X
-    torch.cuda.empty_cache()
-    return Xk, Yk, {"arena_matrices": slots, "x_offset_bytes": place["x_offset"], "y_offset_bytes": place["y_offset"],
-                    "back_to_back_ms": None if fixed else round(place["first_ms"], 3),
-                    "kept_ms": None if fixed else round(place["best_ms"], 3),
-                    "search_seconds": None if fixed else round(seconds, 2)}
+    X, Y = arena[ox:ox + numel].view(n, F), arena[oy:oy + numel].view(n, F)
+    wl.uniform_features(seed, 0, n, F, out=X)
+    return X, Y, {"arena_matrices": slots, "x_offset_bytes": place["x_offset"], "y_offset_bytes": place["y_offset"],
+                  "back_to_back_ms": None if fixed else round(place["first_ms"], 3),
+                  "kept_ms": None if fixed else round(place["best_ms"], 3),
+                  "search_seconds": None if fixed else round(seconds, 2)}
 
 
 def stress_bench(args, G, torch, np, wl, name, props):
@@ -449,7 +445,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-copies", type=int, default=16, help="copies of the batch the CPU oracle runs (and checks)")
     ap.add_argument("--placement-tries", type=int, default=3,
-                    help="groot_feature_placement looks for a good place for X and Y in an arena of this many matrix sizes + 2; "
+                    help="groot_feature_placement looks for a good place for X and Y in an arena of this many matrix sizes + 3; "
                          "0: take the first allocations as they come")
     ap.add_argument("--placement-offsets", type=int, nargs=2, default=None, metavar=("X", "Y"),
                     help="byte offsets of X and Y in the arena, as an earlier run reported them: no search (for profiles)")
@@ -525,8 +521,8 @@ def main():
     nnz_hd = int(np.diff(view["rowptr"])[pv["hd_rows"]].sum()) if n_hd else 0
     G.groot_plan_upload(plan, F)
     t_setup = time.time() - t0
-    X = wl.uniform_features(seed, 0, n, F, device="cuda")
-    Y = torch.empty_like(X)
+    tries = 0 if args.partitioned else min(args.placement_tries, 1) if args.sage_layer else args.placement_tries
+    X, Y, placement = place_features(G, torch, wl, plan, seed, n, F, tries, args.placement_offsets)
     torch.cuda.synchronize()
 
     def run(phases, count):
@@ -536,20 +532,9 @@ def main():
     if args.partitioned:
         partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props)
         return
-    if args.sage_layer:
-        placement = None
-        if args.placement_tries > 0:                     # X and the layer's output where the aggregation runs fastest
-            bufs = [X, Y]
-            del X, Y
-            X, Y, placement = choose_placement(G, torch, plan, bufs, F, min(args.placement_tries, 2))
+    if args.sage_layer:                                  # X and the layer's output where the aggregation runs fastest
         sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props, placement)
         return
-
-    placement = None
-    if args.placement_tries > 0:
-        bufs = [X, Y]
-        del X, Y
-        X, Y, placement = choose_placement(G, torch, plan, bufs, F, args.placement_tries, args.placement_offsets)
 
     # ---- whole path: W warm-up steps, then exactly K timed steps
     run(G.GROOT_PHASE_ALL, args.warmup)

@@ -389,10 +389,10 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
  * two allocations of a process are the slow case).  The class of an address is
  * not visible to a program, but it shows in the time, so this call measures:
  * it runs groot_spmm_execute (three times per try, timed with events on
- * hip_stream, which it synchronises) with X and Y at offsets in the arena that
- * are multiples of a quarter matrix (in whole 4 KB units), X first against Y at
- * the far end, then Y, then each twice more against the other, and returns the
- * byte offsets of the fastest pair that does not overlap, its time per step,
+ * hip_stream, which it synchronises) with X and Y at every pair of offsets in
+ * the arena that are multiples of half a matrix and do not overlap, then at
+ * the quarter-matrix neighbours of the best pair (offsets in whole 4 KB
+ * units), and returns the byte offsets of the fastest pair, its time per step,
  * and the time with the two matrices back to back at the start of the arena.
  * arena_dev (device, 16-byte aligned, owned by the caller, contents are
  * overwritten): at least 2.25 matrices of max(rows, feature rows) x F fp32;

@@ -748,29 +748,27 @@ extern "C" groot_status groot_feature_placement(const groot_plan *plan, void *ar
     if ((st = time_pair(0, apart, &first)) != GROOT_OK) return st;   // the two matrices back to back, as first allocated
     float best = first;
     int64_t bx = 0, by = apart;
-    // X against Y parked at the far end, then Y against that X, then each once more against the other
-    auto scan = [&](bool moving_x, int64_t other, float *t_best, int64_t *q_best) -> groot_status {
-        for (int64_t q = 0; q <= last; ++q) {
-            if (std::llabs(q - other) < apart) continue;
+    // every pair of half-matrix offsets that does not overlap (the fast pairs are those in which both matrices
+    // straddle a boundary between the two classes of address ranges, which a search along one coordinate at a time
+    // does not find), then the quarter-matrix neighbours of the best pair, twice
+    for (int64_t qx = 0; qx <= last; qx += 2)
+        for (int64_t qy = 0; qy <= last; qy += 2) {
+            if (std::llabs(qx - qy) < apart || (qx == 0 && qy == apart)) continue;
             float ms = 0.f;
-            groot_status s2 = moving_x ? time_pair(q, other, &ms) : time_pair(other, q, &ms);
-            if (s2 != GROOT_OK) return s2;
-            if (ms < *t_best) { *t_best = ms; *q_best = q; }
+            if ((st = time_pair(qx, qy, &ms)) != GROOT_OK) return st;
+            if (ms < best) { best = ms; bx = qx; by = qy; }
         }
-        return GROOT_OK;
-    };
-    if (last >= apart) {
-        float tx = std::numeric_limits<float>::max();
-        int64_t qx = 0, qy = last;
-        if ((st = scan(true, last, &tx, &qx)) != GROOT_OK) return st;
-        for (int round = 0; round < 3; ++round) {
-            float ty = std::numeric_limits<float>::max(), tx2 = std::numeric_limits<float>::max();
-            if ((st = scan(false, qx, &ty, &qy)) != GROOT_OK) return st;
-            if (ty < best) { best = ty; bx = qx; by = qy; }
-            if (round == 2) break;
-            if ((st = scan(true, qy, &tx2, &qx)) != GROOT_OK) return st;
-            if (tx2 < best) { best = tx2; bx = qx; by = qy; }
-        }
+    for (int round = 0; round < 2; ++round) {
+        const int64_t cx = bx, cy = by;
+        for (int64_t dx = -1; dx <= 1; ++dx)
+            for (int64_t dy = -1; dy <= 1; ++dy) {
+                const int64_t qx = cx + dx, qy = cy + dy;
+                if ((dx == 0 && dy == 0) || qx < 0 || qy < 0 || qx > last || qy > last || std::llabs(qx - qy) < apart) continue;
+                float ms = 0.f;
+                if ((st = time_pair(qx, qy, &ms)) != GROOT_OK) return st;
+                if (ms < best) { best = ms; bx = qx; by = qy; }
+            }
+        if (bx == cx && by == cy) break;
     }
     *x_offset = (size_t)bx * step;
     *y_offset = (size_t)by * step;
