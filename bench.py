@@ -298,7 +298,8 @@ def place_features(G, torch, wl, plan, seed, n, F, tries, fixed=None):
         slots = min(tries + 3, int(0.75 * free // (numel * 4)))      # a quarter of the memory stays free for the rest
     while slots >= 3 and arena is None:
         try:
-            arena = torch.zeros((slots * numel,), dtype=torch.float32, device="cuda")
+            arena = torch.empty((slots * numel,), dtype=torch.float32, device="cuda")
+            arena.uniform_(-1.0, 1.0)                    # values like the features': the times depend a little on the data
         except RuntimeError:                             # out of memory after all: a smaller arena
             torch.cuda.empty_cache()
             slots -= 1
