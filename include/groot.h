@@ -390,7 +390,9 @@ groot_status groot_rows_scatter(const int64_t *ids_dev, int64_t n, const float *
  * not visible to a program, but it shows in the time, so this call measures:
  * it runs groot_spmm_execute (three times per try, timed with events on
  * hip_stream, which it synchronises) with X and Y at every pair of offsets in
- * the arena that are multiples of half a matrix and do not overlap, then at
+ * the arena that are multiples of half a matrix (of a larger even number of
+ * quarters once the arena holds more than 16 such offsets: at most 256 pairs
+ * are tried, whatever the arena's size) and do not overlap, then at
  * the quarter-matrix neighbours of the best pair (offsets in whole 4 KB
  * units), and returns the byte offsets of the fastest pair, its time per step,
  * and the time with the two matrices back to back at the start of the arena.

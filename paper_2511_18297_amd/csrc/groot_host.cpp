@@ -751,8 +751,10 @@ extern "C" groot_status groot_feature_placement(const groot_plan *plan, void *ar
     // every pair of half-matrix offsets that does not overlap (the fast pairs are those in which both matrices
     // straddle a boundary between the two classes of address ranges, which a search along one coordinate at a time
     // does not find), then the quarter-matrix neighbours of the best pair, twice
-    for (int64_t qx = 0; qx <= last; qx += 2)
-        for (int64_t qy = 0; qy <= last; qy += 2) {
+    int64_t hop = 2;                                           // at most 16 offsets per matrix: 256 pairs whatever the arena's size
+    while (last / hop + 1 > 16) hop += 2;
+    for (int64_t qx = 0; qx <= last; qx += hop)
+        for (int64_t qy = 0; qy <= last; qy += hop) {
             if (std::llabs(qx - qy) < apart || (qx == 0 && qy == apart)) continue;
             float ms = 0.f;
             if ((st = time_pair(qx, qy, &ms)) != GROOT_OK) return st;
