@@ -277,6 +277,7 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
         "roofline": {"bound": "hbm", "kernel": "sage_pipe_kernel (+ hd_kernel)", "achieved": round(gbps, 1),
                      "peak": 8000.0, "unit": "GB/s", "frac": round(gbps / 8000.0, 4), "traffic": None,
                      "algorithmic_bytes": bytes_layer},
+        "bf16_pieces_per_operand": next((int(t.partition("=")[2]) for t in args.tune if t.startswith("sage_pieces=")), 3),
         "fp32_equivalent_tflops": round(tflops, 2), "fp32_mfma_peak_tflops": 157.3,
         "unfused_ms_per_step": round(ms_unfused, 4), "speedup_vs_unfused": round(ms_unfused / ms_fused, 3),
         "max_abs_diff_vs_unfused": worst, "placement": placement, "device": props.name}))

@@ -448,7 +448,12 @@ groot_status groot_plan_hd_pieces(const groot_plan *plan, int64_t capacity, int6
  * wavefronts; graphs with explicit weights always take the latter),
  * "sage_split" (kernel 0 only: 1 bf16 piece products, 0 fp32 matrix
  * instructions), "sage_gap" (kernel 0 only: 0..4, the pause between its matrix
- * instructions; all three read at each call of groot_sage_layer_forward)
+ * instructions; all three read at each call of groot_sage_layer_forward),
+ * "sage_pieces" (kernel 1 only: 3, default: every fp32 operand of the layer's
+ * dense products is cut into three bf16 pieces and six piece products are
+ * kept, fp32 accuracy; 2: two pieces and three products, half the matrix
+ * instructions, every product exact to 3 x 2^-18 of its magnitude instead of
+ * 2^-23; read at each call),
  * "csr_compress" (1, default: groot_plan_upload also builds a compact copy of
  * the matrix for the pipelined LD kernel, 4-byte row pointers and 2-byte column
  * codes, when every entry of a short row lies within 16,384 rows of its own row

@@ -808,7 +808,8 @@ extern "C" groot_status groot_sage_layer_forward_io(const groot_plan *plan, cons
         hd.split_rows = plan->dev.split_rows_rank;
         if (hd.n_chunks) err = launch_hd(hd, X_dev, hd.hd_agg, F_in, hip_stream);
         if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F_in, hip_stream);
-        if (!err) err = launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F_in, F_out, hip_stream);
+        if (!err) err = launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F_in, F_out,
+                                         tuning().sage_pieces.load(), hip_stream);
     } else {
         // the kernel for explicit weights (64 -> 64): high-degree sums go to H first and are picked up from there
         if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F_in, hip_stream);
@@ -1381,6 +1382,11 @@ extern "C" groot_status groot_set_tuning(const char *name, int64_t value)
     if (k == "sage_split" || k == "sage_kernel" || k == "uniform_detect") {
         if (value < 0 || value > 1) return fail(GROOT_EINVAL, "groot_set_tuning: " + k + " must be 0 or 1");
         (k == "sage_split" ? tuning().sage_split : k == "sage_kernel" ? tuning().sage_kernel : tuning().uniform_detect).store((int)value);
+        return GROOT_OK;
+    }
+    if (k == "sage_pieces") {
+        if (value != 2 && value != 3) return fail(GROOT_EINVAL, "groot_set_tuning: sage_pieces must be 2 or 3");
+        tuning().sage_pieces = (int)value;
         return GROOT_OK;
     }
     if (k == "sage_gap") {

@@ -43,6 +43,7 @@ struct Tuning {
     std::atomic<int> sage_gap{2};          // pacing of the fused layer's matrix wavefronts, see launch_sage
     std::atomic<int> sage_split{1};        // 12-wavefront fused layer: 1 dense products as six bf16 piece products, 0 fp32 matrix instructions
     std::atomic<int> sage_kernel{1};       // fused layer: 1 one self-contained wavefront per SIMD, 0 the 12-wavefront kernel
+    std::atomic<int> sage_pieces{3};       // fused layer (sage_kernel 1): bf16 pieces per fp32 operand of the dense products, 3 or 2
     std::atomic<int> uniform_detect{1};    // groot_plan_upload looks whether explicit weights are row-uniform (see DevicePlan)
     std::atomic<int> csr_compress{1};      // groot_plan_upload builds the compact CSR for the pipelined LD kernel when it can
     std::atomic<int> pipe_depth{0};        // gather slots per row of the pipelined LD kernel: 0 the smallest that fits, or 5..8
@@ -120,7 +121,8 @@ int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, co
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t F_in, int32_t F_out, void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform weights
+                     int relu, int32_t F_in, int32_t F_out, int pieces, void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform
+                                                                                         // weights; pieces 3 (fp32 accuracy) or 2
 // Schedule of the high-degree rows built on the device (groot_hd_sched_device.hip): the pieces in execution order,
 // once with rows named by id and once by their place in the list of high-degree rows, and the split rows likewise.
 struct DeviceHdSchedule {

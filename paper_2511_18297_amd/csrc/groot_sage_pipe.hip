@@ -19,6 +19,9 @@
 // (hi hi, hi mid, mid hi, hi lo, lo hi, mid mid; the dropped ones are below 2^-24), summed in fp32 in the
 // instruction's accumulator.  The weights are cut once per workgroup into LDS, in the operand layout of the
 // instruction (48 KB, one 16-byte read per lane and operand); the tile is cut when it is parked.
+// With two pieces instead of three (template argument P; a knob of the library, off by default) a product keeps
+// hi hi, hi mid and mid hi: what is dropped and what the two pieces do not represent stays below 3 x 2^-18 of
+// |x| |w| per product, a bar twice as wide as fp32's for half the matrix instructions.
 //
 // High-degree rows are aggregated beforehand by the HD kernel into a side buffer of the plan, one row per
 // high-degree row in ascending order of their ids; a tile that contains one (or a row with more than kSpD entries,
@@ -53,7 +56,7 @@ struct SpCfg {
     static constexpr int kORowShift = FO == 64 ? 8 : FO == 32 ? 7 : 6;   // log2 of an output row's bytes
     static_assert(FI == 64 || FI == 32, "input width");
     static_assert(FO == 64 || FO == 32 || FO == 16, "output width");
-    static_assert(kSpRows * kOStride * 4 <= 3 * kPlane, "the result tile fits the parked tile's space");
+    static_assert(kSpRows * kOStride * 4 <= 2 * kPlane, "the result tile fits the parked tile's space (two planes at least)");
 };
 
 typedef __bf16 sp_bf2 __attribute__((ext_vector_type(2)));
@@ -87,20 +90,21 @@ __device__ __forceinline__ void sp_split3(float a, float b, unsigned &hi, unsign
     lo = sp_pack2(ra, rb);
 }
 
-// four consecutive elements k..k+3 of tile row `row` into the three planes (row stride kBRow, plane size kPlane)
-template <int kBRow, int kPlane>
+// four consecutive elements k..k+3 of tile row `row` into the P planes (row stride kBRow, plane size kPlane)
+template <int kBRow, int kPlane, int P>
 __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
 {
     unsigned h0, m0, l0, h1, m1, l1;
-    sp_split3(x[0], x[1], h0, m0, l0);
+    sp_split3(x[0], x[1], h0, m0, l0);                   // P = 2: the third piece is never used and is not computed
     sp_split3(x[2], x[3], h1, m1, l1);
     char *p = tile + row * kBRow + k * 2;
     *(sp_u2 *)p = (sp_u2){h0, h1};
     *(sp_u2 *)(p + kPlane) = (sp_u2){m0, m1};
-    *(sp_u2 *)(p + 2 * kPlane) = (sp_u2){l0, l1};
+    if constexpr (P == 3) *(sp_u2 *)(p + 2 * kPlane) = (sp_u2){l0, l1};
 }
 
-template <int W, int FI, int FO, int NW, int D>   // W: kOnes or kMean; D: gather slots per row on the pipelined path
+// W: kOnes or kMean; D: gather slots per row on the pipelined path; P: bf16 pieces per fp32 operand, 3 or 2
+template <int W, int FI, int FO, int NW, int D, int P>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *H, int64_t zero_off, char *trash,
@@ -108,6 +112,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     int32_t T, int64_t n_tiles, int64_t tiles_per_part, int64_t waves_per_part, int32_t parts,
     const int32_t *__restrict__ hd_rows, int32_t n_hd, const char *__restrict__ hd_agg)
 {
+    static_assert(P == 3 || P == 2, "pieces per operand");
     using C = SpCfg<FI, FO, NW>;
     constexpr int F = FI;
     constexpr int kSpD = D, kSpSlots = kSpRows * kSpD, kSpH = (kSpSlots + kWave - 1) / kWave;
@@ -117,8 +122,8 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     using Slot = typename std::conditional<W == kExplicit, SlotW, int64_t>::type;
     __shared__ __align__(16) Slot s_slot[kSpWaves][kSpSlots];
     __shared__ float s_inv[kSpWaves][kSpRows];
-    __shared__ __align__(16) char s_A[kSpWaves][3 * kSpPlane];           // F = 64: 13,056 B per wavefront; the result tile reuses it
-    __shared__ __align__(16) sp_u4 s_W[kNb][kKs][3][kWave];              // F = 64: 49,152 B: [nb][ks][piece][lane] B operands
+    __shared__ __align__(16) char s_A[kSpWaves][P * kSpPlane];           // F = 64, P = 3: 13,056 B per wavefront; the result tile reuses it
+    __shared__ __align__(16) sp_u4 s_W[kNb][kKs][P][kWave];              // F = 64, P = 3: 49,152 B: [nb][ks][piece][lane] B operands
     __shared__ float s_bias[FO];
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
                 pc[2][e / 2] = lo_;
             }
 #pragma unroll
-            for (int q = 0; q < 3; ++q) s_W[nb][ks][q][l] = pc[q];
+            for (int q = 0; q < P; ++q) s_W[nb][ks][q][l] = pc[q];
         }
     }
     if (threadIdx.x < FO) s_bias[threadIdx.x] = bias ? bias[threadIdx.x] : 0.0f;
@@ -265,8 +270,8 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
 #pragma unroll
         for (int grp = 0; grp < kSpG; ++grp) {
             const v4f a = sum(rr[grp]);
-            sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
-            sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, F + 4 * f, rr[grp].self);
+            sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, 4 * f, a);
+            sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, F + 4 * f, rr[grp].self);
             issue(rr[grp], tile + stride, grp);
         }
         if (fix_cur) {
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
                         a = ld_row_sum<W, false, 8>(s, e, col, val, (const v4f *)X, kSpL, f);
                     }
                 }
-                if (redo) sp_park<kSpBRow, kSpPlane>(a_tile, grp * kSpRpg + g, 4 * f, a);
+                if (redo) sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, 4 * f, a);
             }
         }
         sp_wave_sync();
@@ -304,38 +309,37 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             acc[nb] = (v4f){bv, bv, bv, bv};
         }
         const char *a_lane = a_tile + jl * kSpBRow + 16 * kq;
-        // 3 kKs steps (ks, weight piece pb = hi, mid, lo), each against the tile pieces whose product is kept
-        // (hi: lo, mid, hi; mid: mid, hi; lo: hi), on kNb independent accumulators.  The weight operands of step
-        // s + 1 are read from LDS while step s runs; a tile piece of the next ks is read as soon as its register
-        // is dead (lo after the first step, mid after the second, hi after the third, where the first eight
-        // matrix instructions of the next ks do not need it yet).
-        sp_u4 aop[3], bop[2][kNb];
+        // P kKs steps (ks, weight piece pb = hi, mid, lo), each against the tile pieces whose product is kept
+        // (P = 3: hi with lo, mid, hi; mid with mid, hi; lo with hi.  P = 2: hi with mid, hi; mid with hi), on kNb
+        // independent accumulators.  The weight operands of step s + 1 are read from LDS while step s runs; a tile
+        // piece of the next ks is read as soon as its register is dead (the last piece after the first step, the one
+        // before it after the second, hi after the last step, where the first matrix instructions of the next ks do
+        // not need it yet).
+        sp_u4 aop[P], bop[2][kNb];
         auto read_a = [&](int ks, int pc) { aop[pc] = *(const sp_u4 *)(a_lane + pc * kSpPlane + 64 * ks); };
         auto read_b = [&](int s_) {
-            const int ks = s_ / 3, pb = s_ % 3;
+            const int ks = s_ / P, pb = s_ % P;
 #pragma unroll
             for (int nb = 0; nb < kNb; ++nb) bop[s_ & 1][nb] = s_W[nb][ks][pb][l];
         };
-        read_a(0, 2);
-        read_a(0, 1);
-        read_a(0, 0);
+#pragma unroll
+        for (int pc = P - 1; pc >= 0; --pc) read_a(0, pc);
         read_b(0);
 #pragma unroll
-        for (int s_ = 0; s_ < 3 * kKs; ++s_) {
-            const int ks = s_ / 3, pb = s_ % 3;
-            if (s_ + 1 < 3 * kKs) read_b(s_ + 1);
-            if (ks + 1 < kKs && pb == 1) read_a(ks + 1, 2);          // lo is dead after the first step of ks
-            if (ks + 1 < kKs && pb == 2) read_a(ks + 1, 1);          // mid after the second
+        for (int s_ = 0; s_ < P * kKs; ++s_) {
+            const int ks = s_ / P, pb = s_ % P;
+            if (s_ + 1 < P * kKs) read_b(s_ + 1);
+            if (ks + 1 < kKs && pb >= 1) read_a(ks + 1, P - pb);     // piece P - pb was last used in the step before this one
             __builtin_amdgcn_sched_barrier(0);                       // the reads stay ahead of this step's matrix instructions
 #pragma unroll
-            for (int pa = 2 - pb; pa >= 0; --pa)
+            for (int pa = P - 1 - pb; pa >= 0; --pa)
 #pragma unroll
                 for (int nb = 0; nb < kNb; ++nb)
                     acc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(sp_bf8, aop[pa]),
                                                                       __builtin_bit_cast(sp_bf8, bop[s_ & 1][nb]),
                                                                       acc[nb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (ks + 1 < kKs && pb == 2) read_a(ks + 1, 0);          // hi after the third
+            if (ks + 1 < kKs && pb == P - 1) read_a(ks + 1, 0);      // hi after the last step
         }
         sp_wave_sync();                                  // all reads of the parked tile are done: its space takes the result
         // ---- result: lane holds rows 4 kq + r of column 16 nb + jl; through LDS to whole rows per lane group
@@ -362,9 +366,10 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
 }
 
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t FI, int32_t FO, void *stream)
+                     int relu, int32_t FI, int32_t FO, int pieces, void *stream)
 {
-    if (!weights_ok(dp) || !dp.zero_row || (FI != 64 && FI != 32) || (FO != 64 && FO != 32 && FO != 16))
+    if (!weights_ok(dp) || !dp.zero_row || (FI != 64 && FI != 32) || (FO != 64 && FO != 32 && FO != 16) ||
+        (pieces != 2 && pieces != 3))
         return (int)hipErrorInvalidValue;
     // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
     if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
@@ -390,14 +395,17 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
-#define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD)                                                                       \
-    sage_pipe_kernel<WM, FFI, FFO, kNwRun, DD><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(                 \
+#define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD, PP)                                                                   \
+    sage_pipe_kernel<WM, FFI, FFO, kNwRun, DD, PP><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(             \
         dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, byte_distance(X, dp.zero_row), trash, Wn, Ws, bias, relu, \
         dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows,         \
         (const char *)dp.hd_agg)
+#define GROOT_SAGE_PIPE_P(WM, FFI, FFO, DD)                               \
+    if (pieces == 2) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD, 2);         \
+    else GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD, 3)
 #define GROOT_SAGE_PIPE_D(WM, FFI, FFO)                                   \
-    if (dp.sage_depth == 5) GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, 5);      \
-    else GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, 6)
+    if (dp.sage_depth == 5) { GROOT_SAGE_PIPE_P(WM, FFI, FFO, 5); }       \
+    else { GROOT_SAGE_PIPE_P(WM, FFI, FFO, 6); }
 #define GROOT_SAGE_PIPE_FO(WM, FFI)                            \
     if (FO == 64) { GROOT_SAGE_PIPE_D(WM, FFI, 64); }          \
     else if (FO == 32) { GROOT_SAGE_PIPE_D(WM, FFI, 32); }     \
@@ -410,6 +418,7 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
         else { GROOT_SAGE_PIPE_FO(kOnes, 32); }
     }
 #undef GROOT_SAGE_PIPE_D
+#undef GROOT_SAGE_PIPE_P
 #undef GROOT_SAGE_PIPE_FO
 #undef GROOT_SAGE_PIPE_LAUNCH
     return (int)hipGetLastError();

@@ -281,8 +281,10 @@ def sage_variant(request):
     G.groot_set_tuning("sage_split", 1)
 
 
-def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64, F_out=None):
-    """F_out None: the square call (F -> F); else the call with separate input and output widths."""
+def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, row_scale=None, F=64, F_out=None,
+                pieces=3):
+    """F_out None: the square call (F -> F); else the call with separate input and output widths.  pieces: what
+    the library's sage_pieces knob is set to (the caller sets it), for the tolerance."""
     rng = np.random.default_rng(seed)
     X = wl.uniform_features_numpy(seed, 0, n, F)
     if row_scale is not None:
@@ -308,7 +310,7 @@ def _sage_check(torch, g, rowptr, col, val, T, n, seed, relu, with_bias, what, r
     want, A, S = oracle.sage_layer_f64(rowptr, col, val, X, Wn, Ws, b, relu)
     a64 = lambda a: np.abs(a.astype(np.float64))
     scale = np.abs(A) @ a64(Wn) + a64(X) @ a64(Ws) + (a64(b) if b is not None else 0.0)
-    tol = layer_tolerance(S, scale, a64(Wn))
+    tol = layer_tolerance(S, scale, a64(Wn), pieces=pieces)
     err = np.abs(out[guard:n + guard].astype(np.float64) - want)
     assert np.isfinite(err).all(), f"{what}: non-finite output"
     assert (err <= tol).all(), f"{what}: max err/tol {np.max(err / tol)}"
@@ -388,6 +390,26 @@ def test_fused_sage_layer_bf16_pieces_keep_fp32_accuracy(torch_cuda):
     finally:
         G.groot_set_tuning("sage_kernel", 1)
         G.groot_set_tuning("sage_split", 1)
+
+
+@pytest.mark.parametrize("F_in,F_out", [(64, 64), (32, 32), (64, 16), (32, 64)])
+@pytest.mark.parametrize("n_bits,batch,T,relu,with_bias", [(48, 2, 32, True, True), (17, 3, 5, False, False)])
+def test_fused_sage_layer_with_two_pieces_per_operand(torch_cuda, F_in, F_out, n_bits, batch, T, relu, with_bias):
+    """The knob sage_pieces = 2: three piece products instead of six.  Within the wider bar that two pieces allow
+    (3 * 2^-18 of the dense part's absolute terms more), and not the same numbers as with three pieces (the knob
+    does reach the kernel)."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    n = batch * aig.num_nodes
+    args = (torch_cuda, g, rowptr, col, val, T, n, 900 + n_bits + F_in + F_out, relu, with_bias)
+    three = _sage_check(*args, f"sage {F_in}->{F_out}, three pieces", F=F_in, F_out=F_out)[0]
+    G.groot_set_tuning("sage_pieces", 2)
+    try:
+        two, scale, err, _ = _sage_check(*args, f"sage {F_in}->{F_out}, two pieces", F=F_in, F_out=F_out, pieces=2)
+    finally:
+        G.groot_set_tuning("sage_pieces", 3)
+    assert not np.array_equal(two, three)
+    with pytest.raises(G.GrootError):
+        G.groot_set_tuning("sage_pieces", 4)
 
 
 def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):

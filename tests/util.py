@@ -31,11 +31,14 @@ def assert_close_to_oracle(Y_gpu, Y64, S, what=""):
     return float(np.max(err / tol))
 
 
-def layer_tolerance(S, scale, absWn, floor=1e-6):
+def layer_tolerance(S, scale, absWn, floor=1e-6, pieces=3):
     """Accepted deviation of the fused layer from the fp64 layer, element by element.  The aggregation's own
     bar, 1e-5 * sum|a_ij x_jk| + 1e-6 per element of A_hat X, reaches the output through |Wn|; the dense part
     is an fp32 sum of 2F + 1 <= 129 terms (two products per input feature and the bias) whose rounding error
     is at most (2F + 2) * 2^-24 <= 7.8e-6 of the sum of their magnitudes in any order of summation, each
     product being exact to 2^-23 of itself: together below 1e-5 * scale, scale = |A_hat X| |Wn| + |X| |Ws| + |b|,
-    the same coefficient as the aggregation's bar."""
-    return (1e-5 * S + floor) @ absWn + 1e-5 * scale + floor
+    the same coefficient as the aggregation's bar.  With two bf16 pieces per operand instead of three (the
+    library's sage_pieces knob) a product is exact to 3 * 2^-18 of itself instead (each operand is represented to
+    2^-18, and the product of the two second pieces, at most 2^-18, is dropped), which adds that much of scale."""
+    dense = 1e-5 + (3 * 2.0 ** -18 if pieces == 2 else 0.0)
+    return (1e-5 * S + floor) @ absWn + dense * scale + floor
