@@ -147,27 +147,38 @@ def test_training_through_the_library_and_the_regrowth_ablation():
     # the whole model through the fused layer kernel and nothing else: the 4 feature columns padded with zero
     # columns (and zero weight rows) to the narrowest input width, 32; the 5-class head as a layer without
     # aggregation (Wn = 0) and without ReLU, its 5 output columns padded with zero weights to 16
-    with torch.no_grad():
-        pad_rows = lambda w: torch.cat([w.detach(), torch.zeros((HIDDEN - w.shape[0], w.shape[1]), device=w.device)]).contiguous()
-        h = torch.cat([Xb, torch.zeros((n, HIDDEN - Xb.shape[1]), device="cuda")], dim=1).contiguous()
-        for layer in range(3):
-            wn, ws = model.wn[layer], model.ws[layer]
-            if layer == 0:
-                wn, ws = pad_rows(wn), pad_rows(ws)
-            nxt = torch.empty((n, HIDDEN), device="cuda")
-            G.groot_sage_layer_forward_io(plan_big, h, wn.detach().contiguous(), ws.detach().contiguous(),
-                                          model.b[layer].detach().contiguous(), True, nxt, HIDDEN, HIDDEN)
-            h = nxt
-        head_w = torch.zeros((HIDDEN, 16), device="cuda")
-        head_w[:, :CLASSES] = model.out.weight.detach().t()
-        head_b = torch.zeros(16, device="cuda")
-        head_b[:CLASSES] = model.out.bias.detach()
-        out16 = torch.empty((n, 16), device="cuda")
-        G.groot_sage_layer_forward_io(plan_big, h, torch.zeros_like(head_w), head_w, head_b, False, out16, HIDDEN, 16)
-        torch.cuda.synchronize()
-    assert float(out16[:, CLASSES:].abs().max()) == 0.0
-    assert float((out16[:, :CLASSES] - logits_full).abs().max()) <= 1e-3 * float(logits_full.abs().max())
-    assert bool((out16[:, :CLASSES].argmax(1) == pred_full).all())
+    # The same with the layer's cheaper dense products (two bf16 pieces per operand instead of three): the
+    # classification does not change.
+    def whole_model_fused():
+        with torch.no_grad():
+            pad_rows = lambda w: torch.cat([w.detach(), torch.zeros((HIDDEN - w.shape[0], w.shape[1]), device=w.device)]).contiguous()
+            h = torch.cat([Xb, torch.zeros((n, HIDDEN - Xb.shape[1]), device="cuda")], dim=1).contiguous()
+            for layer in range(3):
+                wn, ws = model.wn[layer], model.ws[layer]
+                if layer == 0:
+                    wn, ws = pad_rows(wn), pad_rows(ws)
+                nxt = torch.empty((n, HIDDEN), device="cuda")
+                G.groot_sage_layer_forward_io(plan_big, h, wn.detach().contiguous(), ws.detach().contiguous(),
+                                              model.b[layer].detach().contiguous(), True, nxt, HIDDEN, HIDDEN)
+                h = nxt
+            head_w = torch.zeros((HIDDEN, 16), device="cuda")
+            head_w[:, :CLASSES] = model.out.weight.detach().t()
+            head_b = torch.zeros(16, device="cuda")
+            head_b[:CLASSES] = model.out.bias.detach()
+            out16 = torch.empty((n, 16), device="cuda")
+            G.groot_sage_layer_forward_io(plan_big, h, torch.zeros_like(head_w), head_w, head_b, False, out16, HIDDEN, 16)
+            torch.cuda.synchronize()
+        return out16
+
+    try:
+        for pieces in (3, 2):
+            G.groot_set_tuning("sage_pieces", pieces)
+            out16 = whole_model_fused()
+            assert float(out16[:, CLASSES:].abs().max()) == 0.0
+            assert float((out16[:, :CLASSES] - logits_full).abs().max()) <= 1e-3 * float(logits_full.abs().max()), pieces
+            assert bool((out16[:, :CLASSES].argmax(1) == pred_full).all()), pieces
+    finally:
+        G.groot_set_tuning("sage_pieces", 3)
 
     P = 8
     vb = G.groot_graph_view(g_big)
