@@ -218,6 +218,18 @@ def sage_layer_f64(rowptr, col, val, X, Wn, Ws, b, relu):
     return (np.maximum(H, 0.0) if relu else H), A, S
 
 
+def sage_layer_backward_data_f64(rowptr, col, val, dZ, Wn, Ws):
+    """Gradient of a GraphSAGE-mean layer with respect to its input, in fp64 (Section "GNN and Edge Re-growth
+    After Partition": the model is trained).  For Z = (A_hat X) Wn + X Ws + b and dZ the gradient of the loss
+    at Z, the chain rule gives dX = A_hat^T (dZ Wn^T) + dZ Ws^T; written here as (A_hat^T dZ) Wn^T + dZ Ws^T
+    so that the transposed aggregation takes the fp32 input itself.  Returns dX, A_hat^T dZ and the latter's
+    sum of absolute terms (for the error scale).  Pinned by automatic differentiation of the dense layer on
+    the 18- and 51-node multipliers, by central differences, and by the adjoint identity <dZ, J V> = <J^T dZ, V>."""
+    T, S = spmm_t_f64(rowptr, col, val, dZ)
+    dX = T @ Wn.astype(np.float64).T + np.asarray(dZ, dtype=np.float64) @ Ws.astype(np.float64).T
+    return dX, T, S
+
+
 def sage_forward_f64(rowptr, col, val, X, W1n, W1s, b1, W2n, W2s, b2):
     """Two GraphSAGE-mean layers (Section "GNN and Edge Re-growth After
     Partition": the layer aggregates neighbour features, then transforms):

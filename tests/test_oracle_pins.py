@@ -401,6 +401,46 @@ def test_sage_layer_special_cases():
     assert np.allclose(H[:, 0::2], 0.25, rtol=0, atol=2e-7) and (H[:, 1::2] == 0.0).all()
 
 
+@pytest.mark.parametrize("n", [2, 3])
+def test_sage_layer_backward_data_equals_autograd_of_the_dense_layer(n):
+    """The oracle's input gradient of the layer against automatic differentiation of the dense layer
+    relu(A_hat X Wn + X Ws + b) (dense adjacency written from the fanin records; loss = <H, R> for a random R),
+    against central differences of the oracle's own forward layer along random directions, and through the
+    adjoint identity with the linear part of the forward layer."""
+    import torch
+    csr, A_hat, X, Wn, Ws, b = _layer_inputs(n, 8, 43)
+    N, F = X.shape
+    rng = np.random.default_rng(7 + n)
+    R = rng.uniform(-1, 1, (N, F))
+    A_t, Wn_t, Ws_t, b_t = (torch.from_numpy(np.asarray(a, dtype=np.float64)) for a in (A_hat, Wn, Ws, b))
+    X_t = torch.from_numpy(X.astype(np.float64)).requires_grad_(True)
+    Z_t = A_t @ X_t @ Wn_t + X_t @ Ws_t + b_t
+    (torch.relu(Z_t) * torch.from_numpy(R)).sum().backward()
+    Z = Z_t.detach().numpy()
+    assert (Z > 1e-3).any() and (Z < -1e-3).any()
+    dZ = (R * (Z > 0)).astype(np.float32)                      # the oracle takes fp32 inputs, as the library does
+    # gradient for exactly this dZ: the loss <relu(Z), R'> with R' = dZ where Z > 0 has it
+    X_t.grad = None
+    Z_t = A_t @ X_t @ Wn_t + X_t @ Ws_t + b_t
+    (Z_t * torch.from_numpy(dZ.astype(np.float64))).sum().backward()
+    want = X_t.grad.numpy()
+    dX, T, S = oracle.sage_layer_backward_data_f64(*csr, dZ, Wn, Ws)
+    assert np.allclose(dX, want, rtol=0, atol=1e-14)
+    assert np.allclose(T, A_hat.T @ dZ.astype(np.float64), rtol=0, atol=1e-15)
+    assert np.allclose(S, np.abs(A_hat.T) @ np.abs(dZ.astype(np.float64)), rtol=0, atol=1e-15)
+    # central differences of the forward layer without activation (it is linear in X: exact up to rounding)
+    for trial in range(3):
+        V = rng.uniform(-1, 1, (N, F)).astype(np.float32)
+        Hp, _, _ = oracle.sage_layer_f64(*csr, (X + V).astype(np.float32), Wn, Ws, b, False)
+        Hm, _, _ = oracle.sage_layer_f64(*csr, (X - V).astype(np.float32), Wn, Ws, b, False)
+        directional = 0.5 * float(((Hp - Hm) * dZ.astype(np.float64)).sum())
+        assert abs(directional - float((dX * V.astype(np.float64)).sum())) <= 1e-5 * max(1.0, abs(directional))
+    # adjoint identity with the forward layer's linear part J V = (A_hat V) Wn + V Ws
+    V = rng.uniform(-1, 1, (N, F)).astype(np.float32)
+    JV, _, _ = oracle.sage_layer_f64(*csr, V, Wn, Ws, None, False)
+    assert abs(float((JV * dZ.astype(np.float64)).sum()) - float((dX * V.astype(np.float64)).sum())) <= 1e-12
+
+
 def test_sage_forward_is_two_layers():
     """The two-layer forward is the layer applied twice: ReLU and rounding to fp32 between the layers, none after."""
     csr, _, X, W1n, W1s, b1 = _layer_inputs(4, 8, 61)
