@@ -223,7 +223,7 @@ def partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, pro
         "device": props.name}))
 
 
-def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name, props, placement):
+def sage_layer_bench(args, G, torch, np, aig, g, T, plan, X, H, n, nnz, F, batch, name, props, placement):
     """Fused layer (X -> H, the pair of buffers the placement search kept) against the unfused form (library SpMM
     into a buffer of its own, then torch for the dense part)."""
     assert F in (32, 64), "the fused layer is built for F = 64 and F = 32"
@@ -259,6 +259,42 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
     worst = 0.0
     for lo in range(0, n, 1 << 24):
         worst = max(worst, float((H[lo:lo + (1 << 24)] - ref[lo:lo + (1 << 24)]).abs().max()))
+    del ref
+
+    # The layer's input gradient, dX = A_hat^T (dZ Wn^T) + dZ Ws^T, through the same kernel (X plays dZ, H takes
+    # dX), against the unfused form: one dense product, the library's SpMM on the transposed graph, a second dense
+    # product added to it.
+    WnT, WsT = Wn.t().contiguous(), Ws.t().contiguous()
+    Xs = Y                                                   # dZ / deg; the unfused forward's buffer is free again
+    G.groot_rows_over_degree(plan, X, Xs, F)
+
+    def fused_backward():
+        G.groot_sage_layer_backward_data(plan, Xs, WnT, WsT, H, F, F)
+
+    ms_backward = timed(fused_backward, args.steps, args.warmup)
+    backward = {"ms_per_step": round(ms_backward, 4), "unfused_ms_per_step": None, "speedup_vs_unfused": None,
+                "max_abs_diff_vs_unfused": None}
+    torch.cuda.empty_cache()                                 # the unfused forward's result is still cached
+    if torch.cuda.mem_get_info()[0] > 2.6 * X.numel() * 4:   # two more matrices and the transposed graph's plan
+        plan_t = G.groot_spmm_plan(G.groot_graph_transpose(g), T)
+        G.groot_plan_upload(plan_t, F)
+        G1, out = torch.empty_like(X), torch.empty_like(X)
+
+        def unfused_backward():
+            torch.mm(X, WnT, out=G1)
+            G.groot_spmm_execute(plan_t, G1, out, F)
+            return out.addmm_(X, WsT)
+
+        ms_unfused_backward = timed(unfused_backward, max(3, args.steps // 4), 1)
+        unfused_backward()
+        fused_backward()
+        torch.cuda.synchronize()
+        worst_b = 0.0
+        for lo in range(0, n, 1 << 24):
+            worst_b = max(worst_b, float((H[lo:lo + (1 << 24)] - out[lo:lo + (1 << 24)]).abs().max()))
+        backward.update(unfused_ms_per_step=round(ms_unfused_backward, 4),
+                        speedup_vs_unfused=round(ms_unfused_backward / ms_backward, 3), max_abs_diff_vs_unfused=worst_b)
+        del G1, out, plan_t
     flops = 2.0 * nnz * F + 2.0 * n * (2 * F) * F
     tflops = flops / (ms_fused * 1e-3) / 1e12
     # The dense products run as bf16 piece products (a sixteenth of the fp32 matrix instruction's time per
@@ -280,7 +316,7 @@ def sage_layer_bench(args, G, torch, np, aig, plan, X, H, n, nnz, F, batch, name
         "bf16_pieces_per_operand": next((int(t.partition("=")[2]) for t in args.tune if t.startswith("sage_pieces=")), 3),
         "fp32_equivalent_tflops": round(tflops, 2), "fp32_mfma_peak_tflops": 157.3,
         "unfused_ms_per_step": round(ms_unfused, 4), "speedup_vs_unfused": round(ms_unfused / ms_fused, 3),
-        "max_abs_diff_vs_unfused": worst, "placement": placement, "device": props.name}))
+        "max_abs_diff_vs_unfused": worst, "backward_data": backward, "placement": placement, "device": props.name}))
 
 
 def place_features(G, torch, wl, plan, seed, n, F, tries, fixed=None):
@@ -535,7 +571,7 @@ def main():
         partitioned_bench(args, G, torch, np, g, view, X, Y, n, nnz, F, T, name, props)
         return
     if args.sage_layer:                                  # X and the layer's output where the aggregation runs fastest
-        sage_layer_bench(args, G, torch, np, aig, plan, X, Y, n, nnz, F, batch, name, props, placement)
+        sage_layer_bench(args, G, torch, np, aig, g, T, plan, X, Y, n, nnz, F, batch, name, props, placement)
         return
 
     # ---- whole path: W warm-up steps, then exactly K timed steps

@@ -234,6 +234,41 @@ groot_status groot_sage_layer_forward(const groot_plan *plan, const float *X_dev
 groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
                                          const float *Ws_dev, const float *bias_dev, int32_t relu,
                                          float *H_dev, int32_t F_in, int32_t F_out, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * groot_sage_layer_backward_data -- the fused layer's gradient with respect to
+ * its input, for training (Section "GNN and Edge Re-growth After Partition":
+ * the GraphSAGE model is trained on small multipliers).  With Z = (A_hat X) Wn
+ * + X Ws + b the layer's pre-activation output and dZ the gradient of the loss
+ * at Z (the caller has already applied the activation's derivative),
+ *     dX = A_hat^T (dZ Wn^T) + dZ Ws^T = (A_hat^T dZ) Wn^T + dZ Ws^T.
+ * For a graph built symmetric with mean weights (groot_graph_build's default
+ * flags) A_hat^T = A D^-1, so the aggregation is the unit-weight sum of the
+ * rows of dZ / deg, and the call runs the forward layer's kernel on that
+ * matrix with the row's own operand scaled back by its stored length: one
+ * pass over dZ, no transposed graph, no N x F intermediate.
+ * dZ_over_deg_dev (device): row-major [N, F_out] fp32, row i of dZ divided by
+ * the stored length of row i (do it in the kernel that applies the
+ * activation's derivative, or with groot_rows_over_degree);
+ * WnT_dev, WsT_dev (device): the forward layer's weights transposed, row-major
+ * [F_out, F_in] fp32; dX_dev (device): row-major [N, F_in] fp32, fully
+ * overwritten, not overlapping dZ_over_deg_dev.  F_out = 32 or 64 (the width
+ * of dZ), F_in = 16, 32 or 64.  Accuracy, the "sage_pieces" knob, the plan's
+ * side buffer (one call per plan in flight) and the stream: as for
+ * groot_sage_layer_forward.  The gradients of the weights (X^T and (A_hat X)^T
+ * times dZ) are dense products over all rows and are left to the caller.
+ * Errors: EINVAL (NULL, alignment, widths, plan not uploaded or made on the
+ * device, graph not built symmetric with mean weights, overlap), EHIP.
+ *
+ * groot_rows_over_degree: out[i, :] = Z[i, :] / stored length of row i (rows
+ * of length 0 give 0), F a multiple of 4 in [4, 512], out_dev may be Z_dev.
+ * Only enqueues.  Errors: EINVAL, EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_sage_layer_backward_data(const groot_plan *plan, const float *dZ_over_deg_dev,
+                                            const float *WnT_dev, const float *WsT_dev, float *dX_dev,
+                                            int32_t F_out, int32_t F_in, void *hip_stream);
+groot_status groot_rows_over_degree(const groot_plan *plan, const float *Z_dev, float *out_dev, int32_t F,
+                                    void *hip_stream);
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------

@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_feature_placement", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_sage_layer_backward_data", "groot_rows_over_degree", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_feature_placement", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
     "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
@@ -64,6 +64,8 @@ _lib.groot_spmm_execute_rows.argtypes = [_vp, _vp, _vp, _i32, _i64, _vp, _vp]
 _lib.groot_plan_use_global_columns.argtypes = [_vp, _vp, _i64, _vp]
 _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _vp]
 _lib.groot_sage_layer_forward_io.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp]
+_lib.groot_sage_layer_backward_data.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]
+_lib.groot_rows_over_degree.argtypes = [_vp, _vp, _vp, _i32, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_lists_device_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
@@ -347,6 +349,26 @@ def groot_sage_layer_forward_io(pl: Plan, X, Wn, Ws, bias, relu: bool, H, F_in: 
                                             None if bias is None else _features(bias, "bias", 1, F_out),
                                             1 if relu else 0, _features(H, "H", n, F_out), F_in, F_out,
                                             _stream_handle(stream)))
+
+
+def groot_sage_layer_backward_data(pl: Plan, dZ_over_deg, WnT, WsT, dX, F_out: int = None, F_in: int = None,
+                                   stream=None) -> None:
+    """dZ_over_deg [N, F_out] (row i of dZ divided by the stored length of row i), WnT and WsT [F_out, F_in]
+    (the forward layer's weights transposed), dX [N, F_in]."""
+    F_out = dZ_over_deg.shape[1] if F_out is None else F_out
+    F_in = dX.shape[1] if F_in is None else F_in
+    n = _plan_rows(pl)
+    _check(_lib.groot_sage_layer_backward_data(pl.handle, _features(dZ_over_deg, "dZ_over_deg", n, F_out),
+                                               _features(WnT, "WnT", F_out, F_in), _features(WsT, "WsT", F_out, F_in),
+                                               _features(dX, "dX", n, F_in), F_out, F_in, _stream_handle(stream)))
+
+
+def groot_rows_over_degree(pl: Plan, Z, out, F: int = None, stream=None) -> None:
+    """out[i, :] = Z[i, :] / stored length of row i; out may be Z."""
+    F = Z.shape[1] if F is None else F
+    n = _plan_rows(pl)
+    _check(_lib.groot_rows_over_degree(pl.handle, _features(Z, "Z", n, F), _features(out, "out", n, F), F,
+                                       _stream_handle(stream)))
 
 
 def groot_plan_lists_device(pl: Plan, row_class, hd_rows, ld_rows, ld_rows_by_degree, ld_deg_offsets, counts,

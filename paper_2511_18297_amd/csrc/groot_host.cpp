@@ -66,6 +66,7 @@ struct groot_graph {
     std::vector<int32_t> col;
     std::vector<float> val;
     std::vector<uint8_t> pol;       // empty for graphs not built from an AIG
+    bool symmetric = false;         // built with GROOT_SYMMETRIC: entry (i, j) is stored iff (j, i) is
 };
 
 struct groot_plan {
@@ -226,6 +227,7 @@ extern "C" groot_status groot_graph_build(int64_t n1, const uint8_t *type, const
         g->n = n1 * batch;
         g->nnz = nnz1 * batch;
         g->weight_mode = (flags & GROOT_NORM_MEAN) ? WeightMode::Mean : WeightMode::Ones;
+        g->symmetric = (flags & GROOT_SYMMETRIC) != 0;
         g->rowptr.resize(g->n + 1);
         g->col.resize(g->nnz);
         g->pol.resize(g->nnz);
@@ -779,6 +781,54 @@ extern "C" groot_status groot_feature_placement(const groot_plan *plan, void *ar
     return GROOT_OK;
 }
 
+extern "C" groot_status groot_rows_over_degree(const groot_plan *plan, const float *Z_dev, float *out_dev, int32_t F,
+                                               void *hip_stream)
+{
+    const char *who = "groot_rows_over_degree: ";
+    if (!plan || !Z_dev || !out_dev) return fail(GROOT_EINVAL, std::string(who) + "NULL argument");
+    if (F < 4 || F > 512 || F % 4) return fail(GROOT_EINVAL, std::string(who) + "F must be a multiple of 4 in [4,512]");
+    if ((((uintptr_t)Z_dev) | ((uintptr_t)out_dev)) & 15) return fail(GROOT_EINVAL, std::string(who) + "pointers must be 16-byte aligned");
+    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "plan is not on the device (call groot_plan_upload)");
+    const int err = launch_rows_over_degree(plan->dev, Z_dev, out_dev, F, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string(who) + "launch failed: " + hip_error_text(err));
+    return GROOT_OK;
+}
+
+extern "C" groot_status groot_sage_layer_backward_data(const groot_plan *plan, const float *dZ_over_deg_dev,
+                                                       const float *WnT_dev, const float *WsT_dev, float *dX_dev,
+                                                       int32_t F_out, int32_t F_in, void *hip_stream)
+{
+    const char *who = "groot_sage_layer_backward_data: ";
+    if (!plan) return fail(GROOT_EINVAL, std::string(who) + "NULL plan");
+    if ((F_out != 64 && F_out != 32) || (F_in != 64 && F_in != 32 && F_in != 16))
+        return fail(GROOT_EINVAL, std::string(who) + "the layer's output width (the width of dZ) must be 32 or 64, its input width (of dX) 16, 32 or 64");
+    groot_status st = check_features("groot_sage_layer_backward_data", dZ_over_deg_dev, dX_dev, F_out);
+    if (st != GROOT_OK) return st;
+    if (!WnT_dev || !WsT_dev) return fail(GROOT_EINVAL, std::string(who) + "NULL weight pointer");
+    if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "plan is not on the device (call groot_plan_upload)");
+    if (!plan->g || !plan->g->symmetric || plan->g->weight_mode != WeightMode::Mean ||
+        plan->dev.weight_mode != (int)WeightMode::Mean)
+        return fail(GROOT_EINVAL, std::string(who) + "needs the plan of a graph built symmetric with mean weights (groot_graph_build with its default flags)");
+    if (F_out > plan->max_F) return fail(GROOT_EINVAL, std::string(who) + "the width of dZ exceeds the max_F given to groot_plan_upload");
+    if (plan->dev.n_cols != plan->dev.n)
+        return fail(GROOT_EINVAL, std::string(who) + "the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
+    const char *a = (const char *)dZ_over_deg_dev, *b = (const char *)dX_dev;
+    const int64_t z_bytes = plan->dev.n * (int64_t)F_out * 4, x_bytes = plan->dev.n * (int64_t)F_in * 4;
+    if (a < b + x_bytes && b < a + z_bytes) return fail(GROOT_EINVAL, std::string(who) + "dZ and dX overlap");
+    // unit-weight sums of the high-degree rows into the plan's side buffer, then the layer kernel in its gradient form
+    DevicePlan hd = plan->dev;
+    hd.chunks = plan->dev.chunks_rank;
+    hd.split_rows = plan->dev.split_rows_rank;
+    hd.weight_mode = (int)WeightMode::Ones;
+    int err = 0;
+    if (hd.n_chunks) err = launch_hd(hd, dZ_over_deg_dev, hd.hd_agg, F_out, hip_stream);
+    if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F_out, hip_stream);
+    if (!err) err = launch_sage_pipe(plan->dev, dZ_over_deg_dev, dX_dev, WnT_dev, WsT_dev, nullptr, 0, F_out, F_in,
+                                     tuning().sage_pieces.load(), 1, hip_stream);
+    if (err) return fail(GROOT_EHIP, std::string(who) + "launch failed: " + hip_error_text(err));
+    return GROOT_OK;
+}
+
 extern "C" groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_dev, const float *Wn_dev,
                                                     const float *Ws_dev, const float *bias_dev, int32_t relu,
                                                     float *H_dev, int32_t F_in, int32_t F_out, void *hip_stream)
@@ -809,7 +859,7 @@ extern "C" groot_status groot_sage_layer_forward_io(const groot_plan *plan, cons
         if (hd.n_chunks) err = launch_hd(hd, X_dev, hd.hd_agg, F_in, hip_stream);
         if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F_in, hip_stream);
         if (!err) err = launch_sage_pipe(plan->dev, X_dev, H_dev, Wn_dev, Ws_dev, bias_dev, relu ? 1 : 0, F_in, F_out,
-                                         tuning().sage_pieces.load(), hip_stream);
+                                         tuning().sage_pieces.load(), 0, hip_stream);
     } else {
         // the kernel for explicit weights (64 -> 64): high-degree sums go to H first and are picked up from there
         if (plan->dev.n_chunks) err = launch_hd(plan->dev, X_dev, H_dev, F_in, hip_stream);

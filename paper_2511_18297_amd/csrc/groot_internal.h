@@ -121,8 +121,10 @@ int launch_hd_finish(const DevicePlan &dp, float *Y, int32_t F, void *stream, co
 int launch_sage(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
                 int relu, void *stream);
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t F_in, int32_t F_out, int pieces, void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform
-                                                                                         // weights; pieces 3 (fp32 accuracy) or 2
+                     int relu, int32_t F_in, int32_t F_out, int pieces, int self_times_degree,
+                     void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform weights; pieces 3 (fp32 accuracy) or 2;
+                                      // self_times_degree: unit weights and the own-row operand times the row length (input gradient)
+int launch_rows_over_degree(const DevicePlan &dp, const float *Z, float *out, int32_t F, void *stream);   // out may be Z
 // Schedule of the high-degree rows built on the device (groot_hd_sched_device.hip): the pieces in execution order,
 // once with rows named by id and once by their place in the list of high-degree rows, and the split rows likewise.
 struct DeviceHdSchedule {

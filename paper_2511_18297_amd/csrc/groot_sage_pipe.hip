@@ -23,6 +23,12 @@
 // hi hi, hi mid and mid hi: what is dropped and what the two pieces do not represent stays below 3 x 2^-18 of
 // |x| |w| per product, a bar twice as wide as fp32's for half the matrix instructions.
 //
+// The layer's gradient with respect to its input runs through the same kernel (template argument SD).  With
+// dZ the gradient at the layer's pre-activation output, dX = A_hat^T (dZ Wn^T) + dZ Ws^T = (A_hat^T dZ) Wn^T + dZ Ws^T,
+// and for a symmetric adjacency with mean weights A_hat^T = A D^-1: the aggregation is the plain (unit-weight)
+// sum of the rows of dZ / deg, which the caller hands over, and the row's own part is that row times its length
+// again.  So SD is the layer with unit weights whose own-row operand is scaled by the row's stored length.
+//
 // High-degree rows are aggregated beforehand by the HD kernel into a side buffer of the plan, one row per
 // high-degree row in ascending order of their ids; a tile that contains one (or a row with more than kSpD entries,
 // or the ragged end) is redone by a plain path that picks those sums up (the row's place in the buffer by binary
@@ -104,7 +110,7 @@ __device__ __forceinline__ void sp_park(char *tile, int row, int k, v4f x)
 }
 
 // W: kOnes or kMean; D: gather slots per row on the pipelined path; P: bf16 pieces per fp32 operand, 3 or 2
-template <int W, int FI, int FO, int NW, int D, int P>
+template <int W, int FI, int FO, int NW, int D, int P, bool SD = false>
 __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW / 4, NW / 4))) void sage_pipe_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, char *H, int64_t zero_off, char *trash,
@@ -113,6 +119,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     const int32_t *__restrict__ hd_rows, int32_t n_hd, const char *__restrict__ hd_agg)
 {
     static_assert(P == 3 || P == 2, "pieces per operand");
+    static_assert(!SD || W == kOnes, "the own-row operand is scaled by the row length in the unit-weight form only");
     using C = SpCfg<FI, FO, NW>;
     constexpr int F = FI;
     constexpr int kSpD = D, kSpSlots = kSpRows * kSpD, kSpH = (kSpSlots + kWave - 1) / kWave;
@@ -208,6 +215,8 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
             }
         }
         if (W == kMean && l < kSpRows) s_inv[w][l] = row_weight<kMean>(len_a);
+        if (SD && l < kSpRows) s_inv[w][l] = (float)len_a;   // exact: a row that the slots serve has few entries, and
+                                                             // a longer one has fewer than 2^24 (the plain path redoes ragged tiles)
         sp_wave_sync();
         return fix_a;
     };
@@ -223,7 +232,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
         const int lr = grp * kSpRpg + g;
         int64_t row = tile * kSpRows + lr;
         row = row < n ? row : n - 1;                     // past the end: any valid row, the result is not kept
-        if (W == kMean) q.inv = s_inv[w][lr];
+        if (W == kMean || SD) q.inv = s_inv[w][lr];
 #pragma unroll
         for (int k = 0; k < kSpD; ++k) {
             if constexpr (W == kExplicit) {
@@ -271,7 +280,7 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
         for (int grp = 0; grp < kSpG; ++grp) {
             const v4f a = sum(rr[grp]);
             sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, 4 * f, a);
-            sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, F + 4 * f, rr[grp].self);
+            sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, F + 4 * f, SD ? rr[grp].self * rr[grp].inv : rr[grp].self);
             issue(rr[grp], tile + stride, grp);
         }
         if (fix_cur) {
@@ -298,6 +307,11 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
                     }
                 }
                 if (redo) sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, 4 * f, a);
+                if (SD && !full && row < n) {            // a ragged tile carries no row lengths: the own-row operand again
+                    const v4f own = *(const v4f *)(Xf + (row << kRowShift));
+                    sp_park<kSpBRow, kSpPlane, P>(a_tile, grp * kSpRpg + g, F + 4 * f,
+                                                  own * (float)(rowptr[row + 1] - rowptr[row]));
+                }
             }
         }
         sp_wave_sync();
@@ -365,14 +379,37 @@ __global__ __launch_bounds__(NW * kWave) __attribute__((amdgpu_waves_per_eu(NW /
     }
 }
 
+// out[i, :] = Z[i, :] / (stored length of row i), one lane per float4; out may be Z
+__global__ __launch_bounds__(kBlock) void rows_over_degree_kernel(const int64_t *__restrict__ rowptr, const v4f *Z, v4f *out,
+                                                                  int64_t n, int32_t F4)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n * F4) return;
+    const int64_t row = i / F4;
+    const float d = (float)(rowptr[row + 1] - rowptr[row]);
+    const v4f z = Z[i];
+    out[i] = d > 0.f ? (v4f){z[0] / d, z[1] / d, z[2] / d, z[3] / d} : (v4f){0.f, 0.f, 0.f, 0.f};
+}
+
+int launch_rows_over_degree(const DevicePlan &dp, const float *Z, float *out, int32_t F, void *stream)
+{
+    const int64_t total = dp.n * (int64_t)(F / 4), grid = (total + kBlock - 1) / kBlock;
+    if (total == 0) return 0;
+    if (!grid_ok(grid)) return (int)hipErrorInvalidConfiguration;
+    rows_over_degree_kernel<<<dim3((unsigned)grid), dim3(kBlock), 0, (hipStream_t)stream>>>(dp.rowptr, (const v4f *)Z, (v4f *)out,
+                                                                                          dp.n, F / 4);
+    return (int)hipGetLastError();
+}
+
 int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float *Wn, const float *Ws, const float *bias,
-                     int relu, int32_t FI, int32_t FO, int pieces, void *stream)
+                     int relu, int32_t FI, int32_t FO, int pieces, int self_times_degree, void *stream)
 {
     if (!weights_ok(dp) || !dp.zero_row || (FI != 64 && FI != 32) || (FO != 64 && FO != 32 && FO != 16) ||
         (pieces != 2 && pieces != 3))
         return (int)hipErrorInvalidValue;
     // row-uniform weights only: with explicit weights the slot table is twice as large and LDS does not hold it
     if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
+    const int wm = self_times_degree ? (int)kOnes : dp.weight_mode;
     if (dp.n_hd_rows && (!dp.hd_rows || !dp.hd_agg)) return (int)hipErrorInvalidValue;
     int dev = 0, cus = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -396,7 +433,7 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     char *trash = (char *)(dp.zero_row + kZeroRowFloats);
     hipStream_t st = (hipStream_t)stream;
 #define GROOT_SAGE_PIPE_LAUNCH(WM, FFI, FFO, DD, PP)                                                                   \
-    sage_pipe_kernel<WM, FFI, FFO, kNwRun, DD, PP><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(             \
+    sage_pipe_kernel<WM, FFI, FFO, kNwRun, DD, PP, SDV><<<dim3((unsigned)n_wg), dim3(kNwRun * kWave), 0, st>>>(        \
         dp.rowptr, col_arg, val_arg, (const char *)X, (char *)H, byte_distance(X, dp.zero_row), trash, Wn, Ws, bias, relu, \
         dp.n, dp.threshold, n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows,         \
         (const char *)dp.hd_agg)
@@ -410,12 +447,19 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
     if (FO == 64) { GROOT_SAGE_PIPE_D(WM, FFI, 64); }          \
     else if (FO == 32) { GROOT_SAGE_PIPE_D(WM, FFI, 32); }     \
     else { GROOT_SAGE_PIPE_D(WM, FFI, 16); }
-    if (FI == 64) {
-        if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 64); }
-        else { GROOT_SAGE_PIPE_FO(kOnes, 64); }
-    } else {
-        if (dp.weight_mode == kMean) { GROOT_SAGE_PIPE_FO(kMean, 32); }
+    if (self_times_degree) {
+        constexpr bool SDV = true;
+        if (FI == 64) { GROOT_SAGE_PIPE_FO(kOnes, 64); }
         else { GROOT_SAGE_PIPE_FO(kOnes, 32); }
+    } else {
+        constexpr bool SDV = false;
+        if (FI == 64) {
+            if (wm == kMean) { GROOT_SAGE_PIPE_FO(kMean, 64); }
+            else { GROOT_SAGE_PIPE_FO(kOnes, 64); }
+        } else {
+            if (wm == kMean) { GROOT_SAGE_PIPE_FO(kMean, 32); }
+            else { GROOT_SAGE_PIPE_FO(kOnes, 32); }
+        }
     }
 #undef GROOT_SAGE_PIPE_D
 #undef GROOT_SAGE_PIPE_P

@@ -18,7 +18,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import assert_close_to_oracle, ensure_built, tolerance
+from util import assert_close_to_oracle, ensure_built, layer_tolerance, tolerance
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
@@ -96,6 +96,40 @@ def test_config3_spmm_and_graphsage_forward(torch_cuda, one_copy):
     assert np.isfinite(e1).all() and (e1 <= tol1).all(), f"fused layer 1: max err/tol {np.max(e1 / tol1)}"
     e2 = np.abs(F2.cpu().numpy().astype(np.float64) - H2_ref)
     assert np.isfinite(e2).all() and (e2 <= tol2).all(), f"fused layer 2: max err/tol {np.max(e2 / tol2)}"
+
+
+def test_config3_fused_layer_backward_data(torch_cuda, one_copy):
+    """The fused layer's input gradient on the 1024-bit multiplier (8.4 M rows, the 2,048 primary inputs as
+    high-degree rows of 1,025 entries), every element against the fp64 definition, with three and with two bf16
+    pieces per operand."""
+    torch = torch_cuda
+    aig, rowptr, col, val = one_copy
+    n = aig.num_nodes
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F)
+    rng = np.random.default_rng(12)
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F, F)).astype(np.float32) for _ in range(2))
+    dZ = wl.uniform_features(5, 0, n, F, device="cuda")
+    dZ = dZ * (wl.uniform_features(6, 0, n, F, device="cuda") > -0.1)      # zeros as behind a ReLU
+    dZ_np = dZ.cpu().numpy()
+    scaled = torch.empty_like(dZ)
+    G.groot_rows_over_degree(plan, dZ, scaled)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    want, Tm, S = oracle.sage_layer_backward_data_f64(rowptr, col, val, dZ_np, Wn, Ws)
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale = np.abs(Tm) @ a64(Wn.T) + a64(dZ_np) @ a64(Ws.T)
+    try:
+        for pieces in (3, 2):
+            G.groot_set_tuning("sage_pieces", pieces)
+            dX = torch.full_like(dZ, float("nan"))
+            G.groot_sage_layer_backward_data(plan, scaled, dev(Wn.T), dev(Ws.T), dX)
+            torch.cuda.synchronize()
+            tol = layer_tolerance(S, scale, a64(Wn.T), pieces=pieces)
+            err = np.abs(dX.cpu().numpy().astype(np.float64) - want)
+            assert np.isfinite(err).all() and (err <= tol).all(), f"{pieces} pieces: max err/tol {np.max(err / tol)}"
+    finally:
+        G.groot_set_tuning("sage_pieces", 3)
 
 
 def _sample_rows(rng, n1, batch, n_random):

@@ -412,6 +412,76 @@ def test_fused_sage_layer_with_two_pieces_per_operand(torch_cuda, F_in, F_out, n
         G.groot_set_tuning("sage_pieces", 4)
 
 
+@pytest.mark.parametrize("F_out,F_in", [(64, 64), (32, 32), (64, 16), (32, 64), (64, 32), (32, 16)])
+@pytest.mark.parametrize("n_bits,batch,T", [(48, 2, 32), (17, 3, 5), (40, 1, 1), (3, 1, 32)])
+def test_fused_sage_layer_backward_data(torch_cuda, F_out, F_in, n_bits, batch, T):
+    """dX = A_hat^T (dZ Wn^T) + dZ Ws^T through the layer kernel's gradient form (unit-weight sums of the rows of
+    dZ / deg, own row scaled back by its length) against the fp64 definition: every pair of widths, high-degree
+    rows (summed by the HD kernel with unit weights), every row high-degree, a ragged last tile.  About half of
+    dZ is zero, as behind a ReLU.  groot_rows_over_degree is the division it claims to be, bit for bit."""
+    torch = torch_cuda
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    n = batch * aig.num_nodes
+    seed = 700 + n_bits + F_out + F_in
+    rng = np.random.default_rng(seed)
+    dZ = (wl.uniform_features_numpy(seed, 0, n, F_out) * (rng.random((n, F_out)) < 0.55)).astype(np.float32)
+    Wn, Ws = (rng.uniform(-0.125, 0.125, (F_in, F_out)).astype(np.float32) for _ in range(2))
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F_out)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    dZ_dev = dev(dZ)
+    scaled = torch.empty_like(dZ_dev)
+    G.groot_rows_over_degree(plan, dZ_dev, scaled)
+    deg = np.diff(rowptr).astype(np.float32)
+    assert np.array_equal(scaled.cpu().numpy(), dZ / deg[:, None])
+    G.groot_rows_over_degree(plan, dZ_dev, dZ_dev)            # in place
+    assert torch.equal(dZ_dev, scaled)
+    guard = 2
+    buf = torch.full((n + 2 * guard, F_in), float("nan"), dtype=torch.float32, device="cuda")
+    buf[:guard] = 777.0
+    buf[n + guard:] = 777.0
+    G.groot_sage_layer_backward_data(plan, scaled, dev(Wn.T), dev(Ws.T), buf[guard:n + guard])
+    torch.cuda.synchronize()
+    out = buf.cpu().numpy()
+    assert (out[:guard] == 777.0).all() and (out[n + guard:] == 777.0).all(), "wrote outside dX"
+    want, Tm, S = oracle.sage_layer_backward_data_f64(rowptr, col, val, dZ, Wn, Ws)
+    a64 = lambda a: np.abs(a.astype(np.float64))
+    scale = np.abs(Tm) @ a64(Wn.T) + a64(dZ) @ a64(Ws.T)
+    tol = layer_tolerance(S, scale, a64(Wn.T))
+    err = np.abs(out[guard:n + guard].astype(np.float64) - want)
+    assert np.isfinite(err).all()
+    assert (err <= tol).all(), f"max err/tol {np.max(err / tol)}"
+
+
+def test_fused_sage_layer_backward_data_errors(torch_cuda):
+    """The gradient form needs a symmetric graph with mean weights (it uses A_hat^T = A D^-1): a graph given as
+    CSR, the transposed graph and a graph built without normalisation are refused, and so are unsupported widths
+    and overlapping buffers."""
+    torch = torch_cuda
+    z = lambda *shape: torch.zeros(shape, device="cuda")
+    aig, g, (rowptr, col, val, pol) = _aig_case(17, 1)
+    n = aig.num_nodes
+    for bad in (G.groot_graph_from_csr(rowptr, col, val), G.groot_graph_transpose(g),
+                G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1, flags=G.GROOT_SYMMETRIC | G.GROOT_SELF_LOOPS)):
+        plan = G.groot_spmm_plan(bad, 32)
+        G.groot_plan_upload(plan, 64)
+        with pytest.raises(G.GrootError):
+            G.groot_sage_layer_backward_data(plan, z(n, 64), z(64, 64), z(64, 64), z(n, 64))
+    plan = G.groot_spmm_plan(g, 32)
+    with pytest.raises(G.GrootError):                       # not uploaded
+        G.groot_sage_layer_backward_data(plan, z(n, 64), z(64, 64), z(64, 64), z(n, 64))
+    G.groot_plan_upload(plan, 64)
+    with pytest.raises(G.GrootError):                       # dZ of width 16 is not built
+        G.groot_sage_layer_backward_data(plan, z(n, 16), z(16, 32), z(16, 32), z(n, 32))
+    with pytest.raises(G.GrootError):                       # dX of width 48 is not built
+        G.groot_sage_layer_backward_data(plan, z(n, 64), z(64, 48), z(64, 48), z(n, 48))
+    x = z(n, 64)
+    with pytest.raises(G.GrootError):                       # in place
+        G.groot_sage_layer_backward_data(plan, x, z(64, 64), z(64, 64), x)
+    with pytest.raises(ValueError):                         # the binding: weights of the wrong shape
+        G.groot_sage_layer_backward_data(plan, z(n, 64), z(32, 32), z(64, 32), z(n, 32))
+
+
 def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):
     """Feature rows scaled by powers of two from 2^-60 to 2^60 (each copy of the multiplier its own scale, so
     that neighbours share it): the bf16 pieces have the exponent range of fp32, so the error stays relative
