@@ -128,6 +128,24 @@ def test_training_through_the_library_and_the_regrowth_ablation():
         pred_full = model(Xb, plan_big).argmax(1)
     acc_full = float((pred_full == yb).float().mean())
 
+    # the gradient of a trained 32 -> 32 layer with respect to its input: the fused call against autograd through
+    # the library's aggregation and its transposed aggregation (the way the model above was trained)
+    plan_big_t = G.groot_spmm_plan(G.groot_graph_transpose(g_big), T)
+    G.groot_plan_upload(plan_big_t, HIDDEN)
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    h_in = torch.rand((n, HIDDEN), generator=gen, device="cuda").requires_grad_(True)
+    R = torch.rand((n, HIDDEN), generator=gen, device="cuda") - 0.5
+    wn1, ws1, b1 = model.wn[1].detach(), model.ws[1].detach(), model.b[1].detach()
+    Zl = _aggregate(torch, h_in, plan_big, plan_big_t) @ wn1 + h_in @ ws1 + b1
+    want_dx = torch.autograd.grad((torch.relu(Zl) * R).sum(), h_in)[0]
+    dZ = (R * (Zl.detach() > 0)).contiguous()
+    scaled = torch.empty_like(dZ)
+    G.groot_rows_over_degree(plan_big, dZ, scaled)
+    got_dx = torch.empty_like(dZ)
+    G.groot_sage_layer_backward_data(plan_big, scaled, wn1.t().contiguous(), ws1.t().contiguous(), got_dx)
+    torch.cuda.synchronize()
+    assert float((got_dx - want_dx).abs().max()) <= 1e-5 * float(want_dx.abs().max())
+
     # the two 32 -> 32 layers through the fused layer kernel give the same classification
     with torch.no_grad():
         h = Xb
