@@ -230,6 +230,18 @@ def sage_layer_backward_data_f64(rowptr, col, val, dZ, Wn, Ws):
     return dX, T, S
 
 
+def sage_layer_backward_weights_f64(rowptr, col, val, X, dZ):
+    """Gradients of a GraphSAGE-mean layer with respect to its two weight matrices, in fp64: for
+    Z = (A_hat X) Wn + X Ws + b and dZ the gradient of the loss at Z, dWn = (A_hat X)^T dZ and dWs = X^T dZ
+    (chain rule; Section "GNN and Edge Re-growth After Partition": the model is trained).  Also returns the
+    sums of absolute terms of the two products, with the aggregation's own sum of absolute terms in the first
+    (for the error scale).  Pinned by automatic differentiation of the dense layer on the 18- and 51-node
+    multipliers and by the identity <dWn, V> + <dWs, U> = <dZ, (A_hat X) V + X U>."""
+    A, S = spmm_f64(rowptr, col, val, X)
+    X64, dZ64 = np.asarray(X, dtype=np.float64), np.asarray(dZ, dtype=np.float64)
+    return A.T @ dZ64, X64.T @ dZ64, S.T @ np.abs(dZ64), np.abs(X64).T @ np.abs(dZ64)
+
+
 def sage_forward_f64(rowptr, col, val, X, W1n, W1s, b1, W2n, W2s, b2):
     """Two GraphSAGE-mean layers (Section "GNN and Edge Re-growth After
     Partition": the layer aggregates neighbour features, then transforms):

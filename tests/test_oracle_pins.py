@@ -441,6 +441,33 @@ def test_sage_layer_backward_data_equals_autograd_of_the_dense_layer(n):
     assert abs(float((JV * dZ.astype(np.float64)).sum()) - float((dX * V.astype(np.float64)).sum())) <= 1e-12
 
 
+@pytest.mark.parametrize("n", [2, 3])
+def test_sage_layer_backward_weights_equals_autograd_of_the_dense_layer(n):
+    """The oracle's weight gradients of the layer against automatic differentiation of the dense layer (dense
+    adjacency written from the fanin records) for the same dZ, and through the identity that ties them to the
+    forward layer's value for other weights."""
+    import torch
+    csr, A_hat, X, Wn, Ws, b = _layer_inputs(n, 8, 47)
+    N, F = X.shape
+    rng = np.random.default_rng(17 + n)
+    dZ = (rng.uniform(-1, 1, (N, F)) * (rng.random((N, F)) < 0.6)).astype(np.float32)
+    A_t, X_t, b_t = (torch.from_numpy(np.asarray(a, dtype=np.float64)) for a in (A_hat, X, b))
+    Wn_t = torch.from_numpy(Wn.astype(np.float64)).requires_grad_(True)
+    Ws_t = torch.from_numpy(Ws.astype(np.float64)).requires_grad_(True)
+    Z_t = A_t @ X_t @ Wn_t + X_t @ Ws_t + b_t
+    (Z_t * torch.from_numpy(dZ.astype(np.float64))).sum().backward()
+    dWn, dWs, Sn, Ss = oracle.sage_layer_backward_weights_f64(*csr, X, dZ)
+    assert np.allclose(dWn, Wn_t.grad.numpy(), rtol=0, atol=1e-13)
+    assert np.allclose(dWs, Ws_t.grad.numpy(), rtol=0, atol=1e-13)
+    X64, dZ64 = X.astype(np.float64), dZ.astype(np.float64)
+    assert np.allclose(Sn, (A_hat @ np.abs(X64)).T @ np.abs(dZ64), rtol=0, atol=1e-13)
+    assert np.allclose(Ss, np.abs(X64).T @ np.abs(dZ64), rtol=0, atol=1e-13)
+    V, U = (rng.uniform(-1, 1, (F, F)).astype(np.float32) for _ in range(2))
+    H, _, _ = oracle.sage_layer_f64(*csr, X, V, U, None, False)
+    lhs = float((dWn * V.astype(np.float64)).sum() + (dWs * U.astype(np.float64)).sum())
+    assert abs(lhs - float((H * dZ64).sum())) <= 1e-12
+
+
 def test_sage_forward_is_two_layers():
     """The two-layer forward is the layer applied twice: ReLU and rounding to fp32 between the layers, none after."""
     csr, _, X, W1n, W1s, b1 = _layer_inputs(4, 8, 61)
