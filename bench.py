@@ -295,6 +295,29 @@ def sage_layer_bench(args, G, torch, np, aig, g, T, plan, X, H, n, nnz, F, batch
         backward.update(unfused_ms_per_step=round(ms_unfused_backward, 4),
                         speedup_vs_unfused=round(ms_unfused_backward / ms_backward, 3), max_abs_diff_vs_unfused=worst_b)
         del G1, out, plan_t
+    # The gradients of the two weight matrices, dWn = (A_hat X)^T dZ and dWs = X^T dZ (H plays dZ), in one pass
+    # against the unfused form: the library's SpMM, then two products with N as the contraction length.
+    torch.cuda.empty_cache()
+    ws = torch.empty((G.groot_sage_layer_backward_weights_workspace(plan, F) // 4,), dtype=torch.float32, device="cuda")
+    dW = torch.empty((2, F, F), dtype=torch.float32, device="cuda")
+
+    def fused_wgrad():
+        G.groot_sage_layer_backward_weights(plan, X, H, dW[0], dW[1], ws, F)
+
+    def unfused_wgrad():
+        G.groot_spmm_execute(plan, X, Y, F)
+        return torch.mm(Y.t(), H), torch.mm(X.t(), H)
+
+    ms_wgrad = timed(fused_wgrad, args.steps, args.warmup)
+    ms_unfused_wgrad = timed(unfused_wgrad, 2, 1)
+    ref_n, ref_s = unfused_wgrad()
+    fused_wgrad()
+    torch.cuda.synchronize()
+    weights = {"ms_per_step": round(ms_wgrad, 4), "unfused_ms_per_step": round(ms_unfused_wgrad, 4),
+               "speedup_vs_unfused": round(ms_unfused_wgrad / ms_wgrad, 3),
+               "max_rel_diff_vs_unfused": float(max((dW[0] - ref_n).abs().max() / ref_n.abs().max(),
+                                                    (dW[1] - ref_s).abs().max() / ref_s.abs().max()))}
+
     flops = 2.0 * nnz * F + 2.0 * n * (2 * F) * F
     tflops = flops / (ms_fused * 1e-3) / 1e12
     # The dense products run as bf16 piece products (a sixteenth of the fp32 matrix instruction's time per
@@ -316,7 +339,7 @@ def sage_layer_bench(args, G, torch, np, aig, g, T, plan, X, H, n, nnz, F, batch
         "bf16_pieces_per_operand": next((int(t.partition("=")[2]) for t in args.tune if t.startswith("sage_pieces=")), 3),
         "fp32_equivalent_tflops": round(tflops, 2), "fp32_mfma_peak_tflops": 157.3,
         "unfused_ms_per_step": round(ms_unfused, 4), "speedup_vs_unfused": round(ms_unfused / ms_fused, 3),
-        "max_abs_diff_vs_unfused": worst, "backward_data": backward, "placement": placement, "device": props.name}))
+        "max_abs_diff_vs_unfused": worst, "backward_data": backward, "backward_weights": weights, "placement": placement, "device": props.name}))
 
 
 def place_features(G, torch, wl, plan, seed, n, F, tries, fixed=None):

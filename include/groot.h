@@ -269,6 +269,35 @@ groot_status groot_sage_layer_backward_data(const groot_plan *plan, const float 
                                             int32_t F_out, int32_t F_in, void *hip_stream);
 groot_status groot_rows_over_degree(const groot_plan *plan, const float *Z_dev, float *out_dev, int32_t F,
                                     void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * groot_sage_layer_backward_weights -- the fused layer's gradients with respect
+ * to its two weight matrices, for training (Section "GNN and Edge Re-growth
+ * After Partition").  With Z = (A_hat X) Wn + X Ws + b and dZ the gradient of
+ * the loss at Z,
+ *     dWn = (A_hat X)^T dZ,   dWs = X^T dZ,
+ * both in one pass over X and dZ with the aggregation kept on chip (A_hat X is
+ * never written to memory); fp32 accuracy per product from bf16 piece products
+ * as in the forward layer ("sage_pieces"), fp32 sums over the rows that one
+ * wavefront sweeps (N / 1024 of them on an MI355X), fp64 across wavefronts, in
+ * a fixed order: the same bits on every run.  The bias gradient is the column
+ * sum of dZ and is left to the caller.
+ * X_dev, dZ_dev (device): row-major [N, F] fp32, F = 32 or 64 (a narrower
+ * layer: pad with zero columns); dWn_dev, dWs_dev (device): row-major [F, F]
+ * fp32, fully overwritten; workspace_dev (device, 16-byte aligned): at least
+ * the number of bytes that groot_sage_layer_backward_weights_workspace reports
+ * for F (2 F^2 floats per wavefront of the launch: 32 MiB at F = 64 on an
+ * MI355X), contents overwritten, owned by the caller.  The plan must be
+ * uploaded with max_F >= F and have row-uniform weights.  Only enqueues on
+ * hip_stream, allocates nothing; one call per plan in flight (the aggregated
+ * high-degree rows pass through a buffer of the plan).  Errors: EINVAL (NULL,
+ * alignment, F, plan not uploaded, explicit weights, workspace too small),
+ * EHIP.
+ * ------------------------------------------------------------------------- */
+groot_status groot_sage_layer_backward_weights_workspace(const groot_plan *plan, int32_t F, size_t *bytes);
+groot_status groot_sage_layer_backward_weights(const groot_plan *plan, const float *X_dev, const float *dZ_dev,
+                                               float *dWn_dev, float *dWs_dev, int32_t F, void *workspace_dev,
+                                               size_t workspace_bytes, void *hip_stream);
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------

@@ -24,7 +24,7 @@ GROOT_PHASE_LD, GROOT_PHASE_HD, GROOT_PHASE_FINISH, GROOT_PHASE_ALL = 1, 2, 4, 7
 EXPORTS = [
     "groot_graph_build", "groot_graph_from_csr", "groot_graph_transpose", "groot_graph_view", "groot_graph_free",
     "groot_spmm_plan", "groot_plan_view", "groot_plan_upload", "groot_spmm_execute",
-    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_sage_layer_backward_data", "groot_rows_over_degree", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_feature_placement", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
+    "groot_spmm_execute_phases", "groot_spmm_execute_rows", "groot_plan_use_global_columns", "groot_sage_layer_forward", "groot_sage_layer_forward_io", "groot_sage_layer_backward_data", "groot_rows_over_degree", "groot_sage_layer_backward_weights", "groot_sage_layer_backward_weights_workspace", "groot_plan_lists_device", "groot_plan_lists_device_static", "groot_plan_query", "groot_plan_hd_pieces", "groot_feature_placement", "groot_plan_free", "groot_partition_regrow", "groot_parts_view",
     "groot_parts_count", "groot_parts_free", "groot_partition_regrow_device", "groot_dev_part_view",
     "groot_dev_part_plan", "groot_dev_part_download", "groot_dev_part_free", "groot_rows_gather", "groot_rows_scatter",
     "groot_set_tuning", "groot_last_error",
@@ -66,6 +66,8 @@ _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i
 _lib.groot_sage_layer_forward_io.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp]
 _lib.groot_sage_layer_backward_data.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]
 _lib.groot_rows_over_degree.argtypes = [_vp, _vp, _vp, _i32, _vp]
+_lib.groot_sage_layer_backward_weights_workspace.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_size_t)]
+_lib.groot_sage_layer_backward_weights.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_size_t, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_lists_device_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
@@ -361,6 +363,26 @@ def groot_sage_layer_backward_data(pl: Plan, dZ_over_deg, WnT, WsT, dX, F_out: i
     _check(_lib.groot_sage_layer_backward_data(pl.handle, _features(dZ_over_deg, "dZ_over_deg", n, F_out),
                                                _features(WnT, "WnT", F_out, F_in), _features(WsT, "WsT", F_out, F_in),
                                                _features(dX, "dX", n, F_in), F_out, F_in, _stream_handle(stream)))
+
+
+def groot_sage_layer_backward_weights_workspace(pl: Plan, F: int) -> int:
+    """Bytes of device workspace that groot_sage_layer_backward_weights needs for width F."""
+    b = ctypes.c_size_t(0)
+    _check(_lib.groot_sage_layer_backward_weights_workspace(pl.handle, F, ctypes.byref(b)))
+    return b.value
+
+
+def groot_sage_layer_backward_weights(pl: Plan, X, dZ, dWn, dWs, workspace, F: int = None, stream=None) -> None:
+    """X and dZ [N, F], dWn and dWs [F, F] (overwritten); workspace: a contiguous device tensor of at least
+    groot_sage_layer_backward_weights_workspace(pl, F) bytes."""
+    F = X.shape[1] if F is None else F
+    n = _plan_rows(pl)
+    if not workspace.is_contiguous():
+        raise ValueError("workspace must be contiguous")
+    _check(_lib.groot_sage_layer_backward_weights(pl.handle, _features(X, "X", n, F), _features(dZ, "dZ", n, F),
+                                                  _features(dWn, "dWn", F, F), _features(dWs, "dWs", F, F), F,
+                                                  _dev_ptr(workspace, "workspace"),
+                                                  workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 
 def groot_rows_over_degree(pl: Plan, Z, out, F: int = None, stream=None) -> None:

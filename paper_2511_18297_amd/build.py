@@ -13,7 +13,7 @@ SOURCES = [os.path.join(CSRC, "groot_host.cpp"), os.path.join(CSRC, "groot_kerne
            os.path.join(CSRC, "groot_sage.hip"), os.path.join(CSRC, "groot_plan_device.hip"),
            os.path.join(CSRC, "groot_ld_pipe.hip"), os.path.join(CSRC, "groot_regrow_device.hip"),
            os.path.join(CSRC, "groot_sage_pipe.hip"), os.path.join(CSRC, "groot_compress.hip"),
-           os.path.join(CSRC, "groot_hd_sched_device.hip")]
+           os.path.join(CSRC, "groot_hd_sched_device.hip"), os.path.join(CSRC, "groot_sage_wgrad.hip")]
 HEADERS = [os.path.join(CSRC, "groot_internal.h"), os.path.join(CSRC, "groot_device.h"),
            os.path.join(ROOT, "include", "groot.h")]
 

@@ -18,7 +18,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import assert_close_to_oracle, ensure_built, layer_tolerance, tolerance
+from util import assert_close_to_oracle, ensure_built, layer_tolerance, tolerance, wgrad_tolerance
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1500)]
 
@@ -128,6 +128,39 @@ def test_config3_fused_layer_backward_data(torch_cuda, one_copy):
             tol = layer_tolerance(S, scale, a64(Wn.T), pieces=pieces)
             err = np.abs(dX.cpu().numpy().astype(np.float64) - want)
             assert np.isfinite(err).all() and (err <= tol).all(), f"{pieces} pieces: max err/tol {np.max(err / tol)}"
+    finally:
+        G.groot_set_tuning("sage_pieces", 3)
+
+
+def test_config3_fused_layer_backward_weights(torch_cuda, one_copy):
+    """The fused layer's weight gradients on the 1024-bit multiplier (8.4 M rows: 8,192 rows per wavefront added in
+    fp32) against the fp64 definition."""
+    torch = torch_cuda
+    aig, rowptr, col, val = one_copy
+    n = aig.num_nodes
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F)
+    X = wl.uniform_features(8, 0, n, F, device="cuda")
+    dZ = wl.uniform_features(9, 0, n, F, device="cuda")
+    dZ = dZ * (wl.uniform_features(10, 0, n, F, device="cuda") > -0.1)      # zeros as behind a ReLU
+    X_np, dZ_np = X.cpu().numpy(), dZ.cpu().numpy()
+    dWn, dWs, Sn, Ss = oracle.sage_layer_backward_weights_f64(rowptr, col, val, X_np, dZ_np)
+    ws = torch.empty((G.groot_sage_layer_backward_weights_workspace(plan, F) // 4,), dtype=torch.float32, device="cuda")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count // 8 * 8
+    rows_per_wavefront = 16 * -(-(-(-(-(-n // 16)) // 8)) // (cus // 8 * 4))
+    try:
+        for pieces in (3, 2):
+            G.groot_set_tuning("sage_pieces", pieces)
+            out = torch.full((2, F, F), float("nan"), dtype=torch.float32, device="cuda")
+            G.groot_sage_layer_backward_weights(plan, X, dZ, out[0], out[1], ws, F)
+            torch.cuda.synchronize()
+            got = out.cpu().numpy().astype(np.float64)
+            tol_n, tol_s = wgrad_tolerance(Sn, Ss, np.abs(dZ_np.astype(np.float64)).sum(axis=0), rows_per_wavefront, pieces)
+            en, es = np.abs(got[0] - dWn), np.abs(got[1] - dWs)
+            print(f"{pieces} pieces: max err/tol dWn {np.max(en / tol_n):.2e} dWs {np.max(es / tol_s):.2e}; "
+                  f"max rel err {np.max(en) / np.abs(dWn).max():.2e} {np.max(es) / np.abs(dWs).max():.2e}", flush=True)
+            assert np.isfinite(got).all() and (en <= tol_n).all() and (es <= tol_s).all()
     finally:
         G.groot_set_tuning("sage_pieces", 3)
 

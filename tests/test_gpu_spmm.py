@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 import workloads as wl
-from util import assert_close_to_oracle, ensure_built, layer_tolerance
+from util import wgrad_tolerance, assert_close_to_oracle, ensure_built, layer_tolerance
 
 pytestmark = pytest.mark.gpu
 
@@ -480,6 +480,86 @@ def test_fused_sage_layer_backward_data_errors(torch_cuda):
         G.groot_sage_layer_backward_data(plan, x, z(64, 64), z(64, 64), x)
     with pytest.raises(ValueError):                         # the binding: weights of the wrong shape
         G.groot_sage_layer_backward_data(plan, z(n, 64), z(32, 32), z(64, 32), z(n, 32))
+
+
+def _wgrad_check(torch, g, rowptr, col, val, T, n, seed, F, pieces=3):
+    rng = np.random.default_rng(seed)
+    X = wl.uniform_features_numpy(seed, 0, n, F)
+    dZ = (wl.uniform_features_numpy(seed + 1, 0, n, F) * (rng.random((n, F)) < 0.55)).astype(np.float32)
+    plan = G.groot_spmm_plan(g, T)
+    G.groot_plan_upload(plan, F)
+    need = G.groot_sage_layer_backward_weights_workspace(plan, F)
+    ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    ws[need // 4:] = 777.0
+    out = torch.full((2, F, F), float("nan"), dtype=torch.float32, device="cuda")
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Xd, Zd = dev(X), dev(dZ)
+    G.groot_sage_layer_backward_weights(plan, Xd, Zd, out[0], out[1], ws, F)
+    torch.cuda.synchronize()
+    assert bool((ws[need // 4:] == 777.0).all()), "wrote past the workspace it asked for"
+    got = out.cpu().numpy().astype(np.float64)
+    again = torch.full_like(out, float("nan"))
+    G.groot_sage_layer_backward_weights(plan, Xd, Zd, again[0], again[1], ws, F)
+    torch.cuda.synchronize()
+    assert torch.equal(out, again), "no atomics: the same bits on every run"
+    dWn, dWs, Sn, Ss = oracle.sage_layer_backward_weights_f64(rowptr, col, val, X, dZ)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count // 8 * 8
+    tiles_per_part = -(-(-(-n // 16)) // 8)
+    rows_per_wavefront = 16 * -(-tiles_per_part // (cus // 8 * 4))
+    tol_n, tol_s = wgrad_tolerance(Sn, Ss, np.abs(dZ.astype(np.float64)).sum(axis=0), rows_per_wavefront, pieces)
+    assert np.isfinite(got).all()
+    en, es = np.abs(got[0] - dWn), np.abs(got[1] - dWs)
+    assert (en <= tol_n).all(), f"dWn: max err/tol {np.max(en / tol_n)}"
+    assert (es <= tol_s).all(), f"dWs: max err/tol {np.max(es / tol_s)}"
+    return en / tol_n, es / tol_s
+
+
+@pytest.mark.parametrize("F", [64, 32])
+@pytest.mark.parametrize("n_bits,batch,T", [(48, 2, 32), (17, 3, 5), (40, 1, 1), (3, 1, 32), (64, 1, 32)])
+def test_fused_sage_layer_backward_weights(torch_cuda, F, n_bits, batch, T):
+    """dWn = (A_hat X)^T dZ and dWs = X^T dZ in one pass against the fp64 definition: both widths, high-degree rows
+    (their sums come from the HD kernel), every row high-degree, fewer rows than one tile, a ragged last tile;
+    twice, bit for bit the same; nothing written past the workspace."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    _wgrad_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 800 + n_bits + F, F)
+
+
+def test_fused_sage_layer_backward_weights_other_graphs_and_errors(torch_cuda):
+    """Unit weights (a graph built without normalisation), a graph given as CSR whose weights are 1 / row length
+    (heavy rows split into pieces), two pieces per operand; explicit weights, a short workspace, F = 16 and a plan
+    that is not uploaded are refused."""
+    torch = torch_cuda
+    aig = wl.csa_multiplier_aig(24)
+    flags = G.GROOT_SYMMETRIC | G.GROOT_SELF_LOOPS
+    g1 = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 2, flags=flags)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 2, flags=flags)
+    _wgrad_check(torch, g1, rowptr, col, val, 32, 2 * aig.num_nodes, 31, 64)
+    s = wl.stress_graph(12, 1 << 14, window=512, dmin=64, dmax=2048)
+    gs = G.groot_graph_from_csr(s.rowptr, s.col, s.val)
+    _wgrad_check(torch, gs, s.rowptr, s.col, s.val, 32, s.n, 32, 32)
+    aig2, g2, (rowptr2, col2, val2, _) = _aig_case(48, 2)
+    G.groot_set_tuning("sage_pieces", 2)
+    try:
+        _wgrad_check(torch, g2, rowptr2, col2, val2, 32, 2 * aig2.num_nodes, 33, 64, pieces=2)
+    finally:
+        G.groot_set_tuning("sage_pieces", 3)
+    z = lambda *shape: torch.zeros(shape, device="cuda")
+    n = 2 * aig2.num_nodes
+    plan = G.groot_spmm_plan(g2, 32)
+    with pytest.raises(G.GrootError):                       # not uploaded
+        G.groot_sage_layer_backward_weights(plan, z(n, 64), z(n, 64), z(64, 64), z(64, 64), z(1 << 24), 64)
+    G.groot_plan_upload(plan, 64)
+    need = G.groot_sage_layer_backward_weights_workspace(plan, 64)
+    with pytest.raises(G.GrootError):                       # workspace one float short
+        G.groot_sage_layer_backward_weights(plan, z(n, 64), z(n, 64), z(64, 64), z(64, 64), z(need // 4 - 1), 64)
+    with pytest.raises(G.GrootError):                       # width 16 is not built
+        G.groot_sage_layer_backward_weights(plan, z(n, 16), z(n, 16), z(16, 16), z(16, 16), z(need // 4), 16)
+    with pytest.raises(G.GrootError):
+        G.groot_sage_layer_backward_weights_workspace(plan, 48)
+    plan_t = G.groot_spmm_plan(G.groot_graph_transpose(g2), 32)     # explicit weights
+    G.groot_plan_upload(plan_t, 64)
+    with pytest.raises(G.GrootError):
+        G.groot_sage_layer_backward_weights(plan_t, z(n, 64), z(n, 64), z(64, 64), z(64, 64), z(need // 4), 64)
 
 
 def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):

@@ -42,3 +42,15 @@ def layer_tolerance(S, scale, absWn, floor=1e-6, pieces=3):
     2^-18, and the product of the two second pieces, at most 2^-18, is dropped), which adds that much of scale."""
     dense = 1e-5 + (3 * 2.0 ** -18 if pieces == 2 else 0.0)
     return (1e-5 * S + floor) @ absWn + dense * scale + floor
+
+
+def wgrad_tolerance(Sn, Ss, dz_abs_colsum, rows_per_wavefront, pieces=3, floor=1e-6):
+    """Accepted deviation of the fused layer's weight gradients dWn = (A_hat X)^T dZ and dWs = X^T dZ from fp64,
+    element by element.  Sn = S^T |dZ| with S the aggregation's own sums of absolute terms, Ss = |X|^T |dZ|.  The
+    aggregation's bar (1e-5 S + 1e-6 per element of A_hat X) reaches dWn through |dZ|; each product is exact to
+    2^-23 of itself (three bf16 pieces per operand; two pieces: 3 * 2^-18); a wavefront adds the products of the
+    rows it sweeps in fp32, 16 at a time in the matrix instruction and tile after tile into its accumulator,
+    at most (rows + 16) roundings of 2^-24 of the sum of magnitudes; the sums of the wavefronts meet in fp64 and
+    the result is rounded to fp32 once."""
+    gamma = (rows_per_wavefront + 18) * 2.0 ** -24 + (3 * 2.0 ** -18 if pieces == 2 else 2.0 ** -23)
+    return (1e-5 + gamma) * Sn + 1e-6 * dz_abs_colsum[None, :] + floor, gamma * Ss + floor
