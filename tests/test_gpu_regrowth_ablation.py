@@ -135,9 +135,10 @@ def test_training_through_the_library_and_the_regrowth_ablation():
     gen = torch.Generator(device="cuda").manual_seed(3)
     h_in = torch.rand((n, HIDDEN), generator=gen, device="cuda").requires_grad_(True)
     R = torch.rand((n, HIDDEN), generator=gen, device="cuda") - 0.5
-    wn1, ws1, b1 = model.wn[1].detach(), model.ws[1].detach(), model.b[1].detach()
+    wn1, ws1, b1 = (p.detach().clone().requires_grad_(True) for p in (model.wn[1], model.ws[1], model.b[1]))
     Zl = _aggregate(torch, h_in, plan_big, plan_big_t) @ wn1 + h_in @ ws1 + b1
-    want_dx = torch.autograd.grad((torch.relu(Zl) * R).sum(), h_in)[0]
+    want_dx, want_dwn, want_dws = torch.autograd.grad((torch.relu(Zl) * R).sum(), (h_in, wn1, ws1))
+    wn1, ws1 = wn1.detach(), ws1.detach()
     dZ = (R * (Zl.detach() > 0)).contiguous()
     scaled = torch.empty_like(dZ)
     G.groot_rows_over_degree(plan_big, dZ, scaled)
@@ -145,6 +146,13 @@ def test_training_through_the_library_and_the_regrowth_ablation():
     G.groot_sage_layer_backward_data(plan_big, scaled, wn1.t().contiguous(), ws1.t().contiguous(), got_dx)
     torch.cuda.synchronize()
     assert float((got_dx - want_dx).abs().max()) <= 1e-5 * float(want_dx.abs().max())
+    # ... and with respect to its weights: one fused pass against autograd's two products over all rows
+    ws_buf = torch.empty((G.groot_sage_layer_backward_weights_workspace(plan_big, HIDDEN) // 4,), device="cuda")
+    got_dw = torch.empty((2, HIDDEN, HIDDEN), device="cuda")
+    G.groot_sage_layer_backward_weights(plan_big, h_in.detach(), dZ, got_dw[0], got_dw[1], ws_buf)
+    torch.cuda.synchronize()
+    assert float((got_dw[0] - want_dwn).abs().max()) <= 2e-5 * float(want_dwn.abs().max())
+    assert float((got_dw[1] - want_dws).abs().max()) <= 2e-5 * float(want_dws.abs().max())
 
     # the two 32 -> 32 layers through the fused layer kernel give the same classification
     with torch.no_grad():
