@@ -30,7 +30,9 @@
 namespace groot {
 
 constexpr int kWgRows = 16;                  // rows per tile: the contraction length of one matrix instruction
-constexpr int kWgWaves = 4;                  // one wavefront per SIMD: its accumulators take 128 registers at F = 64
+// wavefronts per workgroup (one workgroup per CU): one per SIMD at F = 64, where the accumulators alone take 128
+// registers; two per SIMD at F = 32 (32 accumulator registers), so that one's vector work overlaps the other's matrix work
+constexpr int wg_waves(int F) { return F == 64 ? 4 : 8; }
 constexpr int kWgTRow = kWgRows * 2 + 8;     // bytes per column of a transposed bf16 plane (8 B of padding)
 
 typedef float wg_f2 __attribute__((ext_vector_type(2)));
@@ -87,7 +89,7 @@ __device__ __forceinline__ void wg_park(char *planes, int c0, int g, const v4f (
 
 // W: kOnes or kMean; F: width of X and of dZ; D: gather slots per row on the pipelined path; P: bf16 pieces per operand
 template <int W, int F, int D, int P>
-__global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_eu(1, 1))) void sage_wgrad_kernel(
+__global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_per_eu(wg_waves(F) / 4, wg_waves(F) / 4))) void sage_wgrad_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, const char *__restrict__ dZ, int64_t zero_off, int64_t n, int32_t T, int64_t n_tiles,
     int64_t tiles_per_part, int64_t waves_per_part, int32_t parts, const int32_t *__restrict__ hd_rows, int32_t n_hd,
@@ -96,6 +98,7 @@ __global__ __launch_bounds__(kWgWaves * kWave) __attribute__((amdgpu_waves_per_e
     static_assert(F == 64 || F == 32, "width");
     static_assert(P == 3 || P == 2, "pieces per operand");
     static_assert(W == kOnes || W == kMean, "row-uniform weights");
+    constexpr int kWgWaves = wg_waves(F);
     constexpr int kL = F / 4, kRpg = kWave / kL, kG = kWgRows / kRpg, kRowShift = F == 64 ? 8 : 7;
     constexpr int kM = 2 * F, kMb = kM / 16, kNb = F / 16;
     constexpr int kPlaneA = kM * kWgTRow, kPlaneB = F * kWgTRow;
@@ -305,7 +308,7 @@ static int64_t wgrad_workgroups()
 size_t sage_wgrad_workspace_bytes(int32_t F)
 {
     const int64_t n_wg = wgrad_workgroups();
-    return n_wg < 0 ? 0 : (size_t)n_wg * kWgWaves * 2 * (size_t)F * (size_t)F * sizeof(float);
+    return n_wg < 0 ? 0 : (size_t)n_wg * wg_waves(F) * 2 * (size_t)F * (size_t)F * sizeof(float);
 }
 
 int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, float *dWn, float *dWs, int32_t F, int pieces,
@@ -320,14 +323,14 @@ int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, flo
     const int64_t n_tiles = (dp.n + kWgRows - 1) / kWgRows;
     const int32_t parts = dp.xcd_remap ? kXcds : 1;
     const int64_t tiles_per_part = (n_tiles + parts - 1) / parts;
-    const int64_t waves_per_part = n_wg / parts * kWgWaves;
+    const int64_t waves_per_part = n_wg / parts * wg_waves(F);
     if (!grid_ok(n_wg) || n_tiles <= 0) return (int)hipErrorInvalidConfiguration;
     // the kernel reads entry 0 of the index array from idle lanes: give it something to read when the matrix has no entries
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     hipStream_t st = (hipStream_t)stream;
 #define GROOT_WGRAD_LAUNCH(WM, FF, DD, PP)                                                                               \
-    sage_wgrad_kernel<WM, FF, DD, PP><<<dim3((unsigned)n_wg), dim3(kWgWaves * kWave), 0, st>>>(                          \
+    sage_wgrad_kernel<WM, FF, DD, PP><<<dim3((unsigned)n_wg), dim3(wg_waves(FF) * kWave), 0, st>>>(                          \
         dp.rowptr, col_arg, val_arg, (const char *)X, (const char *)dZ, byte_distance(X, dp.zero_row), dp.n, dp.threshold, \
         n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows, (const char *)dp.hd_agg,    \
         (float *)workspace)
@@ -351,7 +354,7 @@ int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, flo
     if (err != hipSuccess) return (int)err;
     const int32_t count = 2 * F * F;
     sage_wgrad_reduce_kernel<<<dim3((unsigned)((count + kBlock - 1) / kBlock)), dim3(kBlock), 0, st>>>(
-        (const float *)workspace, n_wg * kWgWaves, F, dWn, dWs);
+        (const float *)workspace, n_wg * wg_waves(F), F, dWn, dWs);
     return (int)hipGetLastError();
 }
 

@@ -505,7 +505,7 @@ def _wgrad_check(torch, g, rowptr, col, val, T, n, seed, F, pieces=3):
     dWn, dWs, Sn, Ss = oracle.sage_layer_backward_weights_f64(rowptr, col, val, X, dZ)
     cus = torch.cuda.get_device_properties(0).multi_processor_count // 8 * 8
     tiles_per_part = -(-(-(-n // 16)) // 8)
-    rows_per_wavefront = 16 * -(-tiles_per_part // (cus // 8 * 4))
+    rows_per_wavefront = 16 * -(-tiles_per_part // (cus // 8 * (4 if F == 64 else 8)))
     tol_n, tol_s = wgrad_tolerance(Sn, Ss, np.abs(dZ.astype(np.float64)).sum(axis=0), rows_per_wavefront, pieces)
     assert np.isfinite(got).all()
     en, es = np.abs(got[0] - dWn), np.abs(got[1] - dWs)
