@@ -263,3 +263,77 @@ def _aggregate(torch, Z, plan, plan_t):
             return dX
 
     return Aggregate.apply(Z)
+
+
+def test_training_step_through_the_three_fused_calls_matches_autograd():
+    """One training step of the three-layer classifier with every layer run by the fused calls (forward layer,
+    input gradient, weight gradients; the bias gradient is a column sum) gives the gradients that autograd gives
+    for the same parameters through the library's aggregation and transposed aggregation, and a few steps of
+    Adam on them train the model.  The 4 input features are padded with zero columns to the narrowest width, 32."""
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need a GPU"
+    torch.cuda.set_device(0)
+    aig = wl.csa_multiplier_aig(12)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 1)
+    plan, plan_t, _gt = _plans(g, HIDDEN)
+    n = aig.num_nodes
+    X4 = torch.from_numpy(wl.paper_node_features(aig)).cuda()
+    X = torch.cat([X4, torch.zeros((n, HIDDEN - X4.shape[1]), device="cuda")], dim=1).contiguous()
+    y = torch.from_numpy(aig.label.astype(np.int64)).cuda()
+    workspace = torch.empty((G.groot_sage_layer_backward_weights_workspace(plan, HIDDEN) // 4,), device="cuda")
+
+    class FusedLayer(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, h, wn, ws, b):
+            h, wn, ws, b = (t.contiguous() for t in (h, wn, ws, b))
+            out = torch.empty((n, HIDDEN), device="cuda")
+            G.groot_sage_layer_forward(plan, h, wn, ws, b, True, out, HIDDEN)
+            ctx.save_for_backward(h, wn, ws, out)
+            return out
+
+        @staticmethod
+        def backward(ctx, d_out):
+            h, wn, ws, out = ctx.saved_tensors
+            dZ = (d_out * (out > 0)).contiguous()
+            scaled = torch.empty_like(dZ)
+            G.groot_rows_over_degree(plan, dZ, scaled)
+            dh = torch.empty_like(h)
+            G.groot_sage_layer_backward_data(plan, scaled, wn.t().contiguous(), ws.t().contiguous(), dh)
+            dW = torch.empty((2, HIDDEN, HIDDEN), device="cuda")
+            G.groot_sage_layer_backward_weights(plan, h, dZ, dW[0], dW[1], workspace)
+            return dh, dW[0], dW[1], dZ.sum(0)
+
+    def parameters(seed):
+        gen = torch.Generator().manual_seed(seed)
+        mk = lambda *shape: ((torch.rand(shape, generator=gen) - 0.5) * 0.5).cuda().requires_grad_(True)
+        return [dict(wn=mk(HIDDEN, HIDDEN), ws=mk(HIDDEN, HIDDEN), b=mk(HIDDEN)) for _ in range(3)] + [dict(w=mk(HIDDEN, CLASSES), b=mk(CLASSES))]
+
+    def loss_of(params, fused, x):
+        h = x
+        for layer in params[:3]:
+            if fused:
+                h = FusedLayer.apply(h, layer["wn"], layer["ws"], layer["b"])
+            else:
+                h = torch.relu(_aggregate(torch, h, plan, plan_t) @ layer["wn"] + h @ layer["ws"] + layer["b"])
+        return torch.nn.functional.cross_entropy(h @ params[3]["w"] + params[3]["b"], y)
+
+    params = parameters(11)
+    flat = [t for layer in params for t in layer.values()]
+    xa, xb = X.clone().requires_grad_(True), X.clone().requires_grad_(True)
+    want = torch.autograd.grad(loss_of(params, False, xa), flat + [xa])
+    got = torch.autograd.grad(loss_of(params, True, xb), flat + [xb])
+    for a, b in zip(want, got):
+        assert float((a - b).abs().max()) <= 2e-5 * float(a.abs().max()) + 1e-9
+
+    opt = torch.optim.Adam(flat, lr=1e-2)
+    first = last = None
+    for step in range(60):
+        opt.zero_grad()
+        loss = loss_of(params, True, X)
+        loss.backward()
+        opt.step()
+        first = float(loss.detach()) if first is None else first
+        last = float(loss.detach())
+    print(f"fused training loss {first:.4f} -> {last:.4f}", flush=True)
+    assert np.isfinite(last) and last < 0.5 * first
