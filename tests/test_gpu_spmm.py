@@ -562,6 +562,52 @@ def test_fused_sage_layer_backward_weights_other_graphs_and_errors(torch_cuda):
         G.groot_sage_layer_backward_weights(plan_t, z(n, 64), z(n, 64), z(64, 64), z(64, 64), z(need // 4), 64)
 
 
+def test_calls_that_only_enqueue_run_under_graph_capture(torch_cuda):
+    """groot_spmm_execute, the fused layer, its input gradient (with groot_rows_over_degree) and its weight
+    gradients only enqueue kernels and allocate nothing, so a caller may capture them into a graph: the captured
+    sequence is replayed three times on fresh inputs, with eager work and synchronisation between the replays, and
+    every replay gives bit for bit what the same calls give eagerly."""
+    torch = torch_cuda
+    aig, g, _ = _aig_case(48, 2)
+    n, F = 2 * aig.num_nodes, 64
+    plan = G.groot_spmm_plan(g, 32)
+    G.groot_plan_upload(plan, F)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    rnd = lambda *shape: torch.rand(shape, generator=gen, device="cuda") - 0.5
+    Wn, Ws, b = rnd(F, F) * 0.25, rnd(F, F) * 0.25, rnd(F) * 0.25
+    WnT, WsT = Wn.t().contiguous(), Ws.t().contiguous()
+    workspace = torch.empty((G.groot_sage_layer_backward_weights_workspace(plan, F) // 4,), device="cuda")
+    X, dZ = rnd(n, F), rnd(n, F)
+
+    def calls(out):
+        G.groot_spmm_execute(plan, X, out["Y"], F)
+        G.groot_sage_layer_forward(plan, X, Wn, Ws, b, True, out["H"], F)
+        G.groot_rows_over_degree(plan, dZ, out["scaled"])
+        G.groot_sage_layer_backward_data(plan, out["scaled"], WnT, WsT, out["dX"])
+        G.groot_sage_layer_backward_weights(plan, X, dZ, out["dW"][0], out["dW"][1], workspace)
+
+    buffers = lambda: dict(Y=torch.empty((n, F), device="cuda"), H=torch.empty((n, F), device="cuda"),
+                           scaled=torch.empty((n, F), device="cuda"), dX=torch.empty((n, F), device="cuda"),
+                           dW=torch.empty((2, F, F), device="cuda"))
+    eager, captured = buffers(), buffers()
+    calls(eager)                                             # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls(captured)
+    for replay in range(3):
+        X.copy_(rnd(n, F))                                   # eager work between the replays
+        dZ.copy_(rnd(n, F) * (rnd(n, F) > 0))
+        for t in captured.values():
+            t.fill_(float("nan"))
+        calls(eager)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in eager:
+            assert torch.equal(eager[name], captured[name]), f"replay {replay}: {name}"
+
+
 def test_fused_sage_layer_wide_dynamic_range(torch_cuda, sage_variant):
     """Feature rows scaled by powers of two from 2^-60 to 2^60 (each copy of the multiplier its own scale, so
     that neighbours share it): the bf16 pieces have the exponent range of fp32, so the error stays relative
