@@ -282,22 +282,24 @@ groot_status groot_rows_over_degree(const groot_plan *plan, const float *Z_dev, 
  * wavefront sweeps (N / 1024 of them on an MI355X), fp64 across wavefronts, in
  * a fixed order: the same bits on every run.  The bias gradient is the column
  * sum of dZ and is left to the caller.
- * X_dev, dZ_dev (device): row-major [N, F] fp32, F = 32 or 64 (a narrower
- * layer: pad with zero columns); dWn_dev, dWs_dev (device): row-major [F, F]
- * fp32, fully overwritten; workspace_dev (device, 16-byte aligned): at least
- * the number of bytes that groot_sage_layer_backward_weights_workspace reports
- * for F (2 F^2 floats per wavefront of the launch: 32 MiB at F = 64 on an
- * MI355X), contents overwritten, owned by the caller.  The plan must be
- * uploaded with max_F >= F and have row-uniform weights.  Only enqueues on
+ * X_dev (device): row-major [N, F_in] fp32, F_in = 32 or 64; dZ_dev (device):
+ * row-major [N, F_out] fp32, F_out = 16, 32 or 64 (other widths: pad with zero
+ * columns); dWn_dev, dWs_dev (device): row-major [F_in, F_out] fp32, fully
+ * overwritten; workspace_dev (device, 16-byte aligned): at least the number of
+ * bytes that groot_sage_layer_backward_weights_workspace reports for these
+ * widths (2 F_in F_out floats per wavefront of the launch: 32 MiB at 64 x 64
+ * on an MI355X), contents overwritten, owned by the caller.  The plan must be
+ * uploaded with max_F >= F_in and have row-uniform weights.  Only enqueues on
  * hip_stream, allocates nothing; one call per plan in flight (the aggregated
  * high-degree rows pass through a buffer of the plan).  Errors: EINVAL (NULL,
- * alignment, F, plan not uploaded, explicit weights, workspace too small),
- * EHIP.
+ * alignment, widths, plan not uploaded, explicit weights, workspace too
+ * small), EHIP.
  * ------------------------------------------------------------------------- */
-groot_status groot_sage_layer_backward_weights_workspace(const groot_plan *plan, int32_t F, size_t *bytes);
+groot_status groot_sage_layer_backward_weights_workspace(const groot_plan *plan, int32_t F_in, int32_t F_out,
+                                                         size_t *bytes);
 groot_status groot_sage_layer_backward_weights(const groot_plan *plan, const float *X_dev, const float *dZ_dev,
-                                               float *dWn_dev, float *dWs_dev, int32_t F, void *workspace_dev,
-                                               size_t workspace_bytes, void *hip_stream);
+                                               float *dWn_dev, float *dWs_dev, int32_t F_in, int32_t F_out,
+                                               void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 void groot_plan_free(groot_plan *plan);
 
 /* ---------------------------------------------------------------------------

@@ -66,8 +66,8 @@ _lib.groot_sage_layer_forward.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i
 _lib.groot_sage_layer_forward_io.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp]
 _lib.groot_sage_layer_backward_data.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp]
 _lib.groot_rows_over_degree.argtypes = [_vp, _vp, _vp, _i32, _vp]
-_lib.groot_sage_layer_backward_weights_workspace.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_size_t)]
-_lib.groot_sage_layer_backward_weights.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _vp, ctypes.c_size_t, _vp]
+_lib.groot_sage_layer_backward_weights_workspace.argtypes = [_vp, _i32, _i32, ctypes.POINTER(ctypes.c_size_t)]
+_lib.groot_sage_layer_backward_weights.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, ctypes.c_size_t, _vp]
 _lib.groot_plan_lists_device.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_lists_device_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.groot_plan_query.argtypes = [_vp, ctypes.c_char_p, _pi64]
@@ -365,23 +365,25 @@ def groot_sage_layer_backward_data(pl: Plan, dZ_over_deg, WnT, WsT, dX, F_out: i
                                                _features(dX, "dX", n, F_in), F_out, F_in, _stream_handle(stream)))
 
 
-def groot_sage_layer_backward_weights_workspace(pl: Plan, F: int) -> int:
-    """Bytes of device workspace that groot_sage_layer_backward_weights needs for width F."""
+def groot_sage_layer_backward_weights_workspace(pl: Plan, F_in: int, F_out: int = None) -> int:
+    """Bytes of device workspace that groot_sage_layer_backward_weights needs for X of width F_in and dZ of width
+    F_out (default: F_in)."""
     b = ctypes.c_size_t(0)
-    _check(_lib.groot_sage_layer_backward_weights_workspace(pl.handle, F, ctypes.byref(b)))
+    _check(_lib.groot_sage_layer_backward_weights_workspace(pl.handle, F_in, F_in if F_out is None else F_out,
+                                                            ctypes.byref(b)))
     return b.value
 
 
-def groot_sage_layer_backward_weights(pl: Plan, X, dZ, dWn, dWs, workspace, F: int = None, stream=None) -> None:
-    """X and dZ [N, F], dWn and dWs [F, F] (overwritten); workspace: a contiguous device tensor of at least
-    groot_sage_layer_backward_weights_workspace(pl, F) bytes."""
-    F = X.shape[1] if F is None else F
+def groot_sage_layer_backward_weights(pl: Plan, X, dZ, dWn, dWs, workspace, F_in: int = None, F_out: int = None,
+                                      stream=None) -> None:
+    """X [N, F_in], dZ [N, F_out], dWn and dWs [F_in, F_out] (overwritten); workspace: a contiguous device tensor of
+    at least groot_sage_layer_backward_weights_workspace(pl, F_in, F_out) bytes."""
+    F_in = X.shape[1] if F_in is None else F_in
+    F_out = dZ.shape[1] if F_out is None else F_out
     n = _plan_rows(pl)
-    if not workspace.is_contiguous():
-        raise ValueError("workspace must be contiguous")
-    _check(_lib.groot_sage_layer_backward_weights(pl.handle, _features(X, "X", n, F), _features(dZ, "dZ", n, F),
-                                                  _features(dWn, "dWn", F, F), _features(dWs, "dWs", F, F), F,
-                                                  _dev_ptr(workspace, "workspace"),
+    _check(_lib.groot_sage_layer_backward_weights(pl.handle, _features(X, "X", n, F_in), _features(dZ, "dZ", n, F_out),
+                                                  _features(dWn, "dWn", F_in, F_out), _features(dWs, "dWs", F_in, F_out),
+                                                  F_in, F_out, _dev_ptr(workspace, "workspace"),
                                                   workspace.numel() * workspace.element_size(), _stream_handle(stream)))
 
 

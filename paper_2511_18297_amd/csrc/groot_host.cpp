@@ -829,25 +829,33 @@ extern "C" groot_status groot_sage_layer_backward_data(const groot_plan *plan, c
     return GROOT_OK;
 }
 
-extern "C" groot_status groot_sage_layer_backward_weights_workspace(const groot_plan *plan, int32_t F, size_t *bytes)
+namespace {
+bool wgrad_widths_ok(int32_t F_in, int32_t F_out)
+{
+    return (F_in == 64 || F_in == 32) && (F_out == 64 || F_out == 32 || F_out == 16);
+}
+}  // namespace
+
+extern "C" groot_status groot_sage_layer_backward_weights_workspace(const groot_plan *plan, int32_t F_in, int32_t F_out,
+                                                                    size_t *bytes)
 {
     const char *who = "groot_sage_layer_backward_weights_workspace: ";
     if (!plan || !bytes) return fail(GROOT_EINVAL, std::string(who) + "NULL argument");
-    if (F != 64 && F != 32) return fail(GROOT_EINVAL, std::string(who) + "F must be 32 or 64");
-    const size_t b = sage_wgrad_workspace_bytes(F);
+    if (!wgrad_widths_ok(F_in, F_out)) return fail(GROOT_EINVAL, std::string(who) + "F_in must be 32 or 64, F_out 16, 32 or 64");
+    const size_t b = sage_wgrad_workspace_bytes(F_in, F_out);
     if (b == 0) return fail(GROOT_EHIP, std::string(who) + "no device");
     *bytes = b;
     return GROOT_OK;
 }
 
 extern "C" groot_status groot_sage_layer_backward_weights(const groot_plan *plan, const float *X_dev, const float *dZ_dev,
-                                                          float *dWn_dev, float *dWs_dev, int32_t F, void *workspace_dev,
-                                                          size_t workspace_bytes, void *hip_stream)
+                                                          float *dWn_dev, float *dWs_dev, int32_t F_in, int32_t F_out,
+                                                          void *workspace_dev, size_t workspace_bytes, void *hip_stream)
 {
     const char *who = "groot_sage_layer_backward_weights: ";
     if (!plan) return fail(GROOT_EINVAL, std::string(who) + "NULL plan");
-    if (F != 64 && F != 32) return fail(GROOT_EINVAL, std::string(who) + "F must be 32 or 64");
-    groot_status st = check_features("groot_sage_layer_backward_weights", X_dev, dZ_dev, F);
+    if (!wgrad_widths_ok(F_in, F_out)) return fail(GROOT_EINVAL, std::string(who) + "F_in must be 32 or 64, F_out 16, 32 or 64");
+    groot_status st = check_features("groot_sage_layer_backward_weights", X_dev, dZ_dev, F_in);
     if (st != GROOT_OK) return st;
     if (!dWn_dev || !dWs_dev || !workspace_dev) return fail(GROOT_EINVAL, std::string(who) + "NULL output or workspace pointer");
     if ((((uintptr_t)dWn_dev) | ((uintptr_t)dWs_dev) | ((uintptr_t)workspace_dev)) & 15)
@@ -855,10 +863,10 @@ extern "C" groot_status groot_sage_layer_backward_weights(const groot_plan *plan
     if (!plan->resident) return fail(GROOT_EINVAL, std::string(who) + "plan is not on the device (call groot_plan_upload)");
     if (plan->dev.weight_mode == (int)WeightMode::Explicit)
         return fail(GROOT_EINVAL, std::string(who) + "needs row-uniform weights (a graph built from an AIG, or one whose weights are 1 / row length)");
-    if (F > plan->max_F) return fail(GROOT_EINVAL, std::string(who) + "F exceeds the max_F given to groot_plan_upload");
+    if (F_in > plan->max_F) return fail(GROOT_EINVAL, std::string(who) + "F_in exceeds the max_F given to groot_plan_upload");
     if (plan->dev.n_cols != plan->dev.n)
         return fail(GROOT_EINVAL, std::string(who) + "the plan's columns were renamed to global rows (groot_plan_use_global_columns)");
-    const size_t need = sage_wgrad_workspace_bytes(F);
+    const size_t need = sage_wgrad_workspace_bytes(F_in, F_out);
     if (need == 0) return fail(GROOT_EHIP, std::string(who) + "no device");
     if (workspace_bytes < need)
         return fail(GROOT_EINVAL, std::string(who) + "workspace too small (ask groot_sage_layer_backward_weights_workspace)");
@@ -867,9 +875,9 @@ extern "C" groot_status groot_sage_layer_backward_weights(const groot_plan *plan
     hd.chunks = plan->dev.chunks_rank;
     hd.split_rows = plan->dev.split_rows_rank;
     int err = 0;
-    if (hd.n_chunks) err = launch_hd(hd, X_dev, hd.hd_agg, F, hip_stream);
-    if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F, hip_stream);
-    if (!err) err = launch_sage_wgrad(plan->dev, X_dev, dZ_dev, dWn_dev, dWs_dev, F, tuning().sage_pieces.load(),
+    if (hd.n_chunks) err = launch_hd(hd, X_dev, hd.hd_agg, F_in, hip_stream);
+    if (!err && hd.n_split_rows) err = launch_hd_finish(hd, hd.hd_agg, F_in, hip_stream);
+    if (!err) err = launch_sage_wgrad(plan->dev, X_dev, dZ_dev, dWn_dev, dWs_dev, F_in, F_out, tuning().sage_pieces.load(),
                                       workspace_dev, hip_stream);
     if (err) return fail(GROOT_EHIP, std::string(who) + "launch failed: " + hip_error_text(err));
     return GROOT_OK;

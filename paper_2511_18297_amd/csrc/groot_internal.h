@@ -124,11 +124,11 @@ int launch_sage_pipe(const DevicePlan &dp, const float *X, float *H, const float
                      int relu, int32_t F_in, int32_t F_out, int pieces, int self_times_degree,
                      void *stream);   // F_in 32 / 64, F_out 16 / 32 / 64, row-uniform weights; pieces 3 (fp32 accuracy) or 2;
                                       // self_times_degree: unit weights and the own-row operand times the row length (input gradient)
-// Weight gradients of the fused layer (groot_sage_wgrad.hip): dWn = (A_hat X)^T dZ, dWs = X^T dZ, F = 32 or 64,
-// row-uniform weights; workspace of sage_wgrad_workspace_bytes(F) bytes (0: no device).
-size_t sage_wgrad_workspace_bytes(int32_t F);
-int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, float *dWn, float *dWs, int32_t F, int pieces,
-                      void *workspace, void *stream);
+// Weight gradients of the fused layer (groot_sage_wgrad.hip): dWn = (A_hat X)^T dZ, dWs = X^T dZ, X of width F_in = 32
+// or 64, dZ of width F_out = 16, 32 or 64, row-uniform weights; workspace of sage_wgrad_workspace_bytes bytes (0: no device).
+size_t sage_wgrad_workspace_bytes(int32_t F_in, int32_t F_out);
+int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, float *dWn, float *dWs, int32_t F_in,
+                      int32_t F_out, int pieces, void *workspace, void *stream);
 int launch_rows_over_degree(const DevicePlan &dp, const float *Z, float *out, int32_t F, void *stream);   // out may be Z
 // Schedule of the high-degree rows built on the device (groot_hd_sched_device.hip): the pieces in execution order,
 // once with rows named by id and once by their place in the list of high-degree rows, and the split rows likewise.

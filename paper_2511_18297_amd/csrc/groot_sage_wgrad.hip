@@ -1,5 +1,6 @@
 // Weight gradients of the fused GraphSAGE-mean layer for gfx950:
-//     dWn = (A_hat X)^T dZ,   dWs = X^T dZ,   X and dZ [N, F], dWn and dWs [F, F], F = 32 or 64,
+//     dWn = (A_hat X)^T dZ,   dWs = X^T dZ,   X [N, FI], dZ [N, FO], dWn and dWs [FI, FO], FI = 32 or 64, FO = 16, 32 or 64
+//     (described below for FI = FO = F = 64),
 // for the layer Z = (A_hat X) Wn + X Ws + b with dZ the gradient of the loss at Z (Section "GNN and Edge
 // Re-growth After Partition": the model is trained).  Two products with N as the contraction length: as plain
 // matrix products over [N, 64] operands they take 58 ms each on 134 M rows with the vendor library, and the
@@ -32,7 +33,7 @@ namespace groot {
 constexpr int kWgRows = 16;                  // rows per tile: the contraction length of one matrix instruction
 // wavefronts per workgroup (one workgroup per CU): one per SIMD at F = 64, where the accumulators alone take 128
 // registers; two per SIMD at F = 32 (32 accumulator registers), so that one's vector work overlaps the other's matrix work
-constexpr int wg_waves(int F) { return F == 64 ? 4 : 8; }
+constexpr int wg_waves(int FI) { return FI == 64 ? 4 : 8; }
 constexpr int kWgTRow = kWgRows * 2 + 8;     // bytes per column of a transposed bf16 plane (8 B of padding)
 
 typedef float wg_f2 __attribute__((ext_vector_type(2)));
@@ -87,21 +88,27 @@ __device__ __forceinline__ void wg_park(char *planes, int c0, int g, const v4f (
     }
 }
 
-// W: kOnes or kMean; F: width of X and of dZ; D: gather slots per row on the pipelined path; P: bf16 pieces per operand
-template <int W, int F, int D, int P>
-__global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_per_eu(wg_waves(F) / 4, wg_waves(F) / 4))) void sage_wgrad_kernel(
+// W: kOnes or kMean; FI: width of X; FO: width of dZ; D: gather slots per row on the pipelined path; P: bf16 pieces per
+// operand.  The rows of dZ are loaded by the lane groups that load the rows of X (FI / 4 lanes per row): FO / FI float4
+// per lane, or one with the lanes past the row's end idle.
+template <int W, int FI, int FO, int D, int P>
+__global__ __launch_bounds__(wg_waves(FI) * kWave) __attribute__((amdgpu_waves_per_eu(wg_waves(FI) / 4, wg_waves(FI) / 4))) void sage_wgrad_kernel(
     const int64_t *__restrict__ rowptr, const int32_t *__restrict__ col, const float *__restrict__ val,
     const char *__restrict__ X, const char *__restrict__ dZ, int64_t zero_off, int64_t n, int32_t T, int64_t n_tiles,
     int64_t tiles_per_part, int64_t waves_per_part, int32_t parts, const int32_t *__restrict__ hd_rows, int32_t n_hd,
     const char *__restrict__ hd_agg, float *__restrict__ partials)
 {
-    static_assert(F == 64 || F == 32, "width");
+    static_assert(FI == 64 || FI == 32, "width of X");
+    static_assert(FO == 64 || FO == 32 || FO == 16, "width of dZ");
     static_assert(P == 3 || P == 2, "pieces per operand");
     static_assert(W == kOnes || W == kMean, "row-uniform weights");
-    constexpr int kWgWaves = wg_waves(F);
+    constexpr int F = FI;
+    constexpr int kWgWaves = wg_waves(FI);
     constexpr int kL = F / 4, kRpg = kWave / kL, kG = kWgRows / kRpg, kRowShift = F == 64 ? 8 : 7;
-    constexpr int kM = 2 * F, kMb = kM / 16, kNb = F / 16;
-    constexpr int kPlaneA = kM * kWgTRow, kPlaneB = F * kWgTRow;
+    constexpr int kZShift = FO == 64 ? 8 : FO == 32 ? 7 : 6;             // log2 of a row of dZ in bytes
+    constexpr int kZ = (FO / 4 + kL - 1) / kL;                           // float4 of a row of dZ per lane
+    constexpr int kM = 2 * F, kMb = kM / 16, kNb = FO / 16;
+    constexpr int kPlaneA = kM * kWgTRow, kPlaneB = FO * kWgTRow;
     constexpr int kSlots = kWgRows * D, kH = (kSlots + kWave - 1) / kWave;
     __shared__ __align__(16) int64_t s_slot[kWgWaves][kSlots];
     __shared__ float s_inv[kWgWaves][kWgRows];
@@ -115,7 +122,9 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
     const int64_t x_begin = part * tiles_per_part;
     const int64_t x_end = x_begin + tiles_per_part < n_tiles ? x_begin + tiles_per_part : n_tiles;
     const int64_t t_first = x_begin + j, stride = waves_per_part;
-    const char *Xf = X + 16 * f, *Zf = dZ + 16 * f;
+    const char *Xf = X + 16 * f;
+    const bool z_lane = 4 * f < FO;                      // kZ == 1: this lane holds four columns of dZ
+    const char *Zf = dZ + 16 * (z_lane ? f : 0);         // an idle lane reads the row's first columns and parks nothing
 
     v4f acc[kMb][kNb];
 #pragma unroll
@@ -165,7 +174,7 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
         };
         // ---- one sweep: kRpg rows, one per lane group: the row's D slots, its own features and its row of dZ
         struct Regs {
-            v4f xs[D], self, dz;
+            v4f xs[D], self, dz[kZ];
             float inv;
         };
         Regs rr[kG];
@@ -177,7 +186,8 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
 #pragma unroll
             for (int k = 0; k < D; ++k) q.xs[k] = *(const v4f *)(Xf + s_slot[w][lr * D + k]);
             q.self = *(const v4f *)(Xf + (row << kRowShift));
-            q.dz = *(const v4f *)(Zf + (row << kRowShift));
+#pragma unroll
+            for (int i = 0; i < kZ; ++i) q.dz[i] = *(const v4f *)(Zf + (row << kZShift) + 16 * kL * i);
         };
         auto sum = [&](const Regs &q) -> v4f {
             v4f a = {0.f, 0.f, 0.f, 0.f};
@@ -206,14 +216,15 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
             rp_b = load_rp(tile + 3 * stride);
             const int64_t base = tile * kWgRows;
             // this tile's values out of the register sets, which take the rows of the next tile
-            v4f av[kG], sv[kG], zv[kG];
+            v4f av[kG], sv[kG], zv[kZ][kG];
 #pragma unroll
             for (int grp = 0; grp < kG; ++grp) {
                 const bool in = base + grp * kRpg + g < n;
                 const v4f zero = {0.f, 0.f, 0.f, 0.f};
                 av[grp] = sum(rr[grp]);                  // a ragged tile has no live slot: zeros
                 sv[grp] = in ? rr[grp].self : zero;
-                zv[grp] = in ? rr[grp].dz : zero;
+#pragma unroll
+                for (int i = 0; i < kZ; ++i) zv[i][grp] = in ? rr[grp].dz[i] : zero;
                 issue(rr[grp], tile + stride, grp);
             }
             if (fix_cur) {
@@ -241,7 +252,10 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
             // transposed into LDS, cut into pieces: [A_hat X | X] and dZ
             wg_park<kG, P, kPlaneA>(a_t, 4 * f, g, av);
             wg_park<kG, P, kPlaneA>(a_t, F + 4 * f, g, sv);
-            wg_park<kG, P, kPlaneB>(b_t, 4 * f, g, zv);
+            if (z_lane) {
+#pragma unroll
+                for (int i = 0; i < kZ; ++i) wg_park<kG, P, kPlaneB>(b_t, 4 * (f + kL * i), g, zv[i]);
+            }
             wg_wave_sync();
             // ---- [A_hat X | X]^T (2F x 16) times dZ (16 x F): lane (jl, kq) reads column jl of a block, rows 4 kq .. 4 kq + 3
             wg_u2 bop[kNb][P];
@@ -272,27 +286,27 @@ __global__ __launch_bounds__(wg_waves(F) * kWave) __attribute__((amdgpu_waves_pe
     }
     // ---- this wavefront's sums to its slice of the workspace (zeros if it had no tile): lane holds rows
     //      16 mb + 4 kq + r of column 16 nb + jl
-    float *mine = partials + ((int64_t)blockIdx.x * kWgWaves + w) * (kM * F);
+    float *mine = partials + ((int64_t)blockIdx.x * kWgWaves + w) * (kM * FO);
 #pragma unroll
     for (int mb = 0; mb < kMb; ++mb)
 #pragma unroll
         for (int nb = 0; nb < kNb; ++nb)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) mine[(16 * mb + 4 * kq + r) * F + 16 * nb + jl] = acc[mb][nb][r];
+            for (int r = 0; r < 4; ++r) mine[(16 * mb + 4 * kq + r) * FO + 16 * nb + jl] = acc[mb][nb][r];
 }
 
-// dWn[m][n] (m < F) and dWs[m - F][n] = sum over the slices, in slice order, in fp64
+// dWn[m][n] (m < FI) and dWs[m - FI][n] = sum over the slices, in slice order, in fp64; half = FI * FO
 __global__ __launch_bounds__(kBlock) void sage_wgrad_reduce_kernel(const float *__restrict__ partials, int64_t slices,
-                                                                   int32_t F, float *__restrict__ dWn,
+                                                                   int32_t half, float *__restrict__ dWn,
                                                                    float *__restrict__ dWs)
 {
-    const int32_t e = blockIdx.x * kBlock + threadIdx.x, count = 2 * F * F;
+    const int32_t e = blockIdx.x * kBlock + threadIdx.x, count = 2 * half;
     if (e >= count) return;
     double s = 0.0;
 #pragma unroll 8
     for (int64_t k = 0; k < slices; ++k) s += (double)partials[k * count + e];
-    if (e < F * F) dWn[e] = (float)s;
-    else dWs[e - F * F] = (float)s;
+    if (e < half) dWn[e] = (float)s;
+    else dWs[e - half] = (float)s;
 }
 
 static int64_t wgrad_workgroups()
@@ -304,17 +318,18 @@ static int64_t wgrad_workgroups()
     return n_wg < kXcds ? kXcds : n_wg;
 }
 
-// bytes of workspace that launch_sage_wgrad needs for width F on the current device (0 on failure)
-size_t sage_wgrad_workspace_bytes(int32_t F)
+// bytes of workspace that launch_sage_wgrad needs for these widths on the current device (0 on failure)
+size_t sage_wgrad_workspace_bytes(int32_t FI, int32_t FO)
 {
     const int64_t n_wg = wgrad_workgroups();
-    return n_wg < 0 ? 0 : (size_t)n_wg * wg_waves(F) * 2 * (size_t)F * (size_t)F * sizeof(float);
+    return n_wg < 0 ? 0 : (size_t)n_wg * wg_waves(FI) * 2 * (size_t)FI * (size_t)FO * sizeof(float);
 }
 
-int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, float *dWn, float *dWs, int32_t F, int pieces,
-                      void *workspace, void *stream)
+int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, float *dWn, float *dWs, int32_t FI, int32_t FO,
+                      int pieces, void *workspace, void *stream)
 {
-    if (!weights_ok(dp) || !dp.zero_row || (F != 64 && F != 32) || (pieces != 2 && pieces != 3) || !workspace)
+    if (!weights_ok(dp) || !dp.zero_row || (FI != 64 && FI != 32) || (FO != 64 && FO != 32 && FO != 16) ||
+        (pieces != 2 && pieces != 3) || !workspace)
         return (int)hipErrorInvalidValue;
     if (dp.weight_mode == kExplicit) return (int)hipErrorInvalidValue;
     if (dp.n_hd_rows && (!dp.hd_rows || !dp.hd_agg)) return (int)hipErrorInvalidValue;
@@ -323,38 +338,43 @@ int launch_sage_wgrad(const DevicePlan &dp, const float *X, const float *dZ, flo
     const int64_t n_tiles = (dp.n + kWgRows - 1) / kWgRows;
     const int32_t parts = dp.xcd_remap ? kXcds : 1;
     const int64_t tiles_per_part = (n_tiles + parts - 1) / parts;
-    const int64_t waves_per_part = n_wg / parts * wg_waves(F);
+    const int64_t waves_per_part = n_wg / parts * wg_waves(FI);
     if (!grid_ok(n_wg) || n_tiles <= 0) return (int)hipErrorInvalidConfiguration;
     // the kernel reads entry 0 of the index array from idle lanes: give it something to read when the matrix has no entries
     const int32_t *col_arg = dp.col ? dp.col : (const int32_t *)dp.rowptr;
     const float *val_arg = dp.val ? dp.val : (const float *)dp.rowptr;
     hipStream_t st = (hipStream_t)stream;
-#define GROOT_WGRAD_LAUNCH(WM, FF, DD, PP)                                                                               \
-    sage_wgrad_kernel<WM, FF, DD, PP><<<dim3((unsigned)n_wg), dim3(wg_waves(FF) * kWave), 0, st>>>(                          \
+#define GROOT_WGRAD_LAUNCH(WM, FFI, FFO, DD, PP)                                                                         \
+    sage_wgrad_kernel<WM, FFI, FFO, DD, PP><<<dim3((unsigned)n_wg), dim3(wg_waves(FFI) * kWave), 0, st>>>(                 \
         dp.rowptr, col_arg, val_arg, (const char *)X, (const char *)dZ, byte_distance(X, dp.zero_row), dp.n, dp.threshold, \
         n_tiles, tiles_per_part, waves_per_part, parts, dp.hd_rows, (int32_t)dp.n_hd_rows, (const char *)dp.hd_agg,    \
         (float *)workspace)
-#define GROOT_WGRAD_P(WM, FF, DD)                        \
-    if (pieces == 2) GROOT_WGRAD_LAUNCH(WM, FF, DD, 2);  \
-    else GROOT_WGRAD_LAUNCH(WM, FF, DD, 3)
-#define GROOT_WGRAD_D(WM, FF)                                  \
-    if (dp.sage_depth == 5) { GROOT_WGRAD_P(WM, FF, 5); }      \
-    else { GROOT_WGRAD_P(WM, FF, 6); }
-    if (F == 64) {
-        if (dp.weight_mode == kMean) { GROOT_WGRAD_D(kMean, 64); }
-        else { GROOT_WGRAD_D(kOnes, 64); }
+#define GROOT_WGRAD_P(WM, FFI, FFO, DD)                        \
+    if (pieces == 2) GROOT_WGRAD_LAUNCH(WM, FFI, FFO, DD, 2);  \
+    else GROOT_WGRAD_LAUNCH(WM, FFI, FFO, DD, 3)
+#define GROOT_WGRAD_D(WM, FFI, FFO)                                  \
+    if (dp.sage_depth == 5) { GROOT_WGRAD_P(WM, FFI, FFO, 5); }      \
+    else { GROOT_WGRAD_P(WM, FFI, FFO, 6); }
+#define GROOT_WGRAD_FO(WM, FFI)                          \
+    if (FO == 64) { GROOT_WGRAD_D(WM, FFI, 64); }        \
+    else if (FO == 32) { GROOT_WGRAD_D(WM, FFI, 32); }   \
+    else { GROOT_WGRAD_D(WM, FFI, 16); }
+    if (FI == 64) {
+        if (dp.weight_mode == kMean) { GROOT_WGRAD_FO(kMean, 64); }
+        else { GROOT_WGRAD_FO(kOnes, 64); }
     } else {
-        if (dp.weight_mode == kMean) { GROOT_WGRAD_D(kMean, 32); }
-        else { GROOT_WGRAD_D(kOnes, 32); }
+        if (dp.weight_mode == kMean) { GROOT_WGRAD_FO(kMean, 32); }
+        else { GROOT_WGRAD_FO(kOnes, 32); }
     }
+#undef GROOT_WGRAD_FO
 #undef GROOT_WGRAD_D
 #undef GROOT_WGRAD_P
 #undef GROOT_WGRAD_LAUNCH
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return (int)err;
-    const int32_t count = 2 * F * F;
+    const int32_t count = 2 * FI * FO;
     sage_wgrad_reduce_kernel<<<dim3((unsigned)((count + kBlock - 1) / kBlock)), dim3(kBlock), 0, st>>>(
-        (const float *)workspace, n_wg * wg_waves(F), F, dWn, dWs);
+        (const float *)workspace, n_wg * wg_waves(FI), FI * FO, dWn, dWs);
     return (int)hipGetLastError();
 }
 

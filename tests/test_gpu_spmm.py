@@ -482,16 +482,18 @@ def test_fused_sage_layer_backward_data_errors(torch_cuda):
         G.groot_sage_layer_backward_data(plan, z(n, 64), z(32, 32), z(64, 32), z(n, 32))
 
 
-def _wgrad_check(torch, g, rowptr, col, val, T, n, seed, F, pieces=3):
+def _wgrad_check(torch, g, rowptr, col, val, T, n, seed, F, pieces=3, F_out=None):
+    """X of width F, dZ of width F_out (default F)."""
+    FO = F if F_out is None else F_out
     rng = np.random.default_rng(seed)
     X = wl.uniform_features_numpy(seed, 0, n, F)
-    dZ = (wl.uniform_features_numpy(seed + 1, 0, n, F) * (rng.random((n, F)) < 0.55)).astype(np.float32)
+    dZ = (wl.uniform_features_numpy(seed + 1, 0, n, FO) * (rng.random((n, FO)) < 0.55)).astype(np.float32)
     plan = G.groot_spmm_plan(g, T)
     G.groot_plan_upload(plan, F)
-    need = G.groot_sage_layer_backward_weights_workspace(plan, F)
+    need = G.groot_sage_layer_backward_weights_workspace(plan, F, FO)
     ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
     ws[need // 4:] = 777.0
-    out = torch.full((2, F, F), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((2, F, FO), float("nan"), dtype=torch.float32, device="cuda")
     dev = lambda a: torch.from_numpy(a).cuda()
     Xd, Zd = dev(X), dev(dZ)
     G.groot_sage_layer_backward_weights(plan, Xd, Zd, out[0], out[1], ws, F)
@@ -522,6 +524,14 @@ def test_fused_sage_layer_backward_weights(torch_cuda, F, n_bits, batch, T):
     twice, bit for bit the same; nothing written past the workspace."""
     aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
     _wgrad_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 800 + n_bits + F, F)
+
+
+@pytest.mark.parametrize("F_in,F_out", [(64, 32), (64, 16), (32, 64), (32, 16)])
+@pytest.mark.parametrize("n_bits,batch,T", [(48, 2, 32), (17, 3, 5), (3, 1, 32)])
+def test_fused_sage_layer_backward_weights_of_a_layer_that_narrows_or_widens(torch_cuda, F_in, F_out, n_bits, batch, T):
+    """X [N, F_in] and dZ [N, F_out] of different widths: the rows of dZ ride with the lane groups of X."""
+    aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
+    _wgrad_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 850 + n_bits + F_in + F_out, F_in, F_out=F_out)
 
 
 def test_fused_sage_layer_backward_weights_other_graphs_and_errors(torch_cuda):
