@@ -346,7 +346,7 @@ def place_features(G, torch, wl, plan, seed, n, F, tries, fixed=None):
     """Where the feature matrices lie in device memory changes the step time by up to 10 % on this machine, the same
     kernels on the same data: slowest when X and Y lie in address ranges of the same one of two classes that
     alternate every 64 GiB or so (the first two allocations of a process), fastest when each of them straddles a
-    boundary between the classes (measurement section).  The library has a call that finds a good place
+    boundary between the classes.  The library has a call that finds a good place
     by measuring, `groot_feature_placement`; a caller that reuses its feature buffers over many layers and epochs
     makes it once.  Here, before any feature matrix exists: one arena of `tries` + 3 matrix sizes is allocated, the
     call picks the offsets of X and Y in it, and the features are generated into the X it picked.  With `tries` = 0

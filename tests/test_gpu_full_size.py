@@ -339,8 +339,8 @@ def test_config4_batch16_full_graph_and_partitioned_mode(torch_cuda, one_copy):
 
 
 def _progress(msg):
-    """A line on stdout and, because pytest holds stdout back until the test ends, in a file under gpurun_out/
-    so that a long test is seen to be alive."""
+    """A line on stdout and, because pytest holds stdout back until the test ends, in a file of the run's output
+    folder, so that a long test is seen to be alive."""
     print(msg, flush=True)
     try:
         root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
