@@ -256,7 +256,7 @@ groot_status groot_sage_layer_forward_io(const groot_plan *plan, const float *X_
  * of dZ), F_in = 16, 32 or 64.  Accuracy, the "sage_pieces" knob, the plan's
  * side buffer (one call per plan in flight) and the stream: as for
  * groot_sage_layer_forward.  The gradients of the weights (X^T and (A_hat X)^T
- * times dZ) are dense products over all rows and are left to the caller.
+ * times dZ): groot_sage_layer_backward_weights below.
  * Errors: EINVAL (NULL, alignment, widths, plan not uploaded or made on the
  * device, graph not built symmetric with mean weights, overlap), EHIP.
  *
