@@ -419,10 +419,11 @@ def test_fused_sage_layer_backward_data(torch_cuda, F_out, F_in, n_bits, batch, 
     dZ / deg, own row scaled back by its length) against the fp64 definition: every pair of widths, high-degree
     rows (summed by the HD kernel with unit weights), every row high-degree, a ragged last tile.  About half of
     dZ is zero, as behind a ReLU.  groot_rows_over_degree is the division it claims to be, bit for bit."""
-    torch = torch_cuda
     aig, g, (rowptr, col, val, pol) = _aig_case(n_bits, batch)
-    n = batch * aig.num_nodes
-    seed = 700 + n_bits + F_out + F_in
+    _backward_data_check(torch_cuda, g, rowptr, col, val, T, batch * aig.num_nodes, 700 + n_bits + F_out + F_in, F_out, F_in)
+
+
+def _backward_data_check(torch, g, rowptr, col, val, T, n, seed, F_out, F_in):
     rng = np.random.default_rng(seed)
     dZ = (wl.uniform_features_numpy(seed, 0, n, F_out) * (rng.random((n, F_out)) < 0.55)).astype(np.float32)
     Wn, Ws = (rng.uniform(-0.125, 0.125, (F_in, F_out)).astype(np.float32) for _ in range(2))
@@ -451,6 +452,19 @@ def test_fused_sage_layer_backward_data(torch_cuda, F_out, F_in, n_bits, batch, 
     err = np.abs(out[guard:n + guard].astype(np.float64) - want)
     assert np.isfinite(err).all()
     assert (err <= tol).all(), f"max err/tol {np.max(err / tol)}"
+
+
+def test_fused_sage_layer_gradients_on_the_booth_shape(torch_cuda):
+    """High-degree rows scattered through the graph and rows of up to 8 entries (the Booth recoding signals): the
+    gradient kernels' plain path for the tiles that hold them, input gradient and weight gradients."""
+    aig = wl.booth_multiplier_aig(32)
+    g = G.groot_graph_build(aig.type, aig.fanin0, aig.fanin1, 2)
+    rowptr, col, val, _ = oracle.csr_build(aig.type, aig.fanin0, aig.fanin1, 2)
+    n = 2 * aig.num_nodes
+    _backward_data_check(torch_cuda, g, rowptr, col, val, 16, n, 71, 64, 32)
+    _backward_data_check(torch_cuda, g, rowptr, col, val, 16, n, 72, 32, 32)
+    _wgrad_check(torch_cuda, g, rowptr, col, val, 16, n, 73, 64)
+    _wgrad_check(torch_cuda, g, rowptr, col, val, 16, n, 74, 32, F_out=16)
 
 
 def test_fused_sage_layer_backward_data_errors(torch_cuda):
